@@ -1,0 +1,108 @@
+"""Seeded synthetic inputs for the scan workloads.
+
+This module only draws random numbers and lays them out; it holds none of the
+scan's arithmetic, and it is the only code shared by the CPU oracle's tests and
+the GPU tests / benchmark.
+
+Recipe (identical for every consumer): ``numpy.random.default_rng(seed)``,
+drawn in fixed chunks of CHUNK = 2**24 elements in index order, so the sequence
+for a given (workload, n) never depends on who asks or how it is consumed.
+
+Workloads (they stand in for the paper's unstated Float32/Float64 arrays of
+1e6..1e9 elements, Sec. VII; the paper uses no public data set):
+
+  int32_sum    inclusive sum,  int32,   uniform integers in [-100, 100],  seed 0
+  f32_sum      inclusive sum,  float32, uniform [0, 1),                   seed 1
+  u64_exsum    exclusive sum,  uint64,  uniform integers in [0, 2**32),   seed 2
+  affine       inclusive affine-map composition, (a, b) float32 pairs,
+               a uniform [0.99, 1.01], b uniform [-1, 1],                 seed 3
+  argmax       inclusive running arg-max with count, 16-byte struct
+               {int32 v, int32 idx, int64 cnt}: v uniform in [0, 2**20),
+               idx = position, cnt = 1,                                    seed 4
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Iterator
+
+import numpy as np
+
+CHUNK = 1 << 24
+
+ARGMAX_DTYPE = np.dtype([("v", "<i4"), ("idx", "<i4"), ("cnt", "<i8")])
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str          # library dtype name
+    op: str             # library operator name
+    inclusive: bool
+    n: int              # size the headline configuration is quoted on
+    seed: int
+    elem_bytes: int
+
+
+WORKLOADS = {
+    "int32_sum": Workload("int32_sum", "i32", "sum", True, 1 << 20, 0, 4),
+    "f32_sum": Workload("f32_sum", "f32", "sum", True, 1 << 28, 1, 4),
+    "u64_exsum": Workload("u64_exsum", "u64", "sum", False, 1 << 27, 2, 8),
+    "affine": Workload("affine", "affine_f32", "affine_compose", True, 1 << 26, 3, 8),
+    "argmax": Workload("argmax", "argmax_i32_cnt64", "argmax_count", True, 1 << 30, 4, 16),
+}
+
+ARGMAX_SWEEP = [1 << k for k in range(10, 31, 2)]   # 2^10 .. 2^30 in powers of 4
+
+
+def _draw(name: str, rng: np.random.Generator, start: int, m: int) -> np.ndarray:
+    if name == "int32_sum":
+        return rng.integers(-100, 101, size=m, dtype=np.int32)
+    if name == "f32_sum":
+        return rng.random(size=m, dtype=np.float32)
+    if name == "u64_exsum":
+        return rng.integers(0, 1 << 32, size=m, dtype=np.uint64)
+    if name == "affine":
+        out = np.empty((m, 2), dtype=np.float32)
+        out[:, 0] = rng.uniform(0.99, 1.01, size=m).astype(np.float32)
+        out[:, 1] = rng.uniform(-1.0, 1.0, size=m).astype(np.float32)
+        return out
+    if name == "argmax":
+        out = np.empty(m, dtype=ARGMAX_DTYPE)
+        out["v"] = rng.integers(0, 1 << 20, size=m, dtype=np.int32)
+        out["idx"] = np.arange(start, start + m, dtype=np.int64).astype(np.int32)
+        out["cnt"] = 1
+        return out
+    raise KeyError(name)
+
+
+def chunks(name: str, n: int | None = None, seed: int | None = None) -> Iterator[np.ndarray]:
+    """Yield the workload's input in order, CHUNK elements at a time."""
+    w = WORKLOADS[name]
+    n = w.n if n is None else int(n)
+    rng = np.random.default_rng(w.seed if seed is None else seed)
+    start = 0
+    while start < n:
+        m = min(CHUNK, n - start)
+        yield _draw(name, rng, start, m)
+        start += m
+
+
+def whole(name: str, n: int | None = None, seed: int | None = None) -> np.ndarray:
+    """The whole input as one array (use only when it fits host memory)."""
+    parts = list(chunks(name, n, seed))
+    if not parts:
+        w = WORKLOADS[name]
+        return _draw(name, np.random.default_rng(w.seed), 0, 0)
+    return parts[0] if len(parts) == 1 else np.concatenate(parts)
+
+
+def random_mat2(n: int, seed: int) -> np.ndarray:
+    """n random 2x2 uint32 matrices, row-major (n, 4): an exact non-commutative test type."""
+    return np.random.default_rng(seed).integers(0, 1 << 32, size=(n, 4), dtype=np.uint32)
+
+
+def random_unit_quats(n: int, seed: int) -> np.ndarray:
+    """n unit quaternions (w, x, y, z) as float32 (n, 4)."""
+    q = np.random.default_rng(seed).normal(size=(n, 4))
+    q /= np.linalg.norm(q, axis=1, keepdims=True)
+    return q.astype(np.float32)

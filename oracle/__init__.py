@@ -1,0 +1,174 @@
+"""TEST INFRASTRUCTURE: sequential CPU oracle for the device-wide scan.
+
+Nothing in the product path may import this package.  It wraps the plain-C
+left fold in ``scan_oracle.c`` (built with gcc into ``liboracle_scan.so``) and
+adds a pure-Python fold over arbitrary Python objects for tiny cases.
+
+Definition followed (paper, Sec. II-C, scan; Sec. V-B first sentence):
+``out[i] = in[0] op ... op in[i]`` (inclusive) or ``in[0] op ... op in[i-1]``
+with ``out[0] = identity`` (exclusive), ``op`` associative and not necessarily
+commutative, the accumulated value always being the left operand.
+
+Every function here is pinned by tests/test_oracle_pins.py to closed forms,
+library special cases, exact per-prefix sums and brute force over every
+parenthesisation; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "scan_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_scan.so")
+
+ARGMAX_DTYPE = np.dtype([("v", "<i4"), ("idx", "<i4"), ("cnt", "<i8")])
+
+
+def build(force: bool = False) -> str:
+    """Compile scan_oracle.c with gcc (no HIP, no shared headers)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+             "-ffp-contract=off", _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+# name -> (C symbol, input numpy dtype, output numpy dtype, words per element in, out,
+#          accumulator ctype fields)
+_SCALAR_CTYPES = {
+    "i32": ctypes.c_int32, "u32": ctypes.c_uint32, "i64": ctypes.c_int64, "u64": ctypes.c_uint64,
+    "f32": ctypes.c_float, "f64": ctypes.c_double,
+}
+_NP = {"i32": np.int32, "u32": np.uint32, "i64": np.int64, "u64": np.uint64,
+       "f32": np.float32, "f64": np.float64}
+
+
+def _scalar_state(acc_ctype):
+    class State(ctypes.Structure):
+        _fields_ = [("acc", acc_ctype), ("started", ctypes.c_int)]
+    return State
+
+
+class _AffineState(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_double), ("b", ctypes.c_double), ("started", ctypes.c_int)]
+
+
+class _ArgmaxElem(ctypes.Structure):
+    _fields_ = [("v", ctypes.c_int32), ("idx", ctypes.c_int32), ("cnt", ctypes.c_int64)]
+
+
+class _ArgmaxState(ctypes.Structure):
+    _fields_ = [("acc", _ArgmaxElem), ("started", ctypes.c_int)]
+
+
+class _Mat2State(ctypes.Structure):
+    _fields_ = [("acc", ctypes.c_uint32 * 4), ("started", ctypes.c_int)]
+
+
+class _QuatState(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_double * 4), ("started", ctypes.c_int)]
+
+
+def _scalar_entry(op: str, dt: str):
+    """(symbol, in dtype, out dtype, state class) for a scalar (op, dtype) pair."""
+    if op == "sum":
+        acc = {"i32": ctypes.c_uint32, "u32": ctypes.c_uint32, "i64": ctypes.c_uint64,
+               "u64": ctypes.c_uint64, "f32": ctypes.c_double, "f64": ctypes.c_longdouble}[dt]
+        out = {"f32": np.float64}.get(dt, _NP[dt])
+    elif op in ("min", "max"):
+        acc = _SCALAR_CTYPES[dt]
+        out = _NP[dt]
+    else:
+        raise KeyError(op)
+    return f"oracle_{op}_{dt}", _NP[dt], out, _scalar_state(acc)
+
+
+class ScanStream:
+    """A scan fed in chunks; the running value is carried between feed() calls.
+
+    kind is one of: ("sum"|"min"|"max", "i32"|"u32"|"i64"|"u64"|"f32"|"f64"),
+    ("affine", "f32"), ("argmax", None), ("mat2", "u32"), ("quat", "f32").
+    Shapes: scalars (n,), affine (n, 2), quat (n, 4), mat2 (n, 4) uint32,
+    argmax (n,) of ARGMAX_DTYPE.
+    """
+
+    def __init__(self, op: str, dt: str | None, inclusive: bool = True):
+        self.op, self.dt, self.inclusive = op, dt, bool(inclusive)
+        lib = _load()
+        if op in ("sum", "min", "max"):
+            sym, self.in_dtype, self.out_dtype, state_cls = _scalar_entry(op, dt)
+            self.width = 1
+        elif op == "affine":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_affine_f32", np.float32, np.float64, _AffineState, 2
+        elif op == "argmax":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_argmax", ARGMAX_DTYPE, ARGMAX_DTYPE, _ArgmaxState, 1
+        elif op == "mat2":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_mat2_u32", np.uint32, np.uint32, _Mat2State, 4
+        elif op == "quat":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_quat_f32", np.float32, np.float64, _QuatState, 4
+        else:
+            raise KeyError(op)
+        self._fn = getattr(lib, sym)
+        self._fn.restype = None
+        self._fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                             ctypes.c_void_p]
+        self._state = state_cls()
+        ctypes.memset(ctypes.byref(self._state), 0, ctypes.sizeof(self._state))
+
+    def feed(self, chunk: np.ndarray) -> np.ndarray:
+        x = np.ascontiguousarray(chunk, dtype=self.in_dtype)
+        if self.width > 1:
+            assert x.ndim == 2 and x.shape[1] == self.width, x.shape
+        else:
+            assert x.ndim == 1, x.shape
+        n = x.shape[0]
+        out = np.empty(x.shape, dtype=self.out_dtype)
+        if n:
+            self._fn(x.ctypes.data, out.ctypes.data, n, int(self.inclusive),
+                     ctypes.addressof(self._state))
+        return out
+
+
+def scan(op: str, dt: str | None, x: np.ndarray, inclusive: bool = True) -> np.ndarray:
+    """One-shot sequential scan of a whole array (see ScanStream for kinds)."""
+    return ScanStream(op, dt, inclusive).feed(x)
+
+
+def fold_scan(op, xs, inclusive=True, identity=None):
+    """Pure-Python left fold over arbitrary objects: the definition itself.
+
+    ``op(earlier, later)``; exclusive needs ``identity``.  For tiny cases and
+    for operators the C file does not carry.
+    """
+    out = []
+    if inclusive:
+        acc = None
+        for i, x in enumerate(xs):
+            acc = x if i == 0 else op(acc, x)
+            out.append(acc)
+    else:
+        if identity is None:
+            raise ValueError("exclusive scan needs the operator's identity")
+        acc = identity
+        for x in xs:
+            out.append(acc)
+            acc = op(acc, x)
+    return out
