@@ -1,0 +1,151 @@
+/*
+ * ks_scan -- device-wide inclusive / exclusive scan for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Operation defined in the paper, Sec. II-C (parallel
+ * primitives: scan is dst[i] = src[0] op ... op src[i] for an associative, not
+ * necessarily commutative op) and Sec. V-B (inclusive or exclusive prefix
+ * reduction, single pass with decoupled look-back).  Every step of the path
+ * runs in the library's own HIP kernels; there is no CPU fallback.
+ *
+ * General conventions
+ *   - `in`, `out`, `temp` are DEVICE pointers owned by the caller.  `in` and
+ *     `out` hold n contiguous elements of the given dtype and must be aligned
+ *     to the element's alignment (4, 8 or 8/16 bytes, see ks_dtype); 16-byte
+ *     aligned pointers take the vectorised path, others a slower correct one.
+ *   - in == out (exactly in place) is allowed; any other overlap is rejected.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise (except ks_scan_check)
+ *     and never throw.  n == 0 returns KS_OK without a launch.
+ *   - Return value: KS_OK (0) or a negative ks_status.
+ *   - In an exclusive scan out[0] is the operator's identity; the accumulated
+ *     (earlier) value is always the left operand of op.
+ */
+#ifndef KS_SCAN_H
+#define KS_SCAN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KS_OK = 0,
+    KS_ERR_INVALID_ARG = -1, /* null pointer with n > 0, bad enum value                      */
+    KS_ERR_UNSUPPORTED = -2, /* (dtype, op) pair not instantiated                            */
+    KS_ERR_MISALIGNED = -3,  /* pointer not aligned to the element type                      */
+    KS_ERR_OVERLAP = -4,     /* in and out overlap without being identical                   */
+    KS_ERR_WORKSPACE = -5,   /* temp too small / misaligned, or internal allocation failed   */
+    KS_ERR_HIP = -6,         /* a HIP call failed; raw code via ks_last_hip_error()          */
+    KS_ERR_TIMEOUT = -7      /* a look-back wait hit its spin limit (see ks_scan_check)      */
+} ks_status;
+
+/* Element types.  Structs are plain little-endian C structs, naturally aligned. */
+typedef enum {
+    KS_I32 = 0,              /* int32_t                                              4 B */
+    KS_U32 = 1,              /* uint32_t                                             4 B */
+    KS_I64 = 2,              /* int64_t                                              8 B */
+    KS_U64 = 3,              /* uint64_t                                             8 B */
+    KS_F32 = 4,              /* float                                                4 B */
+    KS_F64 = 5,              /* double                                               8 B */
+    KS_AFFINE_F32 = 6,       /* struct { float a, b; }  the map x -> a*x + b         8 B */
+    KS_ARGMAX_I32_CNT64 = 7, /* struct { int32_t v; int32_t idx; int64_t cnt; }     16 B */
+    KS_MAT2_U32 = 8,         /* struct { uint32_t m00, m01, m10, m11; } row-major   16 B */
+    KS_QUAT_F32 = 9,         /* struct { float w, x, y, z; }                        16 B */
+    KS_DTYPE_COUNT = 10
+} ks_dtype;
+
+/* Operators; L is the accumulated (earlier) operand, R the later one. */
+typedef enum {
+    KS_SUM = 0,            /* L + R (integers wrap); identity 0.  All six scalar types           */
+    KS_MIN = 1,            /* min(L, R); identity = largest value (+inf).  Scalar types          */
+    KS_MAX = 2,            /* max(L, R); identity = smallest value (-inf). Scalar types          */
+    KS_AFFINE_COMPOSE = 3, /* apply L then R: (R.a*L.a, R.a*L.b + R.b); identity (1,0)           */
+    KS_ARGMAX_COUNT = 4,   /* larger v wins, equal v: lower idx wins; cnt adds (wraps);
+                              identity {INT32_MIN, INT32_MAX, 0}                                 */
+    KS_MAT2_MUL = 5,       /* 2x2 matrix product L*R, entries mod 2^32; identity I               */
+    KS_QUAT_MUL = 6,       /* Hamilton product L*R (paper Sec. V-B, non-commutative example);
+                              identity (1,0,0,0)                                                 */
+    KS_OP_COUNT = 7
+} ks_op;
+
+/* Cross-workgroup strategy. */
+typedef enum {
+    KS_ALGO_AUTO = 0,             /* library's choice for (dtype, n)                              */
+    KS_ALGO_LOOKBACK = 1,         /* one kernel, decoupled look-back (paper Sec. V-B): 2n traffic  */
+    KS_ALGO_REDUCE_THEN_SCAN = 2  /* three kernels per level, no inter-workgroup waiting,
+                                     deterministic for floating point: 3n traffic                 */
+} ks_algo;
+
+/*
+ * Scan n elements of `in` into `out` on `stream` (paper Sec. V-B).
+ * Uses a library-owned workspace cached per (device, stream); the first call on
+ * a stream, or a call needing a larger workspace, allocates device memory (and
+ * must therefore not be made under stream capture: use ks_scan_with_temp there).
+ * Back-to-back calls on one stream are safe; calls on different streams use
+ * different workspaces.  inclusive: non-zero = inclusive, 0 = exclusive.
+ */
+int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n,
+            void *stream);
+
+/*
+ * Bytes of device scratch ks_scan_with_temp needs for this problem (the paper's
+ * pre-allocation interface, Sec. VII-C).  Returns 0 for an unsupported pair or
+ * bad enum.  The figure is a multiple of 256 and never 0 for a supported pair.
+ */
+size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n);
+
+/*
+ * Same as ks_scan but with caller-owned scratch: `temp` is a device pointer,
+ * 256-byte aligned, of at least ks_scan_temp_bytes(...) bytes, whose previous
+ * contents do not matter.  Allocates nothing.  The scratch may be reused by a
+ * later call on the same stream; two calls in flight at once need two buffers.
+ */
+int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, const void *in,
+                      void *out, size_t n, void *temp, size_t temp_bytes, void *stream);
+
+/*
+ * Synchronise `stream` and report whether any look-back kernel since the last
+ * check gave up waiting for a predecessor tile (KS_ERR_TIMEOUT; its output is
+ * then invalid), or a HIP error surfaced (KS_ERR_HIP).  The flag is cleared.
+ */
+int ks_scan_check(void *stream);
+
+/* 1 if the (dtype, op) pair is instantiated, else 0. */
+int ks_pair_supported(ks_dtype dtype, ks_op op);
+
+/* sizeof the element type, 0 for a bad enum. */
+size_t ks_elem_bytes(ks_dtype dtype);
+
+/*
+ * Tuning / test knobs (process-wide, not thread-safe against concurrent calls):
+ *   "spin_limit"   polls a look-back wave makes before giving up (default 1<<20)
+ *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid
+ *                  (0 = what the occupancy query allows; values above it are clamped)
+ *   "rows"         16-byte vectors per thread in the look-back kernel (0 = default;
+ *                  only the compiled values 2, 4, 8 are accepted)
+ *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
+ *                  -1 = the type's default
+ *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
+ *                  workgroup per tile, which is only deadlock-free if the hardware
+ *                  starts workgroups in index order (experimental; waits stay bounded)
+ * Returns KS_OK or KS_ERR_INVALID_ARG.  ks_get_option returns the value or -1.
+ */
+int ks_set_option(const char *name, long long value);
+long long ks_get_option(const char *name);
+
+/*
+ * Measurement aid (paper Sec. IV-C, the vectorised copy kernel as the practical
+ * bandwidth ceiling): copy `bytes` bytes (multiple of 16, both pointers 16-byte
+ * aligned) with 16-byte non-temporal loads and stores.
+ */
+int ks_copy(const void *in, void *out, size_t bytes, void *stream);
+
+const char *ks_status_string(int status);
+int ks_last_hip_error(void);
+const char *ks_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KS_SCAN_H */

@@ -1,0 +1,175 @@
+"""ks_scan: device-wide inclusive / exclusive scan for AMD MI355X (gfx950).
+
+Thin Python binding over the C-ABI library ``libks_scan.so`` (declared in
+``include/ks_scan.h``).  It only marshals arguments: PyTorch supplies device
+memory and the stream, every step of the scan runs in the library's HIP
+kernels.  There is no CPU or PyTorch fallback: if the library is missing the
+import of this package fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported first so that the library binds to the HIP runtime torch already loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libks_scan.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2603_18695_amd.build` "
+        "(hipcc, --offload-arch=gfx950). There is no fallback path.")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+KS_OK = 0
+KS_ERR_INVALID_ARG, KS_ERR_UNSUPPORTED, KS_ERR_MISALIGNED, KS_ERR_OVERLAP = -1, -2, -3, -4
+KS_ERR_WORKSPACE, KS_ERR_HIP, KS_ERR_TIMEOUT = -5, -6, -7
+
+DTYPES = {"i32": 0, "u32": 1, "i64": 2, "u64": 3, "f32": 4, "f64": 5, "affine_f32": 6,
+          "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9}
+OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "mat2_mul": 5, "quat_mul": 6}
+ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
+
+EXPORTS = ["ks_scan", "ks_scan_temp_bytes", "ks_scan_with_temp", "ks_scan_check", "ks_pair_supported",
+           "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
+           "ks_last_hip_error", "ks_version"]
+
+_vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+_lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.ks_scan.restype = _i
+_lib.ks_scan_temp_bytes.argtypes = [_i, _i, _i, _sz]
+_lib.ks_scan_temp_bytes.restype = _sz
+_lib.ks_scan_with_temp.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp, _sz, _vp]
+_lib.ks_scan_with_temp.restype = _i
+_lib.ks_scan_check.argtypes = [_vp]
+_lib.ks_scan_check.restype = _i
+_lib.ks_pair_supported.argtypes = [_i, _i]
+_lib.ks_pair_supported.restype = _i
+_lib.ks_elem_bytes.argtypes = [_i]
+_lib.ks_elem_bytes.restype = _sz
+_lib.ks_set_option.argtypes = [ctypes.c_char_p, ctypes.c_longlong]
+_lib.ks_set_option.restype = _i
+_lib.ks_get_option.argtypes = [ctypes.c_char_p]
+_lib.ks_get_option.restype = ctypes.c_longlong
+_lib.ks_copy.argtypes = [_vp, _vp, _sz, _vp]
+_lib.ks_copy.restype = _i
+_lib.ks_status_string.argtypes = [_i]
+_lib.ks_status_string.restype = ctypes.c_char_p
+_lib.ks_last_hip_error.argtypes = []
+_lib.ks_last_hip_error.restype = _i
+_lib.ks_version.argtypes = []
+_lib.ks_version.restype = ctypes.c_char_p
+
+
+class KsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.ks_status_string(status).decode()
+        if status == KS_ERR_HIP:
+            msg += f" [hip error {_lib.ks_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != KS_OK:
+        raise KsError(status, where)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _nbytes(t: torch.Tensor) -> int:
+    return t.numel() * t.element_size()
+
+
+def _elements(t: torch.Tensor, dtype: str) -> int:
+    if not t.is_cuda:
+        raise ValueError("ks_scan works on device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    eb = _lib.ks_elem_bytes(DTYPES[dtype])
+    if _nbytes(t) % eb:
+        raise ValueError(f"tensor of {_nbytes(t)} bytes is not a whole number of {dtype} elements")
+    return _nbytes(t) // eb
+
+
+def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclusive: bool = True,
+            stream=None) -> torch.Tensor:
+    """out = scan(inp) with the library-owned workspace.  Asynchronous on the stream."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != n:
+        raise ValueError("inp and out differ in size")
+    with torch.cuda.device(inp.device):
+        _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
+                            _stream_ptr(stream)), "ks_scan")
+    return out
+
+
+def ks_scan_temp_bytes(*, dtype: str, op: str, n: int, algo: str = "auto") -> int:
+    return int(_lib.ks_scan_temp_bytes(DTYPES[dtype], OPS[op], ALGOS[algo], n))
+
+
+def ks_scan_with_temp(inp: torch.Tensor, out: torch.Tensor, temp: torch.Tensor, *, dtype: str, op: str,
+                      inclusive: bool = True, algo: str = "auto", stream=None) -> torch.Tensor:
+    """out = scan(inp) using caller-owned device scratch `temp` (any dtype, 256-byte aligned)."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != n:
+        raise ValueError("inp and out differ in size")
+    if not temp.is_cuda or not temp.is_contiguous():
+        raise ValueError("temp must be a contiguous device tensor")
+    with torch.cuda.device(inp.device):
+        _check(_lib.ks_scan_with_temp(DTYPES[dtype], OPS[op], int(bool(inclusive)), ALGOS[algo], inp.data_ptr(),
+                                      out.data_ptr(), n, temp.data_ptr(), _nbytes(temp), _stream_ptr(stream)),
+               "ks_scan_with_temp")
+    return out
+
+
+def ks_scan_check(stream=None) -> None:
+    """Synchronise the stream; raise KsError(KS_ERR_TIMEOUT) if a look-back wait was abandoned."""
+    _check(_lib.ks_scan_check(_stream_ptr(stream)), "ks_scan_check")
+
+
+def ks_pair_supported(dtype: str, op: str) -> bool:
+    return bool(_lib.ks_pair_supported(DTYPES[dtype], OPS[op]))
+
+
+def ks_elem_bytes(dtype: str) -> int:
+    return int(_lib.ks_elem_bytes(DTYPES[dtype]))
+
+
+def ks_set_option(name: str, value: int) -> None:
+    _check(_lib.ks_set_option(name.encode(), int(value)), f"ks_set_option({name})")
+
+
+def ks_get_option(name: str) -> int:
+    return int(_lib.ks_get_option(name.encode()))
+
+
+def ks_copy(inp: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """Vectorised device copy used as the bandwidth ceiling in measurements."""
+    if _nbytes(inp) != _nbytes(out):
+        raise ValueError("inp and out differ in size")
+    _check(_lib.ks_copy(inp.data_ptr(), out.data_ptr(), _nbytes(inp), _stream_ptr(stream)), "ks_copy")
+    return out
+
+
+def ks_version() -> str:
+    return _lib.ks_version().decode()
+
+
+def raw_library() -> ctypes.CDLL:
+    """The ctypes handle, for tests that exercise argument validation with raw pointers."""
+    return _lib
+
+
+def ks_status_string(status: int) -> str:
+    return _lib.ks_status_string(int(status)).decode()
+
+
+def ks_last_hip_error() -> int:
+    return int(_lib.ks_last_hip_error())

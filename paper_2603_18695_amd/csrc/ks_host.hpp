@@ -1,0 +1,56 @@
+// Host-side plumbing shared by the translation units of the library: the
+// per-pair launch table, launch arguments and tuning options.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ks_scan.h"
+
+namespace ks {
+
+struct Options {
+    long long spin_limit = 1ll << 20;
+    long long wgs_per_cu = 0;     // 0 = occupancy query
+    long long rows = 0;           // 0 = default for the type
+    long long prefetch = -1;      // -1 = default, 0 / 1 forced
+    long long grid_mode = 0;      // 0 = persistent resident grid, 1 = one workgroup per tile (experimental)
+};
+Options &options();
+
+struct DeviceInfo {
+    int device = -1;
+    int cus = 0;
+    uint32_t *abort_flag = nullptr;   // device address of the library's abort word on this device
+};
+
+struct ScanCall {
+    int inclusive;
+    ks_algo algo;           // never AUTO here
+    const void *in;
+    void *out;
+    size_t n;
+    void *temp;             // device scratch, 256-byte aligned
+    size_t temp_bytes;
+    hipStream_t stream;
+    uint32_t epoch;         // tag for this call's descriptors (look-back only)
+    bool clear_descriptors; // scratch contents unknown: zero the descriptors first
+    const DeviceInfo *dev;
+};
+
+// One entry per instantiated (dtype, op) pair.
+struct PairEntry {
+    size_t elem_bytes;
+    size_t elem_align;
+    size_t (*temp_bytes)(ks_algo algo, size_t n);
+    ks_algo (*pick_algo)(size_t n);
+    int (*run)(const ScanCall &call);   // returns ks_status; HIP failures via set_hip_error
+};
+
+int set_hip_error(hipError_t e);   // records e, returns KS_ERR_HIP
+
+// defined in the ks_pairs_*.hip files
+const PairEntry *pair_entry(int dtype, int op);
+
+}  // namespace ks

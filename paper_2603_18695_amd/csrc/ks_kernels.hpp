@@ -1,0 +1,296 @@
+// Kernels of the scan library.
+//
+//   scan_lookback_kernel   single pass, decoupled look-back (paper Sec. V-B)
+//   tile_reduce_kernel     reduce-then-scan, first kernel: one aggregate per tile
+//   tile_scan_kernel       reduce-then-scan, last kernel: scan a tile from a seed
+//   fill_zero_kernel       clears caller-provided descriptors
+//
+// Tile descriptors (paper Sec. V-B: per-tile aggregate, inclusive prefix and a
+// partial / prefix status flag; Sec. IV-B for the hazard the flag guards).  The
+// paper stores value and flag separately and orders them with a release store
+// and an acquire load, which on this GPU means writing back and invalidating a
+// per-XCD L2.  Here every 32-bit word of the value travels in one 64-bit word
+// together with its status tag, written and read with relaxed device-scope
+// atomics: a reader can never see a tag without the value it belongs to, so no
+// fence, write-back or invalidate is needed.  A value of W words uses W tagged
+// words and is accepted only when all W tags agree.  The tag also carries a
+// call epoch, so descriptors left by earlier calls read as "not set" and the
+// array never has to be cleared between calls.
+#pragma once
+
+#include "ks_tile.hpp"
+
+namespace ks {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+
+constexpr uint32_t kUnset = 0;
+constexpr uint32_t kPartial = 1;   // value = aggregate of the tile alone
+constexpr uint32_t kPrefix = 2;    // value = combination of tiles 0..t
+
+__device__ __forceinline__ void desc_store_word(uint64_t *p, uint32_t tag, uint32_t payload) {
+    __hip_atomic_store(p, ((uint64_t)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <class T>
+__device__ __forceinline__ void desc_publish(uint64_t *desc, uint32_t tile, uint32_t epoch, uint32_t state,
+                                             const T &value) {
+    constexpr int W = WordsOf<T>::W;
+    auto ws = to_words(value);
+    uint64_t *p = desc + (size_t)tile * W;
+    const uint32_t tag = (epoch << 2) | state;
+#pragma unroll
+    for (int k = 0; k < W; ++k) desc_store_word(p + k, tag, ws.w[k]);
+}
+
+// Returns the state (kUnset if the descriptor is from another epoch or its
+// words do not carry one common tag yet) and the value.
+template <class T>
+__device__ __forceinline__ uint32_t desc_read(const uint64_t *desc, uint32_t tile, uint32_t epoch, T &value) {
+    constexpr int W = WordsOf<T>::W;
+    const uint64_t *p = desc + (size_t)tile * W;
+    typename WordsOf<T>::type ws;
+    uint32_t tag0 = 0;
+    bool same = true;
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        uint64_t v = __hip_atomic_load(p + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t tag = (uint32_t)(v >> 32);
+        ws.w[k] = (uint32_t)v;
+        if (k == 0) tag0 = tag; else same = same && (tag == tag0);
+    }
+    value = from_words<T>(ws);
+    if (!same || (tag0 >> 2) != epoch) return kUnset;
+    return tag0 & 3u;
+}
+
+// Look-back executed by one full wave (paper Sec. V-B, third paragraph; window of
+// 64 predecessors on wave64).  Lane 63 inspects the nearest predecessor and
+// lane 0 the farthest, so lane order is tile order and the ordinary wave scan
+// combines the window with earlier tiles on the left.  Returns false when the
+// spin limit was hit or another workgroup has already given up.
+template <class T, class Op>
+__device__ __forceinline__ bool lookback(const uint64_t *desc, uint32_t tile, uint32_t epoch,
+                                         uint32_t spin_limit, uint32_t *abort_flag, T &exclusive_prefix) {
+    const int lane = threadIdx.x & (kWave - 1);
+    Op op;
+    T running = Op::identity();              // combination of the windows already consumed (later tiles)
+    long long newest = (long long)tile - 1;  // newest tile of the current window
+    uint32_t spins = 0;
+    for (;;) {
+        const long long mine = newest - (kWave - 1) + lane;
+        T val = Op::identity();
+        uint32_t st = (mine >= 0) ? kUnset : kPartial;   // before tile 0: nothing, counts as an empty aggregate
+        int top;                                          // highest lane holding a PREFIX, -1 if none
+        for (;;) {
+            if (st == kUnset) st = desc_read<T>(desc, (uint32_t)mine, epoch, val);
+            const uint64_t prefix_mask = __ballot(st == kPrefix);
+            const uint64_t unset_mask = __ballot(st == kUnset);
+            top = prefix_mask ? 63 - __builtin_clzll(prefix_mask) : -1;
+            const uint64_t needed = (top >= 63) ? 0ull : (~0ull << (top + 1));   // lanes above the nearest PREFIX
+            if ((unset_mask & needed) == 0) break;
+            ++spins;
+            if (spins > spin_limit) {
+                if (lane == 0) __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return false;
+            }
+            if ((spins & 63u) == 0) {   // has another workgroup given up?  (decided wave-uniformly)
+                const uint32_t f = __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__ballot(f != 0) != 0) return false;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (lane < top) val = Op::identity();   // tiles already covered by the PREFIX found
+        const T window = read_lane(wave_inclusive_scan(val, op), kWave - 1);
+        running = op(window, running);
+        if (top >= 0) break;
+        newest -= kWave;
+    }
+    exclusive_prefix = running;
+    return true;
+}
+
+// Cross-wave exchange through LDS (paper Sec. V-B: shared-memory exchange that
+// yields the tile aggregate).  Returns the combination of the waves before
+// this one; `aggregate` receives the whole tile's.
+template <class T, class Op>
+__device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_tot, const T &wave_total,
+                                                  T &aggregate, Op op) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    if (lane == 0) s_tot[wave] = to_words(wave_total);
+    __syncthreads();
+    T carry = Op::identity();
+    T all = Op::identity();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const T t = from_words<T>(s_tot[w]);
+        if (w < wave) carry = op(carry, t);
+        all = op(all, t);
+    }
+    aggregate = all;
+    return carry;
+}
+
+template <class IO, int ROWS>
+__device__ __forceinline__ size_t lane_first_element(uint32_t tile) {
+    using S = TileShape<IO, ROWS>;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    return (size_t)tile * (kWaves * S::WAVE_ELEMS) + (size_t)wave * S::WAVE_ELEMS + (size_t)lane * S::G;
+}
+
+// ---------------------------------------------------------------------------
+// Single-pass scan.  The grid is persistent: workgroup b handles tiles b,
+// b + gridDim.x, ... in increasing order, and the host launches no more
+// workgroups than can be resident at once, so the tile a workgroup waits for is
+// always owned by a workgroup that is running (the paper does not say how tiles
+// are assigned; this removes any reliance on dispatch order without a ticket
+// atomic per tile).  Every wait is bounded by spin_limit.
+// IO = element type in memory, Op::acc = type of registers and descriptors.
+// ---------------------------------------------------------------------------
+template <class IO, class Op, int ROWS, bool INCLUSIVE, bool PREFETCH>
+__global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
+                                                               size_t n, uint64_t *desc, uint32_t epoch,
+                                                               uint32_t ntiles, uint32_t spin_limit,
+                                                               uint32_t *abort_flag, int aligned) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    using Items = ThreadItems<A, ROWS, S::G>;
+    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    __shared__ typename WordsOf<A>::type s_prefix;
+    __shared__ uint32_t s_ok;
+    Op op;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+
+    uint32_t tile = blockIdx.x;
+    if (tile >= ntiles) return;
+    Items cur;
+    {
+        const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
+        load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(tile), n, vec, cur);
+    }
+    for (;;) {
+        const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
+        WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+        A aggregate;
+        const A wave_carry = exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+
+        // publish as early as possible: successors only need the aggregate
+        if (threadIdx.x == 0) desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+
+        const uint32_t next = tile + gridDim.x;
+        Items nxt;
+        if (PREFETCH && next < ntiles) {
+            const bool nvec = aligned && ((size_t)(next + 1) * TILE <= n);
+            load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(next), n, nvec, nxt);
+        }
+
+        if (wave == 0) {
+            A excl = Op::identity();
+            bool ok = true;
+            if (tile != 0) {
+                ok = lookback<A, Op>(desc, tile, epoch, spin_limit, abort_flag, excl);
+                if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
+            }
+            if (lane == 0) {
+                s_prefix = to_words(excl);
+                s_ok = ok ? 1u : 0u;
+            }
+        }
+        __syncthreads();
+        if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
+        const A tile_prefix = from_words<A>(s_prefix);
+
+        apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
+        store_items<IO, ROWS, A>(out, lane_first_element<IO, ROWS>(tile), n, vec, cur);
+
+        if (next >= ntiles) break;
+        tile = next;
+        if (PREFETCH) {
+            cur = nxt;
+        } else {
+            const bool nvec = aligned && ((size_t)(tile + 1) * TILE <= n);
+            load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(tile), n, nvec, cur);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Reduce-then-scan (no waiting between workgroups; one workgroup per tile).
+// Aggregates and seeds are arrays of Op::acc.
+// ---------------------------------------------------------------------------
+template <class IO, class Op, int ROWS>
+__global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restrict__ in, size_t n,
+                                                             typename Op::acc *__restrict__ aggregates,
+                                                             int aligned) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    Op op;
+    const size_t tile = blockIdx.x;
+    const bool vec = aligned && ((tile + 1) * TILE <= n);
+    ThreadItems<A, ROWS, S::G> cur;
+    load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+    WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    A aggregate;
+    (void)exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+    if (threadIdx.x == 0) aggregates[tile] = aggregate;
+}
+
+// seeds == nullptr: every tile starts from the identity (used when one tile
+// covers the whole input).  Otherwise seeds[tile] = combination of all earlier tiles.
+template <class IO, class Op, int ROWS, bool INCLUSIVE>
+__global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict__ in, IO *__restrict__ out, size_t n,
+                                                           const typename Op::acc *__restrict__ seeds,
+                                                           int aligned) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    Op op;
+    const size_t tile = blockIdx.x;
+    const bool vec = aligned && ((tile + 1) * TILE <= n);
+    ThreadItems<A, ROWS, S::G> cur;
+    load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+    WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    A aggregate;
+    const A wave_carry = exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+    const A seed = seeds ? seeds[tile] : Op::identity();
+    apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(seed, wave_carry), op);
+    store_items<IO, ROWS, A>(out, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+}
+
+template <int UNUSED = 0>
+__global__ void fill_zero_kernel(uint64_t *p, size_t words) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < words; i += stride) p[i] = 0ull;
+}
+
+// Vectorised copy, one 16-byte granule per lane and ROWS granules per thread in
+// the same wave-run arrangement as the scan (paper Sec. IV-C, copy kernel).
+template <int ROWS>
+__global__ __launch_bounds__(kBlock) void copy_kernel(const u32x4 *__restrict__ in, u32x4 *__restrict__ out,
+                                                      size_t granules) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const size_t first = ((size_t)blockIdx.x * kWaves + wave) * (size_t)(kWave * ROWS) + lane;
+    u32x4 v[ROWS];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const size_t i = first + (size_t)j * kWave;
+        if (i < granules) v[j] = __builtin_nontemporal_load(in + i);
+    }
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const size_t i = first + (size_t)j * kWave;
+        if (i < granules) __builtin_nontemporal_store(v[j], out + i);
+    }
+}
+
+}  // namespace ks

@@ -1,0 +1,246 @@
+// C ABI of the scan library: argument validation, (dtype, op) lookup, the
+// library-owned workspace cache and the status / option entry points.
+// Declarations and conventions: include/ks_scan.h.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "ks_host.hpp"
+#include "ks_kernels.hpp"
+
+namespace ks {
+
+// Set by a look-back wave that exhausted its spin limit; one word per device.
+__device__ uint32_t g_abort_flag;
+
+const PairEntry *pair_entry_i32(int, int);
+const PairEntry *pair_entry_i64(int, int);
+const PairEntry *pair_entry_float(int, int);
+const PairEntry *pair_entry_struct(int, int);
+
+const PairEntry *pair_entry(int dtype, int op) {
+    if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT) return nullptr;
+    if (const PairEntry *e = pair_entry_i32(dtype, op)) return e;
+    if (const PairEntry *e = pair_entry_i64(dtype, op)) return e;
+    if (const PairEntry *e = pair_entry_float(dtype, op)) return e;
+    return pair_entry_struct(dtype, op);
+}
+
+Options &options() {
+    static Options o;
+    return o;
+}
+
+static thread_local int t_last_hip = 0;
+int set_hip_error(hipError_t e) {
+    t_last_hip = (int)e;
+    return KS_ERR_HIP;
+}
+
+namespace {
+
+std::mutex g_mutex;
+std::map<int, DeviceInfo> g_devices;
+
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    uint32_t epoch = 0;   // last epoch handed out; descriptors carry (epoch << 2 | state)
+};
+std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
+
+constexpr uint32_t kMaxEpoch = (1u << 30) - 1;
+
+int device_info(const DeviceInfo **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_hip_error(e);
+    auto it = g_devices.find(dev);
+    if (it == g_devices.end()) {
+        DeviceInfo d;
+        d.device = dev;
+        e = hipDeviceGetAttribute(&d.cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return set_hip_error(e);
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_abort_flag));
+        if (e != hipSuccess) return set_hip_error(e);
+        d.abort_flag = static_cast<uint32_t *>(p);
+        it = g_devices.emplace(dev, d).first;
+    }
+    *out = &it->second;
+    return KS_OK;
+}
+
+int validate(ks_dtype dtype, ks_op op, const void *in, void *out, size_t n, const PairEntry **entry) {
+    if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
+    const PairEntry *e = pair_entry(dtype, op);
+    if (!e) return KS_ERR_UNSUPPORTED;
+    *entry = e;
+    if (n == 0) return KS_OK;
+    if (!in || !out) return KS_ERR_INVALID_ARG;
+    if (n > ((size_t)1 << 40)) return KS_ERR_INVALID_ARG;
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if ((a % e->elem_align) || (b % e->elem_align)) return KS_ERR_MISALIGNED;
+    const size_t bytes = n * e->elem_bytes;
+    if (a != b && a < b + bytes && b < a + bytes) return KS_ERR_OVERLAP;
+    return KS_OK;
+}
+
+}  // namespace
+}  // namespace ks
+
+using namespace ks;
+
+extern "C" {
+
+int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, const void *in, void *out, size_t n,
+                      void *temp, size_t temp_bytes, void *stream) {
+    const PairEntry *e = nullptr;
+    int st = validate(dtype, op, in, out, n, &e);
+    if (st != KS_OK || n == 0) return st;
+    if ((int)algo < KS_ALGO_AUTO || (int)algo > KS_ALGO_REDUCE_THEN_SCAN) return KS_ERR_INVALID_ARG;
+    if (algo == KS_ALGO_AUTO) algo = e->pick_algo(n);
+    if (!temp || ((uintptr_t)temp & 255u) || temp_bytes < e->temp_bytes(algo, n)) return KS_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    ScanCall c{inclusive, algo, in, out, n, temp, temp_bytes, (hipStream_t)stream, 1u, true, dev};
+    return e->run(c);
+}
+
+int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
+    const PairEntry *e = nullptr;
+    int st = validate(dtype, op, in, out, n, &e);
+    if (st != KS_OK || n == 0) return st;
+    const ks_algo algo = e->pick_algo(n);
+    const size_t need = e->temp_bytes(algo, n);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    Workspace &ws = g_workspaces[std::make_pair(dev->device, (hipStream_t)stream)];
+    bool fresh = false;
+    if (ws.bytes < need) {
+        // growing: hipFree waits for the device, so nothing in flight still uses the old buffer
+        if (ws.ptr) (void)hipFree(ws.ptr);
+        ws.ptr = nullptr;
+        ws.bytes = 0;
+        const size_t want = need < ((size_t)1 << 20) ? ((size_t)1 << 20) : need;
+        hipError_t he = hipMalloc(&ws.ptr, want);
+        if (he != hipSuccess) {
+            ws.ptr = nullptr;
+            set_hip_error(he);
+            return KS_ERR_WORKSPACE;
+        }
+        ws.bytes = want;
+        fresh = true;
+    }
+    if (fresh || ws.epoch >= kMaxEpoch) {
+        hipError_t he = hipMemsetAsync(ws.ptr, 0, ws.bytes, (hipStream_t)stream);
+        if (he != hipSuccess) return set_hip_error(he);
+        ws.epoch = 0;
+    }
+    if (algo == KS_ALGO_LOOKBACK) ++ws.epoch;
+    ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, ws.epoch, false, dev};
+    return e->run(c);
+}
+
+size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n) {
+    const PairEntry *e = pair_entry((int)dtype, (int)op);
+    if (!e || (int)algo < KS_ALGO_AUTO || (int)algo > KS_ALGO_REDUCE_THEN_SCAN) return 0;
+    return e->temp_bytes(algo, n);
+}
+
+int ks_scan_check(void *stream) {
+    hipError_t he = hipStreamSynchronize((hipStream_t)stream);
+    if (he != hipSuccess) return set_hip_error(he);
+    uint32_t flag = 0;
+    he = hipMemcpyFromSymbol(&flag, HIP_SYMBOL(g_abort_flag), sizeof(flag));
+    if (he != hipSuccess) return set_hip_error(he);
+    if (flag != 0) {
+        const uint32_t zero = 0;
+        he = hipMemcpyToSymbol(HIP_SYMBOL(g_abort_flag), &zero, sizeof(zero));
+        if (he != hipSuccess) return set_hip_error(he);
+        return KS_ERR_TIMEOUT;
+    }
+    return KS_OK;
+}
+
+int ks_pair_supported(ks_dtype dtype, ks_op op) { return pair_entry((int)dtype, (int)op) ? 1 : 0; }
+
+size_t ks_elem_bytes(ks_dtype dtype) {
+    switch (dtype) {
+        case KS_I32: case KS_U32: case KS_F32: return 4;
+        case KS_I64: case KS_U64: case KS_F64: case KS_AFFINE_F32: return 8;
+        case KS_ARGMAX_I32_CNT64: case KS_MAT2_U32: case KS_QUAT_F32: return 16;
+        default: return 0;
+    }
+}
+
+static long long *option_slot(const char *name) {
+    if (!name) return nullptr;
+    Options &o = options();
+    if (!std::strcmp(name, "spin_limit")) return &o.spin_limit;
+    if (!std::strcmp(name, "wgs_per_cu")) return &o.wgs_per_cu;
+    if (!std::strcmp(name, "rows")) return &o.rows;
+    if (!std::strcmp(name, "prefetch")) return &o.prefetch;
+    if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
+    return nullptr;
+}
+
+int ks_set_option(const char *name, long long value) {
+    long long *slot = option_slot(name);
+    if (!slot) return KS_ERR_INVALID_ARG;
+    Options &o = options();
+    if (slot == &o.rows && !(value == 0 || value == 2 || value == 4 || value == 8)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
+    if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
+    if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.prefetch && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
+    *slot = value;
+    return KS_OK;
+}
+
+long long ks_get_option(const char *name) {
+    long long *slot = option_slot(name);
+    return slot ? *slot : -1;
+}
+
+int ks_copy(const void *in, void *out, size_t bytes, void *stream) {
+    if (bytes == 0) return KS_OK;
+    if (!in || !out) return KS_ERR_INVALID_ARG;
+    if ((bytes & 15u) || ((uintptr_t)in & 15u) || ((uintptr_t)out & 15u)) return KS_ERR_MISALIGNED;
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if (a < b + bytes && b < a + bytes) return KS_ERR_OVERLAP;
+    constexpr int ROWS = 4;
+    const size_t granules = bytes / 16;
+    const size_t per_wg = (size_t)kBlock * ROWS;
+    const size_t grid = (granules + per_wg - 1) / per_wg;
+    if (grid > 0x7fffffffull) return KS_ERR_INVALID_ARG;
+    hipLaunchKernelGGL((copy_kernel<ROWS>), dim3((unsigned)grid), dim3(kBlock), 0, (hipStream_t)stream,
+                       static_cast<const u32x4 *>(in), static_cast<u32x4 *>(out), granules);
+    hipError_t he = hipGetLastError();
+    return he == hipSuccess ? KS_OK : set_hip_error(he);
+}
+
+const char *ks_status_string(int status) {
+    switch (status) {
+        case KS_OK: return "ok";
+        case KS_ERR_INVALID_ARG: return "invalid argument";
+        case KS_ERR_UNSUPPORTED: return "(dtype, op) pair not supported";
+        case KS_ERR_MISALIGNED: return "pointer not aligned to the element type";
+        case KS_ERR_OVERLAP: return "in and out overlap without being identical";
+        case KS_ERR_WORKSPACE: return "scratch buffer missing, too small, misaligned or not allocatable";
+        case KS_ERR_HIP: return "HIP runtime error (see ks_last_hip_error)";
+        case KS_ERR_TIMEOUT: return "a look-back wait exceeded its spin limit";
+        default: return "unknown status";
+    }
+}
+
+int ks_last_hip_error(void) { return t_last_hip; }
+
+const char *ks_version(void) { return "ks_scan 0.1 (gfx950)"; }
+
+}  // extern "C"

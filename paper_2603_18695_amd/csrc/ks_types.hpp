@@ -1,0 +1,173 @@
+// Element types and operators of the scan library (device side).
+//
+// An operator is a stateless functor with
+//     using acc = ...;                    // type the scan is carried out in
+//     static acc identity();              // op(identity, x) == x bit for bit
+//     acc operator()(acc l, acc r) const; // l = accumulated (earlier), r = later
+// The element type in memory ("io" type) is converted to acc on load and back
+// on store (convert<>); for most pairs the two are the same type.  io types are
+// trivially copyable, 4, 8 or 16 bytes; acc types are a multiple of 4 bytes and
+// are moved between lanes and through memory as arrays of 32-bit words (paper
+// Sec. IV-A: any composite type is shuffled field by field as 32-bit pieces).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ks {
+
+template <int W>
+struct Words {
+    uint32_t w[W];
+};
+
+template <class T>
+struct WordsOf {
+    static_assert(sizeof(T) % 4 == 0, "element size must be a multiple of 4 bytes");
+    static constexpr int W = sizeof(T) / 4;
+    using type = Words<W>;
+};
+
+template <class T>
+__device__ __forceinline__ typename WordsOf<T>::type to_words(const T &x) {
+    return __builtin_bit_cast(typename WordsOf<T>::type, x);
+}
+template <class T>
+__device__ __forceinline__ T from_words(const typename WordsOf<T>::type &w) {
+    return __builtin_bit_cast(T, w);
+}
+
+// ---- element structs -------------------------------------------------------
+
+struct AffineF32 {      // the map x -> a*x + b
+    float a, b;
+};
+struct AffineF64 {      // the same map carried in double (accumulation type of AffineF32)
+    double a, b;
+};
+struct ArgmaxI32Cnt64 { // running maximum, where it first occurred, how many seen
+    int32_t v;
+    int32_t idx;
+    int64_t cnt;
+};
+struct Mat2U32 {        // row-major 2x2 matrix over Z/2^32
+    uint32_t m00, m01, m10, m11;
+};
+struct QuatF32 {
+    float w, x, y, z;
+};
+
+// ---- limits for min / max identities ---------------------------------------
+
+template <class T> struct Limits;
+template <> struct Limits<int32_t>  { __device__ static int32_t  lo() { return INT32_MIN; } __device__ static int32_t  hi() { return INT32_MAX; } };
+template <> struct Limits<uint32_t> { __device__ static uint32_t lo() { return 0u; }        __device__ static uint32_t hi() { return UINT32_MAX; } };
+template <> struct Limits<int64_t>  { __device__ static int64_t  lo() { return INT64_MIN; } __device__ static int64_t  hi() { return INT64_MAX; } };
+template <> struct Limits<uint64_t> { __device__ static uint64_t lo() { return 0ull; }      __device__ static uint64_t hi() { return UINT64_MAX; } };
+template <> struct Limits<float>    { __device__ static float    lo() { return -__builtin_inff(); } __device__ static float  hi() { return __builtin_inff(); } };
+template <> struct Limits<double>   { __device__ static double   lo() { return -__builtin_inf(); }  __device__ static double hi() { return __builtin_inf(); } };
+
+// ---- operators --------------------------------------------------------------
+
+template <class T>
+struct SumOp {
+    using acc = T;
+    __device__ static T identity() { return T(0); }
+    __device__ __forceinline__ T operator()(T l, T r) const { return l + r; }
+};
+// signed integer sums wrap: add in the unsigned type
+template <>
+struct SumOp<int32_t> {
+    using acc = int32_t;
+    __device__ static int32_t identity() { return 0; }
+    __device__ __forceinline__ int32_t operator()(int32_t l, int32_t r) const { return (int32_t)((uint32_t)l + (uint32_t)r); }
+};
+template <>
+struct SumOp<int64_t> {
+    using acc = int64_t;
+    __device__ static int64_t identity() { return 0; }
+    __device__ __forceinline__ int64_t operator()(int64_t l, int64_t r) const { return (int64_t)((uint64_t)l + (uint64_t)r); }
+};
+
+template <class T>
+struct MinOp {
+    using acc = T;
+    __device__ static T identity() { return Limits<T>::hi(); }
+    __device__ __forceinline__ T operator()(T l, T r) const { return r < l ? r : l; }
+};
+template <class T>
+struct MaxOp {
+    using acc = T;
+    __device__ static T identity() { return Limits<T>::lo(); }
+    __device__ __forceinline__ T operator()(T l, T r) const { return r > l ? r : l; }
+};
+
+// Apply l first, then r.  Carried in double: the offset b of a long composition
+// is a sum with heavy cancellation (it crosses zero while its terms stay O(100)),
+// so float32 intermediates cannot hold 1e-3 absolute accuracy over millions of
+// elements; the float32 inputs and outputs are converted at the memory boundary.
+struct AffineComposeOp {
+    using acc = AffineF64;
+    __device__ static AffineF64 identity() { return AffineF64{1.0, 0.0}; }
+    __device__ __forceinline__ AffineF64 operator()(AffineF64 l, AffineF64 r) const {
+        return AffineF64{r.a * l.a, __builtin_fma(r.a, l.b, r.b)};
+    }
+};
+
+struct ArgmaxCountOp {
+    using acc = ArgmaxI32Cnt64;
+    __device__ static ArgmaxI32Cnt64 identity() { return ArgmaxI32Cnt64{INT32_MIN, INT32_MAX, 0}; }
+    __device__ __forceinline__ ArgmaxI32Cnt64 operator()(ArgmaxI32Cnt64 l, ArgmaxI32Cnt64 r) const {
+        const bool take_r = (r.v > l.v) || (r.v == l.v && r.idx < l.idx);
+        ArgmaxI32Cnt64 o;
+        o.v = take_r ? r.v : l.v;
+        o.idx = take_r ? r.idx : l.idx;
+        o.cnt = (int64_t)((uint64_t)l.cnt + (uint64_t)r.cnt);
+        return o;
+    }
+};
+
+struct Mat2MulOp {
+    using acc = Mat2U32;
+    __device__ static Mat2U32 identity() { return Mat2U32{1u, 0u, 0u, 1u}; }
+    __device__ __forceinline__ Mat2U32 operator()(Mat2U32 l, Mat2U32 r) const {
+        return Mat2U32{l.m00 * r.m00 + l.m01 * r.m10, l.m00 * r.m01 + l.m01 * r.m11,
+                       l.m10 * r.m00 + l.m11 * r.m10, l.m10 * r.m01 + l.m11 * r.m11};
+    }
+};
+
+struct QuatMulOp {   // Hamilton product l * r
+    using acc = QuatF32;
+    __device__ static QuatF32 identity() { return QuatF32{1.0f, 0.0f, 0.0f, 0.0f}; }
+    __device__ __forceinline__ QuatF32 operator()(QuatF32 l, QuatF32 r) const {
+        return QuatF32{l.w * r.w - l.x * r.x - l.y * r.y - l.z * r.z,
+                       l.w * r.x + l.x * r.w + l.y * r.z - l.z * r.y,
+                       l.w * r.y - l.x * r.z + l.y * r.w + l.z * r.x,
+                       l.w * r.z + l.x * r.y - l.y * r.x + l.z * r.w};
+    }
+};
+
+// ---- memory type <-> accumulation type ---------------------------------------
+
+template <class To, class From>
+struct Convert {
+    static_assert(sizeof(To) == 0, "no conversion between these element types");
+};
+template <class T>
+struct Convert<T, T> {
+    __device__ __forceinline__ static T apply(const T &x) { return x; }
+};
+template <>
+struct Convert<AffineF64, AffineF32> {
+    __device__ __forceinline__ static AffineF64 apply(const AffineF32 &x) { return AffineF64{(double)x.a, (double)x.b}; }
+};
+template <>
+struct Convert<AffineF32, AffineF64> {
+    __device__ __forceinline__ static AffineF32 apply(const AffineF64 &x) { return AffineF32{(float)x.a, (float)x.b}; }
+};
+template <class To, class From>
+__device__ __forceinline__ To convert(const From &x) {
+    return Convert<To, From>::apply(x);
+}
+
+}  // namespace ks

@@ -1,0 +1,112 @@
+"""Helpers shared by the GPU parity tests: host <-> device marshalling and the comparison bars.
+
+Bars (stated once, used everywhere):
+  * integer, index and struct-of-integer results: bit-exact against the oracle;
+  * floating point results: |gpu - ref| <= 1e-4 * |ref| + 1e-3 element by element, where ref is
+    the oracle's fp64 result on the same float32 inputs (relative 1e-4, absolute 1e-3 near zero);
+  * min / max of floats are order independent and compared exactly.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+
+RTOL, ATOL = 1e-4, 1e-3
+
+# library (dtype, op) -> oracle (op, dt), numpy storage dtype, columns per element
+KINDS = {
+    ("i32", "sum"): ("sum", "i32", np.int32, 1), ("i32", "min"): ("min", "i32", np.int32, 1),
+    ("i32", "max"): ("max", "i32", np.int32, 1),
+    ("u32", "sum"): ("sum", "u32", np.uint32, 1), ("u32", "min"): ("min", "u32", np.uint32, 1),
+    ("u32", "max"): ("max", "u32", np.uint32, 1),
+    ("i64", "sum"): ("sum", "i64", np.int64, 1), ("i64", "min"): ("min", "i64", np.int64, 1),
+    ("i64", "max"): ("max", "i64", np.int64, 1),
+    ("u64", "sum"): ("sum", "u64", np.uint64, 1), ("u64", "min"): ("min", "u64", np.uint64, 1),
+    ("u64", "max"): ("max", "u64", np.uint64, 1),
+    ("f32", "sum"): ("sum", "f32", np.float32, 1), ("f32", "min"): ("min", "f32", np.float32, 1),
+    ("f32", "max"): ("max", "f32", np.float32, 1),
+    ("f64", "sum"): ("sum", "f64", np.float64, 1), ("f64", "min"): ("min", "f64", np.float64, 1),
+    ("f64", "max"): ("max", "f64", np.float64, 1),
+    ("affine_f32", "affine_compose"): ("affine", "f32", np.float32, 2),
+    ("argmax_i32_cnt64", "argmax_count"): ("argmax", None, oracle.ARGMAX_DTYPE, 1),
+    ("mat2_u32", "mat2_mul"): ("mat2", "u32", np.uint32, 4),
+    ("quat_f32", "quat_mul"): ("quat", "f32", np.float32, 4),
+}
+FLOAT_TOL = {("f32", "sum"), ("f64", "sum"), ("affine_f32", "affine_compose"), ("quat_f32", "quat_mul")}
+
+_SIGNED_VIEW = {np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}
+
+
+def to_device(x: np.ndarray, device="cuda") -> torch.Tensor:
+    """Copy a host array to the device as raw storage (unsigned and struct types travel as signed ints)."""
+    x = np.ascontiguousarray(x)
+    if x.dtype == oracle.ARGMAX_DTYPE:
+        x = x.view(np.int32).reshape(-1, 4)
+    elif x.dtype in _SIGNED_VIEW:
+        x = x.view(_SIGNED_VIEW[x.dtype])
+    return torch.from_numpy(x).to(device)
+
+
+def to_host(t: torch.Tensor, like_dtype) -> np.ndarray:
+    a = t.cpu().numpy()
+    like_dtype = np.dtype(like_dtype)
+    if like_dtype == oracle.ARGMAX_DTYPE:
+        return a.reshape(-1).view(oracle.ARGMAX_DTYPE)
+    if like_dtype in _SIGNED_VIEW:
+        return a.view(like_dtype)
+    return a
+
+
+def random_input(dtype: str, op: str, n: int, seed: int) -> np.ndarray:
+    """Generic seeded inputs for the (dtype, op) sweep (value ranges chosen so sums wrap and maxima tie)."""
+    import ks_inputs
+    rng = np.random.default_rng(seed)
+    _, _, npdt, cols = KINDS[(dtype, op)]
+    if dtype == "affine_f32":
+        return ks_inputs.whole("affine", n, seed)
+    if dtype == "argmax_i32_cnt64":
+        x = ks_inputs.whole("argmax", n, seed)
+        x["v"] = rng.integers(0, 50, size=n)          # many ties
+        x["cnt"] = rng.integers(0, 1 << 40, size=n)
+        return x
+    if dtype == "mat2_u32":
+        return ks_inputs.random_mat2(n, seed)
+    if dtype == "quat_f32":
+        return ks_inputs.random_unit_quats(n, seed)
+    if np.issubdtype(npdt, np.integer):
+        info = np.iinfo(npdt)
+        return rng.integers(info.min, info.max, size=n, dtype=npdt, endpoint=True)
+    if op == "sum":
+        return rng.uniform(-1.0, 1.0, size=n).astype(npdt)
+    return rng.normal(size=n).astype(npdt)
+
+
+def reference(dtype: str, op: str, x: np.ndarray, inclusive: bool) -> np.ndarray:
+    oop, odt, _, _ = KINDS[(dtype, op)]
+    return oracle.scan(oop, odt, x, inclusive)
+
+
+def assert_matches(dtype: str, op: str, got: np.ndarray, ref: np.ndarray, what: str = "") -> float:
+    """Apply the bar for this pair; returns the worst |err| / (ATOL + RTOL |ref|) for float pairs, else 0."""
+    if (dtype, op) in FLOAT_TOL:
+        g = got.astype(np.float64).reshape(ref.shape)
+        err = np.abs(g - ref)
+        bound = ATOL + RTOL * np.abs(ref)
+        worst = float(np.max(err / bound)) if err.size else 0.0
+        if not worst <= 1.0:
+            i = int(np.argmax(err / bound))
+            raise AssertionError(f"{what}: float mismatch, worst ratio {worst:.3g} at flat index {i}: "
+                                 f"gpu={g.reshape(-1)[i]!r} ref={ref.reshape(-1)[i]!r}")
+        return worst
+    g = got.reshape(ref.shape) if got.dtype != oracle.ARGMAX_DTYPE else got
+    if g.tobytes() != ref.tobytes():
+        if g.dtype == oracle.ARGMAX_DTYPE:
+            bad = np.nonzero((g["v"] != ref["v"]) | (g["idx"] != ref["idx"]) | (g["cnt"] != ref["cnt"]))[0]
+        else:
+            bad = np.nonzero((g != ref).reshape(len(ref), -1).any(axis=1))[0]
+        i = int(bad[0]) if len(bad) else -1
+        raise AssertionError(f"{what}: {len(bad)} of {len(ref)} elements differ, first at {i}: "
+                             f"gpu={g[i]!r} ref={ref[i]!r}")
+    return 0.0

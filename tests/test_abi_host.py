@@ -1,0 +1,119 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every declared symbol, and its
+host-side validation answers without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ks_scan.h")
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2603_18695_amd as ks
+    return ks
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ks_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ["ks_scan", "ks_scan_temp_bytes", "ks_scan_with_temp", "ks_scan_check", "ks_copy",
+                 "ks_status_string", "ks_last_hip_error", "ks_version"]:
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(ks):
+    lib = ctypes.CDLL(ks.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    assert sorted(ks.EXPORTS) == declared_functions()
+
+
+def test_python_binding_has_the_same_names(ks):
+    for name in declared_functions():
+        assert hasattr(ks, name), name
+
+
+def test_enums_and_sizes(ks):
+    assert ks.ks_elem_bytes("f32") == 4 and ks.ks_elem_bytes("u64") == 8
+    assert ks.ks_elem_bytes("affine_f32") == 8 and ks.ks_elem_bytes("argmax_i32_cnt64") == 16
+    lib = ks.raw_library()
+    assert lib.ks_elem_bytes(99) == 0
+    for dt in ["i32", "u32", "i64", "u64", "f32", "f64"]:
+        for op in ["sum", "min", "max"]:
+            assert ks.ks_pair_supported(dt, op)
+    assert ks.ks_pair_supported("affine_f32", "affine_compose")
+    assert ks.ks_pair_supported("argmax_i32_cnt64", "argmax_count")
+    assert ks.ks_pair_supported("mat2_u32", "mat2_mul") and ks.ks_pair_supported("quat_f32", "quat_mul")
+    assert not ks.ks_pair_supported("f32", "affine_compose")
+    assert not ks.ks_pair_supported("affine_f32", "sum")
+
+
+def test_validation_returns_before_any_gpu_work(ks):
+    lib = ks.raw_library()
+    F32, SUM, AFF = ks.DTYPES["f32"], ks.OPS["sum"], ks.OPS["affine_compose"]
+    a, b = 0x10000000, 0x20000000   # never dereferenced: every call below fails validation first
+    assert lib.ks_scan(99, SUM, 1, a, b, 10, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan(F32, 99, 1, a, b, 10, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan(F32, AFF, 1, a, b, 10, None) == ks.KS_ERR_UNSUPPORTED
+    assert lib.ks_scan(F32, SUM, 1, None, b, 10, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan(F32, SUM, 1, a, None, 10, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan(F32, SUM, 1, a + 2, b, 10, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan(ks.DTYPES["u64"], SUM, 1, a + 4, b, 10, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan(F32, SUM, 1, a, a + 8, 10, None) == ks.KS_ERR_OVERLAP
+    assert lib.ks_scan(F32, SUM, 1, a + 8, a, 10, None) == ks.KS_ERR_OVERLAP
+    assert lib.ks_scan(F32, SUM, 1, None, None, 0, None) == ks.KS_OK          # n == 0: no-op
+    assert lib.ks_scan(F32, SUM, 1, a, b, (1 << 40) + 1, None) == ks.KS_ERR_INVALID_ARG
+    # with_temp: scratch problems are reported before any launch
+    need = lib.ks_scan_temp_bytes(F32, SUM, 1, 1 << 20)
+    assert need >= 256 and need % 256 == 0
+    assert lib.ks_scan_with_temp(F32, SUM, 1, 1, a, b, 1 << 20, None, need, None) == ks.KS_ERR_WORKSPACE
+    assert lib.ks_scan_with_temp(F32, SUM, 1, 1, a, b, 1 << 20, 0x30000000, need - 1, None) == ks.KS_ERR_WORKSPACE
+    assert lib.ks_scan_with_temp(F32, SUM, 1, 1, a, b, 1 << 20, 0x30000010, need, None) == ks.KS_ERR_WORKSPACE
+    assert lib.ks_scan_with_temp(F32, SUM, 1, 7, a, b, 1 << 20, 0x30000000, need, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan_with_temp(F32, SUM, 1, 1, None, None, 0, None, 0, None) == ks.KS_OK
+    assert lib.ks_copy(a, a + 16, 64, None) == ks.KS_ERR_OVERLAP
+    assert lib.ks_copy(a, b, 60, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_copy(None, None, 0, None) == ks.KS_OK
+
+
+def test_temp_bytes_grow_with_n_and_cover_both_strategies(ks):
+    for dt, op in [("f32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count")]:
+        last = 0
+        for k in range(10, 31, 4):
+            lb = ks.ks_scan_temp_bytes(dtype=dt, op=op, n=1 << k, algo="lookback")
+            rts = ks.ks_scan_temp_bytes(dtype=dt, op=op, n=1 << k, algo="reduce_then_scan")
+            auto = ks.ks_scan_temp_bytes(dtype=dt, op=op, n=1 << k)
+            assert lb % 256 == 0 and rts % 256 == 0 and lb >= 256 and rts >= 256
+            assert auto in (lb, rts)
+            assert lb >= last
+            last = lb
+    assert ks.raw_library().ks_scan_temp_bytes(99, 0, 0, 100) == 0
+
+
+def test_options_are_validated(ks):
+    assert ks.ks_get_option("spin_limit") > 0
+    ks.ks_set_option("rows", 8)
+    assert ks.ks_get_option("rows") == 8
+    ks.ks_set_option("rows", 0)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("rows", 3)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("no_such_option", 1)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("grid_mode", 5)
+    assert ks.ks_get_option("no_such_option") == -1
+
+
+def test_status_strings(ks):
+    lib = ks.raw_library()
+    seen = {lib.ks_status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8
+    assert b"gfx950" in lib.ks_version()

@@ -1,0 +1,250 @@
+"""GPU parity: the HIP library, called through its C ABI, against the sequential CPU oracle on the
+same seeded inputs.  Bars are in tests/parity.py (bit-exact integers / structs, 1e-4 relative +
+1e-3 absolute for floating point against the fp64 oracle)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import ks_inputs
+import oracle
+from parity import KINDS, assert_matches, random_input, reference, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2603_18695_amd as ks
+    yield ks
+    for name, v in [("rows", 0), ("prefetch", -1), ("grid_mode", 0), ("wgs_per_cu", 0), ("spin_limit", 1 << 20)]:
+        ks.ks_set_option(name, v)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def tile_elems(ks, dtype, rows=4):
+    return 256 * rows * (16 // ks.ks_elem_bytes(dtype))
+
+
+def run(ks, dtype, op, x, inclusive=True, algo="auto", api="with_temp", in_place=False):
+    d_in = to_device(x)
+    d_out = d_in if in_place else torch.empty_like(d_in)
+    n = len(x)
+    if api == "plain":
+        ks.ks_scan(d_in, d_out, dtype=dtype, op=op, inclusive=inclusive)
+    else:
+        nbytes = ks.ks_scan_temp_bytes(dtype=dtype, op=op, n=n, algo=algo)
+        temp = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        temp.fill_(0xAB)   # previous contents must not matter
+        ks.ks_scan_with_temp(d_in, d_out, temp, dtype=dtype, op=op, inclusive=inclusive, algo=algo)
+    ks.ks_scan_check()
+    return to_host(d_out, x.dtype)
+
+
+def edge_sizes(tile):
+    s = {1, 2, 3, 63, 64, 65, 255, 256, 257, 1023, 1025, tile - 1, tile, tile + 1, 2 * tile + 17,
+         64 * tile - 1, 64 * tile, 64 * tile + 1, 65 * tile + 3, 130 * tile + 777}
+    return sorted(s)
+
+
+ALL_PAIRS = sorted(KINDS)
+
+
+@pytest.mark.parametrize("dtype,op", ALL_PAIRS)
+def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
+    tile = tile_elems(ks, dtype)
+    for n in edge_sizes(tile):
+        x = random_input(dtype, op, n, seed=1000 + n % 97)
+        for inclusive in (True, False):
+            ref = reference(dtype, op, x, inclusive)
+            for algo in ("lookback", "reduce_then_scan", "auto"):
+                say(f"[case] pair=({dtype},{op}) n={n} inclusive={inclusive} algo={algo} api=with_temp")
+                got = run(ks, dtype, op, x, inclusive, algo)
+                assert_matches(dtype, op, got, ref, f"({dtype},{op}) n={n} incl={inclusive} {algo}")
+
+
+@pytest.mark.parametrize("dtype,op", [("i32", "sum"), ("f32", "sum"), ("u64", "sum"),
+                                      ("affine_f32", "affine_compose"), ("argmax_i32_cnt64", "argmax_count"),
+                                      ("mat2_u32", "mat2_mul")])
+def test_library_owned_workspace_back_to_back(ks, dtype, op):
+    # ks_scan: epoch-tagged descriptors reused call after call, sizes going up and down
+    tile = tile_elems(ks, dtype)
+    for n in [300 * tile + 5, 7 * tile, 1000 * tile + 1, 3, 2 * tile, 999 * tile + 63]:
+        x = random_input(dtype, op, n, seed=n % 1013)
+        for inclusive in (True, False):
+            say(f"[case] pair=({dtype},{op}) n={n} inclusive={inclusive} api=plain")
+            got = run(ks, dtype, op, x, inclusive, api="plain")
+            assert_matches(dtype, op, got, reference(dtype, op, x, inclusive), f"plain ({dtype},{op}) n={n}")
+
+
+def test_closed_forms_on_the_gpu(ks):
+    n = (1 << 22) + 12345
+    say("[case] all-ones int32 / uint64 / f32, iota uint64")
+    ones = np.ones(n, dtype=np.int32)
+    assert np.array_equal(run(ks, "i32", "sum", ones), np.arange(1, n + 1, dtype=np.int32))
+    got = run(ks, "u64", "sum", np.ones(n, dtype=np.uint64), inclusive=False)
+    assert np.array_equal(got, np.arange(0, n, dtype=np.uint64))
+    # float32 all-ones is exact while the running sum stays below 2^24
+    got = run(ks, "f32", "sum", np.ones(n, dtype=np.float32))
+    assert np.array_equal(got, np.arange(1, n + 1, dtype=np.float32))
+    i = np.arange(n, dtype=np.uint64)
+    assert np.array_equal(run(ks, "u64", "sum", i), i * (i + 1) // 2)
+    # wrap-around: all INT32_MAX
+    big = np.full(n, np.iinfo(np.int32).max, dtype=np.int32)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(run(ks, "i32", "sum", big), np.cumsum(big, dtype=np.int32))
+
+
+def test_operand_order_is_kept_at_every_level(ks):
+    # Fibonacci matrices: any swapped pair of operands or dropped element breaks the closed form
+    n = 70 * 1024 + 5
+    say("[case] mat2 Fibonacci closed form, mat2 upper/lower triangular alternation")
+    x = np.tile(np.array([[1, 1, 1, 0]], dtype=np.uint32), (n, 1))
+    got = run(ks, "mat2_u32", "mat2_mul", x, algo="lookback")
+    a, b = 1, 0    # F(1), F(0)
+    m = (1 << 32) - 1
+    for k in range(1, n + 1):
+        a, b = (a + b) & m, a          # a = F(k+1), b = F(k)
+        if k % 1009 == 0 or k == n:
+            assert got[k - 1].tolist() == [a, b, b, (a - b) & m], k
+    # alternating non-commuting factors against the oracle, both strategies
+    y = np.where((np.arange(n) % 2 == 0)[:, None], np.array([[1, 1, 0, 1]]), np.array([[1, 0, 1, 1]])).astype(np.uint32)
+    ref = reference("mat2_u32", "mat2_mul", y, True)
+    for algo in ("lookback", "reduce_then_scan"):
+        assert_matches("mat2_u32", "mat2_mul", run(ks, "mat2_u32", "mat2_mul", y, algo=algo), ref, algo)
+
+
+def test_in_place_and_misaligned_pointers(ks):
+    for dtype, op in [("i32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
+        tile = tile_elems(ks, dtype)
+        n = 37 * tile + 11
+        x = random_input(dtype, op, n, seed=5)
+        ref = reference(dtype, op, x, True)
+        say(f"[case] in-place ({dtype},{op}) n={n}")
+        assert_matches(dtype, op, run(ks, dtype, op, x, in_place=True, algo="lookback"), ref, "in place lookback")
+        assert_matches(dtype, op, run(ks, dtype, op, x, in_place=True, algo="reduce_then_scan"), ref, "in place rts")
+        # element-aligned but not 16-byte aligned: slices that start one element in
+        say(f"[case] misaligned ({dtype},{op}) n={n - 1}")
+        d_all = to_device(x)
+        d_in = d_all[1:]
+        d_out_all = torch.empty_like(d_all)
+        d_out = d_out_all[1:]
+        if ks.ks_elem_bytes(dtype) < 16:
+            assert d_in.data_ptr() % 16 != 0
+        for algo in ("lookback", "reduce_then_scan"):
+            temp = torch.empty(ks.ks_scan_temp_bytes(dtype=dtype, op=op, n=n - 1, algo=algo), dtype=torch.uint8, device="cuda")
+            ks.ks_scan_with_temp(d_in.contiguous() if not d_in.is_contiguous() else d_in, d_out, temp,
+                                 dtype=dtype, op=op, algo=algo)
+            ks.ks_scan_check()
+            assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
+
+
+@pytest.mark.parametrize("rows", [2, 4, 8])
+@pytest.mark.parametrize("prefetch", [0, 1])
+def test_lookback_variants(ks, rows, prefetch):
+    ks.ks_set_option("rows", rows)
+    ks.ks_set_option("prefetch", prefetch)
+    try:
+        for dtype, op in [("f32", "sum"), ("i32", "sum"), ("u64", "sum"), ("affine_f32", "affine_compose"),
+                          ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
+            tile = tile_elems(ks, dtype, rows)
+            for n in [tile * 5000 + 3, tile * 64 + 1]:
+                x = random_input(dtype, op, n, seed=rows * 10 + prefetch)
+                for inclusive in (True, False):
+                    say(f"[case] rows={rows} prefetch={prefetch} ({dtype},{op}) n={n} incl={inclusive}")
+                    got = run(ks, dtype, op, x, inclusive, algo="lookback")
+                    assert_matches(dtype, op, got, reference(dtype, op, x, inclusive), f"rows={rows} pf={prefetch}")
+    finally:
+        ks.ks_set_option("rows", 0)
+        ks.ks_set_option("prefetch", -1)
+
+
+def test_repeated_launches_give_identical_integer_results(ks):
+    # race hunt: same input many times, small resident grid and full grid, exact compare each time
+    n = (1 << 24) + 4099
+    x = ks_inputs.whole("int32_sum", n)
+    ref = reference("i32", "sum", x, True)
+    d_in = to_device(x)
+    d_out = torch.empty_like(d_in)
+    d_ref = to_device(ref)
+    for wgs in (0, 1, 3):
+        ks.ks_set_option("wgs_per_cu", wgs)
+        for it in range(25):
+            if it % 8 == 0:
+                say(f"[case] repeat int32 sum n={n} wgs_per_cu={wgs} iteration={it}")
+            d_out.zero_()
+            ks.ks_scan(d_in, d_out, dtype="i32", op="sum")
+            assert torch.equal(d_out, d_ref), (wgs, it)
+    ks.ks_set_option("wgs_per_cu", 0)
+    ks.ks_scan_check()
+
+
+# ---------------------------------------------------------------- the five benchmark configurations, full size
+
+def _full_config(ks, name, n=None, api="plain", algo="auto"):
+    """Stream the workload to the device chunk by chunk, scan it in one call, compare chunk by chunk."""
+    w = ks_inputs.WORKLOADS[name]
+    n = w.n if n is None else n
+    oop, odt, npdt, cols = KINDS[(w.dtype, w.op)]
+    host_cols = 4 if npdt == oracle.ARGMAX_DTYPE else cols
+    tdt = {np.dtype(np.int32): torch.int32, np.dtype(np.float32): torch.float32,
+           np.dtype(np.uint64): torch.int64}.get(np.dtype(npdt), torch.int32)
+    shape = (n,) if host_cols == 1 else (n, host_cols)
+    d_in = torch.empty(shape, dtype=tdt, device="cuda")
+    at = 0
+    for chunk in ks_inputs.chunks(name, n):
+        d_in[at:at + len(chunk)] = to_device(chunk)
+        at += len(chunk)
+    d_out = torch.empty_like(d_in)
+    say(f"[case] workload={name} n={n} api={api} algo={algo}")
+    if api == "plain":
+        ks.ks_scan(d_in, d_out, dtype=w.dtype, op=w.op, inclusive=w.inclusive)
+    else:
+        temp = torch.empty(ks.ks_scan_temp_bytes(dtype=w.dtype, op=w.op, n=n, algo=algo), dtype=torch.uint8, device="cuda")
+        ks.ks_scan_with_temp(d_in, d_out, temp, dtype=w.dtype, op=w.op, inclusive=w.inclusive, algo=algo)
+    ks.ks_scan_check()
+    stream = oracle.ScanStream(oop, odt, w.inclusive)
+    worst, at = 0.0, 0
+    for chunk in ks_inputs.chunks(name, n):
+        ref = stream.feed(chunk)
+        got = to_host(d_out[at:at + len(chunk)], chunk.dtype)
+        worst = max(worst, assert_matches(w.dtype, w.op, got, ref, f"{name} n={n} chunk at {at}"))
+        at += len(chunk)
+    say(f"[done] workload={name} n={n}: worst float ratio {worst:.4f}")
+    return worst
+
+
+def test_config_int32_sum_2_20(ks):
+    _full_config(ks, "int32_sum")
+    _full_config(ks, "int32_sum", api="with_temp", algo="lookback")
+    _full_config(ks, "int32_sum", api="with_temp", algo="reduce_then_scan")
+
+
+def test_config_f32_sum_2_28(ks):
+    assert _full_config(ks, "f32_sum") <= 1.0
+    assert _full_config(ks, "f32_sum", api="with_temp", algo="reduce_then_scan") <= 1.0
+
+
+def test_config_u64_exclusive_sum_2_27(ks):
+    _full_config(ks, "u64_exsum")
+    _full_config(ks, "u64_exsum", api="with_temp", algo="reduce_then_scan")
+
+
+def test_config_affine_2_26(ks):
+    assert _full_config(ks, "affine") <= 1.0
+    assert _full_config(ks, "affine", api="with_temp", algo="reduce_then_scan") <= 1.0
+
+
+@pytest.mark.parametrize("log2n", list(range(10, 29, 2)))
+def test_config_argmax_struct_sweep(ks, log2n):
+    _full_config(ks, "argmax", n=1 << log2n)
+    _full_config(ks, "argmax", n=1 << log2n, api="with_temp", algo="reduce_then_scan")
+
+
+def test_config_argmax_struct_2_30(ks):
+    _full_config(ks, "argmax", n=1 << 30)
