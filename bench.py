@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the device-wide scan on one MI355X.
+
+A step is one pass of the whole hot path (one ks_scan call: load, register scan, wave scan, LDS
+exchange, look-back, store) over one batch of synthetic input that is already resident in HBM.
+Default workload: BASELINE's headline configuration, inclusive float32 sum scan of n = 2^28
+values uniform in [0, 1) from seed 1.  Prints ONE JSON line on stdout; everything else goes to
+stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="f32_sum")
+    ap.add_argument("--n", type=int, default=0)
+    ap.add_argument("--algo", default="auto", choices=["auto", "lookback", "reduce_then_scan"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (cpu_baseline = null)")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the scan's cross-GPU sharding is a design note, "
+            "not code); run with --gpus 1")
+        return 2
+
+    import torch
+    import ks_inputs
+    import paper_2603_18695_amd as ks
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the scan has no CPU fallback")
+        return 2
+    torch.cuda.set_device(0)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        ks.ks_set_option(k, int(v))
+
+    w = ks_inputs.WORKLOADS[args.workload]
+    n = args.n or (w.n if args.workload != "argmax" else 1 << 26)
+    eb = w.elem_bytes
+    algorithmic_bytes = 2 * n * eb                      # every element read once and written once
+
+    # ---- inputs: generated on the host from the seeded recipe, then resident in HBM
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import KINDS, to_device, to_host, assert_matches
+    t0 = time.time()
+    host_chunks = list(ks_inputs.chunks(args.workload, n))
+    d_in = torch.cat([to_device(c) for c in host_chunks])
+    d_out = torch.empty_like(d_in)
+    temp = torch.empty(ks.ks_scan_temp_bytes(dtype=w.dtype, op=w.op, n=n, algo=args.algo), dtype=torch.uint8,
+                       device="cuda")
+    log(f"inputs: workload={args.workload} n={n} ({n * eb / 2**20:.0f} MiB each way) generated in {time.time() - t0:.1f}s")
+
+    def step():
+        if args.algo == "auto":
+            ks.ks_scan(d_in, d_out, dtype=w.dtype, op=w.op, inclusive=w.inclusive)
+        else:
+            ks.ks_scan_with_temp(d_in, d_out, temp, dtype=w.dtype, op=w.op, inclusive=w.inclusive, algo=args.algo)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ks.ks_scan_check()
+
+    # ---- timed region: exactly K steps, sync on both sides; HIP events on the launch stream
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ks.ks_scan_check()
+    wall_ms = (t_end - t_start) * 1e3 / args.steps
+    event_ms = ev0.elapsed_time(ev1) / args.steps
+    gbs_wall = algorithmic_bytes / (wall_ms * 1e-3) / 1e9
+    gbs_event = algorithmic_bytes / (event_ms * 1e-3) / 1e9
+    log(f"scan: {wall_ms:.4f} ms/step wall, {event_ms:.4f} ms/step by HIP events -> {gbs_event:.1f} GB/s "
+        f"({100 * gbs_event / HBM_PEAK_GBS:.1f}% of {HBM_PEAK_GBS:.0f} GB/s)")
+
+    # ---- copy kernel on the same bytes: the practical ceiling (context, not the metric)
+    for _ in range(5):
+        ks.ks_copy(d_in, d_out)
+    torch.cuda.synchronize()
+    c0 = torch.cuda.Event(enable_timing=True)
+    c1 = torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(50):
+        ks.ks_copy(d_in, d_out)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_ms = c0.elapsed_time(c1) / 50
+    copy_gbs = algorithmic_bytes / (copy_ms * 1e-3) / 1e9
+    log(f"copy ceiling: {copy_ms:.4f} ms -> {copy_gbs:.1f} GB/s")
+
+    # ---- oracle leg: the sequential CPU scan on this host, one core, and a parity check of the
+    #      result the timed configuration produced
+    cpu = None
+    parity = None
+    if not args.no_cpu:
+        import oracle
+        step()
+        torch.cuda.synchronize()
+        oop, odt, _, _ = KINDS[(w.dtype, w.op)]
+        budget_elems = min(n, 1 << 28)
+        stream = oracle.ScanStream(oop, odt, w.inclusive)
+        cpu_s, done, at, worst = 0.0, 0, 0, 0.0
+        for c in host_chunks:
+            if done >= budget_elems:
+                break
+            t = time.perf_counter()
+            ref = stream.feed(c)
+            cpu_s += time.perf_counter() - t
+            got = to_host(d_out[at:at + len(c)], c.dtype)
+            worst = max(worst, assert_matches(w.dtype, w.op, got, ref, f"bench parity at {at}"))
+            at += len(c)
+            done += len(c)
+        parity = {"checked_elements": done, "worst_float_ratio": worst}
+        cpu_gbs = 2 * done * eb / cpu_s / 1e9
+        cpu = {"value": cpu_gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {done} elements of the same workload, sequential C left fold (fp64 accumulator "
+                         f"for float inputs), {cpu_s:.2f} s on {os.cpu_count()} visible host cpus, 1 thread used",
+               "elements_per_s": done / cpu_s}
+        log(f"oracle: {done} elements in {cpu_s:.2f}s -> {cpu_gbs:.2f} GB/s on 1 core; parity ok (worst ratio {worst:.3f})")
+
+    result = {
+        "metric": "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X" if args.workload == "f32_sum" and n == 1 << 28
+                  else f"scan GB/s (read+write), workload {args.workload} n={n}, 1 MI355X",
+        "value": gbs_wall,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64"}[args.workload],
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
+                               f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb,
+                   "options": {k: ks.ks_get_option(k) for k in ["rows", "prefetch", "grid_mode", "wgs_per_cu"]}},
+        "elements_per_s": n / (wall_ms * 1e-3),
+        "pct_of_hbm_peak": 100 * gbs_wall / HBM_PEAK_GBS,
+        "copy_ceiling_gbs": copy_gbs,
+        "roofline": {"bound": "hbm", "achieved": gbs_event, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs_event / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms": event_ms, "algorithmic_bytes": algorithmic_bytes},
+        "cpu_baseline": cpu,
+        "parity": parity,
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -82,6 +82,10 @@ typedef enum {
  * Uses a library-owned workspace cached per (device, stream); the first call on
  * a stream, or a call needing a larger workspace, allocates device memory (and
  * must therefore not be made under stream capture: use ks_scan_with_temp there).
+ * The first look-back launch of each kernel variant (dtype, op, inclusive and
+ * tuning options) also runs a short residency check that synchronises the
+ * stream; this holds for ks_scan_with_temp too, so warm a variant up once
+ * before capturing it into a graph.
  * Back-to-back calls on one stream are safe; calls on different streams use
  * different workspaces.  inclusive: non-zero = inclusive, 0 = exclusive.
  */
@@ -129,6 +133,9 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
  *                  workgroup per tile, which is only deadlock-free if the hardware
  *                  starts workgroups in index order (experimental; waits stay bounded)
+ *   "last_grid", "last_resident_per_cu"   read-only: grid of the most recent look-back
+ *                  launch and the verified number of resident workgroups per compute
+ *                  unit of its kernel variant
  * Returns KS_OK or KS_ERR_INVALID_ARG.  ks_get_option returns the value or -1.
  */
 int ks_set_option(const char *name, long long value);

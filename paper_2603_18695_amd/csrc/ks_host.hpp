@@ -16,6 +16,8 @@ struct Options {
     long long rows = 0;           // 0 = default for the type
     long long prefetch = -1;      // -1 = default, 0 / 1 forced
     long long grid_mode = 0;      // 0 = persistent resident grid, 1 = one workgroup per tile (experimental)
+    long long last_grid = 0;      // read-only: workgroups of the most recent look-back launch
+    long long last_resident_per_cu = 0;   // read-only: verified resident workgroups per CU of that kernel variant
 };
 Options &options();
 
@@ -23,6 +25,7 @@ struct DeviceInfo {
     int device = -1;
     int cus = 0;
     uint32_t *abort_flag = nullptr;   // device address of the library's abort word on this device
+    uint32_t *residency = nullptr;    // two words used by the one-off residency check of a kernel variant
 };
 
 struct ScanCall {

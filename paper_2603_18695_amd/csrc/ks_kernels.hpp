@@ -34,11 +34,11 @@ __device__ __forceinline__ void desc_store_word(uint64_t *p, uint32_t tag, uint3
 }
 
 template <class T>
-__device__ __forceinline__ void desc_publish(uint64_t *desc, uint32_t tile, uint32_t epoch, uint32_t state,
+__device__ __forceinline__ void desc_publish(uint64_t *desc, size_t entry, uint32_t epoch, uint32_t state,
                                              const T &value) {
     constexpr int W = WordsOf<T>::W;
     auto ws = to_words(value);
-    uint64_t *p = desc + (size_t)tile * W;
+    uint64_t *p = desc + entry * W;
     const uint32_t tag = (epoch << 2) | state;
 #pragma unroll
     for (int k = 0; k < W; ++k) desc_store_word(p + k, tag, ws.w[k]);
@@ -47,9 +47,9 @@ __device__ __forceinline__ void desc_publish(uint64_t *desc, uint32_t tile, uint
 // Returns the state (kUnset if the descriptor is from another epoch or its
 // words do not carry one common tag yet) and the value.
 template <class T>
-__device__ __forceinline__ uint32_t desc_read(const uint64_t *desc, uint32_t tile, uint32_t epoch, T &value) {
+__device__ __forceinline__ uint32_t desc_read(const uint64_t *desc, size_t entry, uint32_t epoch, T &value) {
     constexpr int W = WordsOf<T>::W;
-    const uint64_t *p = desc + (size_t)tile * W;
+    const uint64_t *p = desc + entry * W;
     typename WordsOf<T>::type ws;
     uint32_t tag0 = 0;
     bool same = true;
@@ -65,48 +65,108 @@ __device__ __forceinline__ uint32_t desc_read(const uint64_t *desc, uint32_t til
     return tag0 & 3u;
 }
 
-// Look-back executed by one full wave (paper Sec. V-B, third paragraph; window of
-// 64 predecessors on wave64).  Lane 63 inspects the nearest predecessor and
-// lane 0 the farthest, so lane order is tile order and the ordinary wave scan
-// combines the window with earlier tiles on the left.  Returns false when the
-// spin limit was hit or another workgroup has already given up.
-template <class T, class Op>
-__device__ __forceinline__ bool lookback(const uint64_t *desc, uint32_t tile, uint32_t epoch,
-                                         uint32_t spin_limit, uint32_t *abort_flag, T &exclusive_prefix) {
+// Besides its own descriptor D(t) (PARTIAL: aggregate of tile t; PREFIX:
+// combination of tiles 0..t) every tile has a second one, X(t):
+//     PARTIAL  combination of the 64 tiles before t   (what t's first window gave)
+//     PREFIX   combination of all tiles before t      (t's exclusive prefix)
+// X is stored transposed, X(t) at [(t mod 64) * M + t / 64] with M = ceil(tiles/64),
+// so that X(t-64), X(t-128), ..., X(t-4096) are 64 consecutive entries.  After a
+// first window over D(t-64..t-1) a tile therefore covers 4096 more tiles with
+// one coalesced 64-lane read, instead of walking back 64 tiles per memory round
+// trip.  On this GPU a round trip takes 0.5 us idle and about 2 us while the
+// memory system streams at full rate, and ~2000 tiles are in flight at once:
+// the single-level walk of the paper (Sec. V-B) then advances the prefix more
+// slowly than tiles arrive.  States, tags and the rule "nearest PREFIX ends the
+// search, everything after it must be at least PARTIAL" are unchanged.
+constexpr int kWindow = 64;
+
+__device__ __forceinline__ size_t xdesc_index(uint32_t tile, uint32_t m) {
+    return (size_t)(tile % kWindow) * m + tile / kWindow;
+}
+
+// Bookkeeping of the bounded wait: every failed poll of a look-back wave counts
+// against `limit`; the abort word lets all workgroups stop once one has given up.
+struct SpinState {
+    uint32_t spins;
+    uint32_t limit;
+    uint32_t *abort_flag;
+    uint32_t who;   // tile doing the waiting; the abort word receives who + 1
+};
+
+__device__ __forceinline__ bool spin_once(SpinState &sp) {
+    const int lane = threadIdx.x & (kWave - 1);
+    ++sp.spins;
+    if (sp.spins > sp.limit) {
+        if (lane == 0) __hip_atomic_store(sp.abort_flag, sp.who + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+    }
+    if ((sp.spins & 63u) == 0) {   // has another workgroup given up?  (decided wave-uniformly)
+        const uint32_t f = __hip_atomic_load(sp.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__ballot(f != 0) != 0) return false;
+    }
+    __builtin_amdgcn_s_sleep(1);
+    return true;
+}
+
+// One window: lane l owns entry base + first + l of `desc`, where first may be
+// negative: entries before the start hold nothing (lane order = sequence order,
+// lane 63 nearest).  Waits until the nearest PREFIX in the window and everything
+// after it are visible, or, with no PREFIX in the window, until every lane is.
+// On return `total` is the combination, in order, of the lanes from the nearest
+// PREFIX on (all lanes if there is none) and found_prefix tells which.
+template <class A, class Op>
+__device__ __forceinline__ bool poll_window(const uint64_t *desc, size_t base, long long first, uint32_t epoch,
+                                            SpinState &sp, A &total, bool &found_prefix) {
     const int lane = threadIdx.x & (kWave - 1);
     Op op;
-    T running = Op::identity();              // combination of the windows already consumed (later tiles)
-    long long newest = (long long)tile - 1;  // newest tile of the current window
-    uint32_t spins = 0;
+    const long long mine = first + lane;
+    A val = Op::identity();
+    uint32_t st = (mine >= 0) ? kUnset : kPartial;   // nothing there: counts as an empty aggregate
+    int top;
     for (;;) {
-        const long long mine = newest - (kWave - 1) + lane;
-        T val = Op::identity();
-        uint32_t st = (mine >= 0) ? kUnset : kPartial;   // before tile 0: nothing, counts as an empty aggregate
-        int top;                                          // highest lane holding a PREFIX, -1 if none
-        for (;;) {
-            if (st == kUnset) st = desc_read<T>(desc, (uint32_t)mine, epoch, val);
-            const uint64_t prefix_mask = __ballot(st == kPrefix);
-            const uint64_t unset_mask = __ballot(st == kUnset);
-            top = prefix_mask ? 63 - __builtin_clzll(prefix_mask) : -1;
-            const uint64_t needed = (top >= 63) ? 0ull : (~0ull << (top + 1));   // lanes above the nearest PREFIX
-            if ((unset_mask & needed) == 0) break;
-            ++spins;
-            if (spins > spin_limit) {
-                if (lane == 0) __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                return false;
-            }
-            if ((spins & 63u) == 0) {   // has another workgroup given up?  (decided wave-uniformly)
-                const uint32_t f = __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (__ballot(f != 0) != 0) return false;
-            }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if (lane < top) val = Op::identity();   // tiles already covered by the PREFIX found
-        const T window = read_lane(wave_inclusive_scan(val, op), kWave - 1);
-        running = op(window, running);
-        if (top >= 0) break;
-        newest -= kWave;
+        if (st == kUnset) st = desc_read<A>(desc, base + (size_t)mine, epoch, val);
+        const uint64_t prefix_mask = __ballot(st == kPrefix);
+        const uint64_t unset_mask = __ballot(st == kUnset);
+        top = prefix_mask ? 63 - __builtin_clzll(prefix_mask) : -1;
+        const uint64_t needed = (top >= 63) ? 0ull : (~0ull << (top + 1));   // lanes after the nearest PREFIX
+        if ((unset_mask & needed) == 0) break;
+        if (!spin_once(sp)) return false;
     }
+    if (lane < top) val = Op::identity();   // already covered by the PREFIX found
+    total = read_lane(wave_inclusive_scan(val, op), kWave - 1);
+    found_prefix = top >= 0;
+    return true;
+}
+
+// Look-back executed by one full wave (paper Sec. V-B, third paragraph; window of
+// 64 descriptors on wave64).  Returns false when the spin limit was hit or
+// another workgroup gave up; otherwise exclusive_prefix = combination of all
+// tiles before `tile`, and X(tile) has been published in state PREFIX.
+template <class A, class Op>
+__device__ __forceinline__ bool lookback(const uint64_t *desc, uint64_t *xdesc, uint32_t m, uint32_t tile,
+                                         uint32_t epoch, uint32_t spin_limit, uint32_t *abort_flag,
+                                         A &exclusive_prefix) {
+    const int lane = threadIdx.x & (kWave - 1);
+    Op op;
+    SpinState sp{0u, spin_limit, abort_flag, tile};
+    const size_t my_x = xdesc_index(tile, m);
+    A running;
+    bool done;
+    // first window: D of the 64 tiles before this one
+    if (!poll_window<A, Op>(desc, 0, (long long)tile - kWindow, epoch, sp, running, done)) return false;
+    if (!done) {
+        // tell later tiles what these 64 tiles add up to, then walk X(tile - 64), X(tile - 128), ...
+        if (lane == 0) desc_publish<A>(xdesc, my_x, epoch, kPartial, running);
+        const size_t row = (size_t)(tile % kWindow) * m;
+        long long first = (long long)(tile / kWindow) - kWindow;   // window = entries first .. first+63 of the row
+        while (!done) {
+            A window;
+            if (!poll_window<A, Op>(xdesc, row, first, epoch, sp, window, done)) return false;
+            running = op(window, running);
+            first -= kWindow;
+        }
+    }
+    if (lane == 0) desc_publish<A>(xdesc, my_x, epoch, kPrefix, running);
     exclusive_prefix = running;
     return true;
 }
@@ -141,20 +201,52 @@ __device__ __forceinline__ size_t lane_first_element(uint32_t tile) {
     return (size_t)tile * (kWaves * S::WAVE_ELEMS) + (size_t)wave * S::WAVE_ELEMS + (size_t)lane * S::G;
 }
 
+// Do all workgroups of this launch run at the same time?  Each one counts itself
+// in residency[0] and waits, bounded, for the count to reach the grid size; a
+// workgroup that gives up sets residency[1].  Every wave of the workgroup stays
+// alive at the closing barrier until its thread 0 is done, so the workgroup
+// holds all of its registers and wave slots while it is counted.  The host uses
+// this once per kernel variant to size the persistent grid: the occupancy the
+// runtime reports can be higher than what the hardware grants (observed here: 8
+// workgroups per compute unit reported, 7 granted, for kernels with more than
+// 80 scalar registers), and a persistent grid larger than the resident set
+// would never finish its second round.
+__device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t spin_limit) {
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(&residency[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (uint32_t spins = 0;; ++spins) {
+            if (__hip_atomic_load(&residency[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x) break;
+            if (spins >= spin_limit ||
+                __hip_atomic_load(&residency[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                __hip_atomic_store(&residency[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------------------
 // Single-pass scan.  The grid is persistent: workgroup b handles tiles b,
 // b + gridDim.x, ... in increasing order, and the host launches no more
 // workgroups than can be resident at once, so the tile a workgroup waits for is
 // always owned by a workgroup that is running (the paper does not say how tiles
 // are assigned; this removes any reliance on dispatch order without a ticket
-// atomic per tile).  Every wait is bounded by spin_limit.
+// atomic per tile: one device-scope atomic on a single address costs 12 ns here,
+// more than a tile's share of the run time).  Every wait is bounded by spin_limit.
 // IO = element type in memory, Op::acc = type of registers and descriptors.
 // ---------------------------------------------------------------------------
 template <class IO, class Op, int ROWS, bool INCLUSIVE, bool PREFETCH>
 __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
-                                                               size_t n, uint64_t *desc, uint32_t epoch,
-                                                               uint32_t ntiles, uint32_t spin_limit,
-                                                               uint32_t *abort_flag, int aligned) {
+                                                               size_t n, uint64_t *desc, uint64_t *xdesc,
+                                                               uint32_t epoch, uint32_t ntiles,
+                                                               uint32_t spin_limit, uint32_t *abort_flag,
+                                                               int aligned, uint32_t *residency) {
+    if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
+        residency_check(residency, spin_limit);
+        return;
+    }
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     using Items = ThreadItems<A, ROWS, S::G>;
@@ -168,6 +260,7 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
 
     uint32_t tile = blockIdx.x;
     if (tile >= ntiles) return;
+    const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
     Items cur;
     {
         const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
@@ -180,7 +273,10 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
         const A wave_carry = exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
 
         // publish as early as possible: successors only need the aggregate
-        if (threadIdx.x == 0) desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+        if (threadIdx.x == 0) {
+            desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+            if (tile == 0) desc_publish<A>(xdesc, 0, epoch, kPrefix, Op::identity());   // nothing before tile 0
+        }
 
         const uint32_t next = tile + gridDim.x;
         Items nxt;
@@ -193,7 +289,7 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
             A excl = Op::identity();
             bool ok = true;
             if (tile != 0) {
-                ok = lookback<A, Op>(desc, tile, epoch, spin_limit, abort_flag, excl);
+                ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
                 if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
             }
             if (lane == 0) {

@@ -26,6 +26,8 @@ struct Pair {
 
     static size_t tile_elems(int rows) { return (size_t)kWaves * kWave * rows * (16 / sizeof(T)); }
 
+    static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
+
     static int lookback_rows() {
         const long long r = options().rows;
         return (r == 2 || r == 4 || r == 8) ? (int)r : PairDefaults<T>::rows;
@@ -47,7 +49,7 @@ struct Pair {
             // sized for the smallest tile any compiled variant uses, so a later change of the
             // "rows" option cannot outgrow a buffer sized earlier
             const size_t tiles = ceil_div(n, tile_elems(2));
-            return align_up((tiles > 0 ? tiles : 1) * W * sizeof(uint64_t), 256);
+            return desc_bytes(tiles) + desc_bytes(ceil_div(tiles, kWindow) * kWindow);
         }
         size_t total = 0, m = n;
         const size_t tile = tile_elems(kRtsRows);
@@ -64,22 +66,45 @@ struct Pair {
     static int launch_lookback(const ScanCall &c, int aligned) {
         auto kernel = scan_lookback_kernel<T, Op, ROWS, INCLUSIVE, PREFETCH>;
         const size_t tiles = ceil_div(c.n, tile_elems(ROWS));
-        if (tiles * W * sizeof(uint64_t) > c.temp_bytes) return KS_ERR_WORKSPACE;
-        static int per_cu = 0;   // resident workgroups per compute unit for this variant
+        const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
+        if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
+        static int per_cu = 0;   // resident workgroups per compute unit for this variant, as verified below
         if (per_cu == 0) {
             int nb = 0;
             hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kBlock, 0);
             if (e != hipSuccess) return set_hip_error(e);
-            if (nb < 1) return KS_ERR_WORKSPACE;
-            per_cu = nb;
+            // The query is an upper bound only; run the kernel in its residency-check mode and
+            // step down until every workgroup of the grid is seen running at once.  One-off per
+            // variant and device; it synchronises the stream.
+            int verified = 0;
+            for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
+                uint32_t zero[2] = {0u, 0u};
+                e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
+                if (e != hipSuccess) return set_hip_error(e);
+                hipLaunchKernelGGL(kernel, dim3((unsigned)(tryb * c.dev->cus)), dim3(kBlock), 0, c.stream,
+                                   static_cast<const T *>(nullptr), static_cast<T *>(nullptr), (size_t)0,
+                                   static_cast<uint64_t *>(nullptr), static_cast<uint64_t *>(nullptr), 0u, 0u,
+                                   (uint32_t)(1u << 16), c.dev->abort_flag, 0, c.dev->residency);
+                if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
+                uint32_t seen[2] = {0u, 1u};
+                e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
+                if (e != hipSuccess) return set_hip_error(e);
+                if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
+                if (seen[1] == 0u) verified = tryb;
+            }
+            if (verified < 1) return KS_ERR_WORKSPACE;
+            per_cu = verified;
         }
         long long want = options().wgs_per_cu;
         int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
         size_t grid = (size_t)use * (size_t)c.dev->cus;
         if (options().grid_mode == 1 || grid > tiles) grid = tiles;
+        options().last_grid = (long long)grid;
+        options().last_resident_per_cu = per_cu;
         uint64_t *desc = static_cast<uint64_t *>(c.temp);
+        uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
         if (c.clear_descriptors) {
-            const size_t words = tiles * W;
+            const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
             const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
             hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
         }
@@ -87,8 +112,8 @@ struct Pair {
         if (spin < 0) spin = 0;
         if (spin > 0xffffffffll) spin = 0xffffffffll;
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
-                           static_cast<T *>(c.out), c.n, desc, c.epoch, (uint32_t)tiles, (uint32_t)spin,
-                           c.dev->abort_flag, aligned);
+                           static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch, (uint32_t)tiles, (uint32_t)spin,
+                           c.dev->abort_flag, aligned, static_cast<uint32_t *>(nullptr));
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
     }

@@ -15,6 +15,8 @@ namespace ks {
 
 // Set by a look-back wave that exhausted its spin limit; one word per device.
 __device__ uint32_t g_abort_flag;
+// {workgroups counted, gave-up flag} of a residency check.
+__device__ uint32_t g_residency[2];
 
 const PairEntry *pair_entry_i32(int, int);
 const PairEntry *pair_entry_i64(int, int);
@@ -68,6 +70,9 @@ int device_info(const DeviceInfo **out) {
         e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_abort_flag));
         if (e != hipSuccess) return set_hip_error(e);
         d.abort_flag = static_cast<uint32_t *>(p);
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_residency));
+        if (e != hipSuccess) return set_hip_error(e);
+        d.residency = static_cast<uint32_t *>(p);
         it = g_devices.emplace(dev, d).first;
     }
     *out = &it->second;
@@ -187,6 +192,8 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "rows")) return &o.rows;
     if (!std::strcmp(name, "prefetch")) return &o.prefetch;
     if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
+    if (!std::strcmp(name, "last_grid")) return &o.last_grid;
+    if (!std::strcmp(name, "last_resident_per_cu")) return &o.last_resident_per_cu;
     return nullptr;
 }
 
@@ -194,6 +201,7 @@ int ks_set_option(const char *name, long long value) {
     long long *slot = option_slot(name);
     if (!slot) return KS_ERR_INVALID_ARG;
     Options &o = options();
+    if (slot == &o.last_grid || slot == &o.last_resident_per_cu) return KS_ERR_INVALID_ARG;   // read-only
     if (slot == &o.rows && !(value == 0 || value == 2 || value == 4 || value == 8)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
