@@ -26,6 +26,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 
+def measured_traffic(workload: str, n: int):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, for the
+    headline configuration only (None for anything else, or when the summary is absent)."""
+    if workload != "f32_sum" or n != 1 << 28:
+        return None
+    path = os.path.join(ROOT, "profiles", "scan_lookback_f32_sum_2p28_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -170,7 +185,8 @@ def main() -> int:
         "pct_of_hbm_peak": 100 * gbs_wall / HBM_PEAK_GBS,
         "copy_ceiling_gbs": copy_gbs,
         "roofline": {"bound": "hbm", "achieved": gbs_event, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs_event / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gbs_event / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(args.workload, n) if args.algo == "auto" and not args.opt else None,
                      "kernel_ms": event_ms, "algorithmic_bytes": algorithmic_bytes},
         "cpu_baseline": cpu,
         "parity": parity,

@@ -127,7 +127,7 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid
  *                  (0 = what the occupancy query allows; values above it are clamped)
  *   "rows"         16-byte vectors per thread in the look-back kernel (0 = default;
- *                  only the compiled values 2, 4, 8 are accepted)
+ *                  only the compiled values 2, 4, 8, 16 are accepted)
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one

@@ -11,10 +11,15 @@ namespace ks {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 
-template <class T>
+// Measured on MI355X for every element size: the largest compiled tile with the
+// next tile prefetched wins (fewer tiles, fewer look-backs, longer streams
+// between synchronisations), even though it leaves only 2 workgroups per
+// compute unit resident.  Types whose accumulator is wider than the element in
+// memory run out of registers earlier and stop at 8 rows.
+template <class T, class A>
 struct PairDefaults {
-    static constexpr int rows = 4;
-    static constexpr bool prefetch = false;
+    static constexpr int rows = sizeof(A) > sizeof(T) ? 8 : 16;
+    static constexpr bool prefetch = true;
 };
 
 // T = element type in memory; A = Op::acc = type of aggregates, seeds and descriptors.
@@ -30,11 +35,11 @@ struct Pair {
 
     static int lookback_rows() {
         const long long r = options().rows;
-        return (r == 2 || r == 4 || r == 8) ? (int)r : PairDefaults<T>::rows;
+        return (r == 2 || r == 4 || r == 8 || r == 16) ? (int)r : PairDefaults<T, A>::rows;
     }
     static bool lookback_prefetch() {
         const long long p = options().prefetch;
-        return p < 0 ? PairDefaults<T>::prefetch : p != 0;
+        return p < 0 ? PairDefaults<T, A>::prefetch : p != 0;
     }
 
     static ks_algo pick_algo(size_t n) {
@@ -129,8 +134,9 @@ struct Pair {
     static int run_lookback(const ScanCall &c, int aligned) {
         switch (lookback_rows()) {
             case 2: return lookback_rows_dispatch<2>(c, aligned);
-            case 8: return lookback_rows_dispatch<8>(c, aligned);
-            default: return lookback_rows_dispatch<4>(c, aligned);
+            case 4: return lookback_rows_dispatch<4>(c, aligned);
+            case 16: return lookback_rows_dispatch<16>(c, aligned);
+            default: return lookback_rows_dispatch<8>(c, aligned);
         }
     }
 

@@ -27,8 +27,16 @@ def say(msg):
     sys.stdout.flush()
 
 
-def tile_elems(ks, dtype, rows=4):
+def tile_elems(ks, dtype, rows):
     return 256 * rows * (16 // ks.ks_elem_bytes(dtype))
+
+
+def default_rows(dtype):
+    # library defaults: 16 sixteen-byte rows per thread, 8 where the accumulator is wider than the element
+    return 8 if dtype == "affine_f32" else 16
+
+
+RTS_ROWS = 4   # tile of the reduce-then-scan kernels
 
 
 def run(ks, dtype, op, x, inclusive=True, algo="auto", api="with_temp", in_place=False):
@@ -46,9 +54,11 @@ def run(ks, dtype, op, x, inclusive=True, algo="auto", api="with_temp", in_place
     return to_host(d_out, x.dtype)
 
 
-def edge_sizes(tile):
-    s = {1, 2, 3, 63, 64, 65, 255, 256, 257, 1023, 1025, tile - 1, tile, tile + 1, 2 * tile + 17,
-         64 * tile - 1, 64 * tile, 64 * tile + 1, 65 * tile + 3, 130 * tile + 777}
+def edge_sizes(*tiles):
+    s = {1, 2, 3, 63, 64, 65, 255, 256, 257, 1023, 1025}
+    for tile in tiles:   # around one tile, the 64-tile look-back window and two windows
+        s |= {tile - 1, tile, tile + 1, 2 * tile + 17, 64 * tile - 1, 64 * tile, 64 * tile + 1, 65 * tile + 3,
+              130 * tile + 777}
     return sorted(s)
 
 
@@ -57,8 +67,7 @@ ALL_PAIRS = sorted(KINDS)
 
 @pytest.mark.parametrize("dtype,op", ALL_PAIRS)
 def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
-    tile = tile_elems(ks, dtype)
-    for n in edge_sizes(tile):
+    for n in edge_sizes(tile_elems(ks, dtype, default_rows(dtype)), tile_elems(ks, dtype, RTS_ROWS)):
         x = random_input(dtype, op, n, seed=1000 + n % 97)
         for inclusive in (True, False):
             ref = reference(dtype, op, x, inclusive)
@@ -73,8 +82,8 @@ def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
                                       ("mat2_u32", "mat2_mul")])
 def test_library_owned_workspace_back_to_back(ks, dtype, op):
     # ks_scan: epoch-tagged descriptors reused call after call, sizes going up and down
-    tile = tile_elems(ks, dtype)
-    for n in [300 * tile + 5, 7 * tile, 1000 * tile + 1, 3, 2 * tile, 999 * tile + 63]:
+    tile = tile_elems(ks, dtype, RTS_ROWS)
+    for n in [300 * tile + 5, 7 * tile, 4000 * tile + 1, 3, 2 * tile, 3999 * tile + 63]:
         x = random_input(dtype, op, n, seed=n % 1013)
         for inclusive in (True, False):
             say(f"[case] pair=({dtype},{op}) n={n} inclusive={inclusive} api=plain")
@@ -121,7 +130,7 @@ def test_operand_order_is_kept_at_every_level(ks):
 
 def test_in_place_and_misaligned_pointers(ks):
     for dtype, op in [("i32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
-        tile = tile_elems(ks, dtype)
+        tile = tile_elems(ks, dtype, default_rows(dtype))
         n = 37 * tile + 11
         x = random_input(dtype, op, n, seed=5)
         ref = reference(dtype, op, x, True)
@@ -144,7 +153,7 @@ def test_in_place_and_misaligned_pointers(ks):
             assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
 
 
-@pytest.mark.parametrize("rows", [2, 4, 8])
+@pytest.mark.parametrize("rows", [2, 4, 8, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
 def test_lookback_variants(ks, rows, prefetch):
     ks.ks_set_option("rows", rows)
