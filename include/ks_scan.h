@@ -126,8 +126,12 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "spin_limit"   polls a look-back wave makes before giving up (default 1<<20)
  *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid
  *                  (0 = what the occupancy query allows; values above it are clamped)
- *   "rows"         16-byte vectors per thread in the look-back kernel (0 = default;
- *                  only the compiled values 2, 4, 8, 16 are accepted)
+ *   "waves"        wave64s per workgroup of the look-back kernel: 0 = the type's default,
+ *                  else 4, 8 or 16
+ *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
+ *                  default, else 4, 8 or 16.  A (waves, rows, prefetch) combination that
+ *                  would not fit the register file for an element type makes the scan
+ *                  call return KS_ERR_UNSUPPORTED
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one

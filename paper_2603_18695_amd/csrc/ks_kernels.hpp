@@ -22,6 +22,8 @@
 
 namespace ks {
 
+// Workgroup shapes: the reduce-then-scan kernels and the copy kernel use 4
+// waves; the look-back kernel is compiled for 4, 8 and 16 waves.
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 
@@ -174,7 +176,7 @@ __device__ __forceinline__ bool lookback(const uint64_t *desc, uint64_t *xdesc, 
 // Cross-wave exchange through LDS (paper Sec. V-B: shared-memory exchange that
 // yields the tile aggregate).  Returns the combination of the waves before
 // this one; `aggregate` receives the whole tile's.
-template <class T, class Op>
+template <class T, class Op, int WAVES>
 __device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_tot, const T &wave_total,
                                                   T &aggregate, Op op) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -184,7 +186,7 @@ __device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_t
     T carry = Op::identity();
     T all = Op::identity();
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
         const T t = from_words<T>(s_tot[w]);
         if (w < wave) carry = op(carry, t);
         all = op(all, t);
@@ -193,12 +195,12 @@ __device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_t
     return carry;
 }
 
-template <class IO, int ROWS>
+template <class IO, int WAVES, int ROWS>
 __device__ __forceinline__ size_t lane_first_element(uint32_t tile) {
     using S = TileShape<IO, ROWS>;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    return (size_t)tile * (kWaves * S::WAVE_ELEMS) + (size_t)wave * S::WAVE_ELEMS + (size_t)lane * S::G;
+    return (size_t)tile * (WAVES * S::WAVE_ELEMS) + (size_t)wave * S::WAVE_ELEMS + (size_t)lane * S::G;
 }
 
 // Do all workgroups of this launch run at the same time?  Each one counts itself
@@ -236,13 +238,17 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 // atomic per tile: one device-scope atomic on a single address costs 12 ns here,
 // more than a tile's share of the run time).  Every wait is bounded by spin_limit.
 // IO = element type in memory, Op::acc = type of registers and descriptors.
+// WAVES x ROWS fixes the tile: WAVES * 64 * ROWS granules of 16 bytes.  With
+// PREFETCH the next tile's granules are requested before the look-back wait and
+// parked unconverted.
 // ---------------------------------------------------------------------------
-template <class IO, class Op, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
-                                                               size_t n, uint64_t *desc, uint64_t *xdesc,
-                                                               uint32_t epoch, uint32_t ntiles,
-                                                               uint32_t spin_limit, uint32_t *abort_flag,
-                                                               int aligned, uint32_t *residency) {
+template <class IO, class Op, int WAVES, int ROWS, bool PREFETCH>
+__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
+                                                                     size_t n, uint64_t *desc, uint64_t *xdesc,
+                                                                     uint32_t epoch, uint32_t ntiles,
+                                                                     uint32_t spin_limit, uint32_t *abort_flag,
+                                                                     int aligned, int inclusive,
+                                                                     uint32_t *residency) {
     if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
         residency_check(residency, spin_limit);
         return;
@@ -250,8 +256,8 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     using Items = ThreadItems<A, ROWS, S::G>;
-    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
-    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    constexpr size_t TILE = (size_t)WAVES * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[WAVES];
     __shared__ typename WordsOf<A>::type s_prefix;
     __shared__ uint32_t s_ok;
     Op op;
@@ -264,13 +270,13 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
     Items cur;
     {
         const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
-        load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(tile), n, vec, cur);
+        load_items<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(tile), n, vec, cur);
     }
     for (;;) {
         const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
         WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
         A aggregate;
-        const A wave_carry = exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+        const A wave_carry = exchange_wave_totals<A, Op, WAVES>(s_tot, ws.wave_total, aggregate, op);
 
         // publish as early as possible: successors only need the aggregate
         if (threadIdx.x == 0) {
@@ -279,10 +285,10 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
         }
 
         const uint32_t next = tile + gridDim.x;
-        Items nxt;
+        RawItems<ROWS> nxt;
         if (PREFETCH && next < ntiles) {
             const bool nvec = aligned && ((size_t)(next + 1) * TILE <= n);
-            load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(next), n, nvec, nxt);
+            load_raw<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(next), n, nvec, nxt);
         }
 
         if (wave == 0) {
@@ -301,16 +307,19 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_kernel(const IO *__restr
         if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
         const A tile_prefix = from_words<A>(s_prefix);
 
-        apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
-        store_items<IO, ROWS, A>(out, lane_first_element<IO, ROWS>(tile), n, vec, cur);
+        if (inclusive)
+            apply_prefix<true, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
+        else
+            apply_prefix<false, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
+        store_items<IO, ROWS, A>(out, lane_first_element<IO, WAVES, ROWS>(tile), n, vec, cur);
 
         if (next >= ntiles) break;
         tile = next;
         if (PREFETCH) {
-            cur = nxt;
+            unpack_items<IO, ROWS, Op>(nxt, cur);
         } else {
             const bool nvec = aligned && ((size_t)(tile + 1) * TILE <= n);
-            load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>(tile), n, nvec, cur);
+            load_items<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(tile), n, nvec, cur);
         }
     }
 }
@@ -331,10 +340,10 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
     const size_t tile = blockIdx.x;
     const bool vec = aligned && ((tile + 1) * TILE <= n);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+    load_items<IO, ROWS, Op>(in, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
     WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
-    (void)exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+    (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
     if (threadIdx.x == 0) aggregates[tile] = aggregate;
 }
 
@@ -352,13 +361,13 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict_
     const size_t tile = blockIdx.x;
     const bool vec = aligned && ((tile + 1) * TILE <= n);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(in, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+    load_items<IO, ROWS, Op>(in, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
     WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
-    const A wave_carry = exchange_wave_totals<A, Op>(s_tot, ws.wave_total, aggregate, op);
+    const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
     const A seed = seeds ? seeds[tile] : Op::identity();
     apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(seed, wave_carry), op);
-    store_items<IO, ROWS, A>(out, lane_first_element<IO, ROWS>((uint32_t)tile), n, vec, cur);
+    store_items<IO, ROWS, A>(out, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
 }
 
 template <int UNUSED = 0>

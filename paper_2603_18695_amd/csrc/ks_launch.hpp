@@ -11,15 +11,42 @@ namespace ks {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 
-// Measured on MI355X for every element size: the largest compiled tile with the
-// next tile prefetched wins (fewer tiles, fewer look-backs, longer streams
-// between synchronisations), even though it leaves only 2 workgroups per
-// compute unit resident.  Types whose accumulator is wider than the element in
-// memory run out of registers earlier and stop at 8 rows.
+// Shape of the look-back kernel's workgroup and tile.  Measured on MI355X
+// (float32 sum, n = 2^28): 4 waves x 4 rows 3.8 TB/s, 4 x 8 4.6, 4 x 16 5.2,
+// 16 x 8 5.7, 12 x 10 5.8 -- the fewer and larger the tiles, the less the
+// look-back costs, and one 1024-thread workgroup per compute unit with the
+// next tile prefetched keeps 256 KiB of data resident per compute unit.
+struct Shape {
+    int waves, rows;
+    bool prefetch;
+};
+
+// Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
+// registers; the tile needs 4 * ROWS * (acc size / element size) of them, the
+// parked next tile 4 * ROWS, the rest goes to addresses, wave-scan temporaries
+// and descriptors.  The bound is loose: variants close to it may spill a few
+// registers (they stay correct); the defaults below were checked not to.
+template <class T, class A, int WAVES, int ROWS, bool PREFETCH>
+constexpr bool variant_fits() {
+    constexpr int per_wave = 512 / (WAVES / 4 > 0 ? WAVES / 4 : 1);
+    constexpr int budget = per_wave > 256 ? 256 : per_wave;
+    constexpr int data = 4 * ROWS * (int)(sizeof(A) / sizeof(T));
+    constexpr int parked = PREFETCH ? 4 * ROWS : 0;
+    constexpr int other = 40 + 12 * (int)(sizeof(A) / 4);
+    return data + parked + other <= budget;
+}
+
+// Default shape per element class: the best measured on MI355X among the
+// variants that compile without register spills (float32 sum 2^28: 5.79 TB/s;
+// uint64 sum 2^27: 5.56; affine 2^26: 4.03; arg-max struct 2^26: 4.00).
 template <class T, class A>
 struct PairDefaults {
-    static constexpr int rows = sizeof(A) > sizeof(T) ? 8 : 16;
-    static constexpr bool prefetch = true;
+    static constexpr Shape shape() {
+        if (sizeof(A) == 4) return Shape{16, 8, true};                      // 128 KiB tile, 1 workgroup per CU
+        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{8, 16, true};    // 128 KiB tile, 1 workgroup per CU
+        if (sizeof(A) == sizeof(T)) return Shape{4, 16, true};              // 16-byte structs: 64 KiB tile, 2 per CU
+        return Shape{8, 8, true};                                           // accumulator wider than the element
+    }
 };
 
 // T = element type in memory; A = Op::acc = type of aggregates, seeds and descriptors.
@@ -28,18 +55,20 @@ struct Pair {
     using A = typename Op::acc;
     static constexpr int W = WordsOf<A>::W;
     static constexpr int kRtsRows = 4;
+    static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
 
     static size_t tile_elems(int rows) { return (size_t)kWaves * kWave * rows * (16 / sizeof(T)); }
+    static size_t shape_tile_elems(int waves, int rows) { return (size_t)waves * kWave * rows * (16 / sizeof(T)); }
 
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
-    static int lookback_rows() {
-        const long long r = options().rows;
-        return (r == 2 || r == 4 || r == 8 || r == 16) ? (int)r : PairDefaults<T, A>::rows;
-    }
-    static bool lookback_prefetch() {
-        const long long p = options().prefetch;
-        return p < 0 ? PairDefaults<T, A>::prefetch : p != 0;
+    static Shape lookback_shape() {
+        Shape s = PairDefaults<T, A>::shape();
+        const Options &o = options();
+        if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
+        if (o.rows == 4 || o.rows == 8 || o.rows == 16) s.rows = (int)o.rows;
+        if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
+        return s;
     }
 
     static ks_algo pick_algo(size_t n) {
@@ -52,8 +81,8 @@ struct Pair {
         if (algo == KS_ALGO_AUTO) algo = pick_algo(n);
         if (algo == KS_ALGO_LOOKBACK) {
             // sized for the smallest tile any compiled variant uses, so a later change of the
-            // "rows" option cannot outgrow a buffer sized earlier
-            const size_t tiles = ceil_div(n, tile_elems(2));
+            // shape options cannot outgrow a buffer sized earlier
+            const size_t tiles = ceil_div(n, (size_t)kMinTileGranules * (16 / sizeof(T)));
             return desc_bytes(tiles) + desc_bytes(ceil_div(tiles, kWindow) * kWindow);
         }
         size_t total = 0, m = n;
@@ -67,76 +96,90 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
-    template <int ROWS, bool INCLUSIVE, bool PREFETCH>
+    template <int WAVES, int ROWS, bool PREFETCH>
     static int launch_lookback(const ScanCall &c, int aligned) {
-        auto kernel = scan_lookback_kernel<T, Op, ROWS, INCLUSIVE, PREFETCH>;
-        const size_t tiles = ceil_div(c.n, tile_elems(ROWS));
-        const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
-        if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
-        static int per_cu = 0;   // resident workgroups per compute unit for this variant, as verified below
-        if (per_cu == 0) {
-            int nb = 0;
-            hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kBlock, 0);
-            if (e != hipSuccess) return set_hip_error(e);
-            // The query is an upper bound only; run the kernel in its residency-check mode and
-            // step down until every workgroup of the grid is seen running at once.  One-off per
-            // variant and device; it synchronises the stream.
-            int verified = 0;
-            for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
-                uint32_t zero[2] = {0u, 0u};
-                e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
+        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH>()) {
+            return KS_ERR_UNSUPPORTED;   // this shape would spill registers for this element type
+        } else {
+            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, PREFETCH>;
+            constexpr int kThreads = WAVES * kWave;
+            const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
+            const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
+            if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
+            static int per_cu = 0;   // resident workgroups per compute unit for this variant, as verified below
+            if (per_cu == 0) {
+                int nb = 0;
+                hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kThreads, 0);
                 if (e != hipSuccess) return set_hip_error(e);
-                hipLaunchKernelGGL(kernel, dim3((unsigned)(tryb * c.dev->cus)), dim3(kBlock), 0, c.stream,
-                                   static_cast<const T *>(nullptr), static_cast<T *>(nullptr), (size_t)0,
-                                   static_cast<uint64_t *>(nullptr), static_cast<uint64_t *>(nullptr), 0u, 0u,
-                                   (uint32_t)(1u << 16), c.dev->abort_flag, 0, c.dev->residency);
-                if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
-                uint32_t seen[2] = {0u, 1u};
-                e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
-                if (e != hipSuccess) return set_hip_error(e);
-                if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
-                if (seen[1] == 0u) verified = tryb;
+                // The query is an upper bound only; run the kernel in its residency-check mode and
+                // step down until every workgroup of the grid is seen running at once.  One-off per
+                // variant and device; it synchronises the stream.
+                int verified = 0;
+                for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
+                    uint32_t zero[2] = {0u, 0u};
+                    e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
+                    if (e != hipSuccess) return set_hip_error(e);
+                    hipLaunchKernelGGL(kernel, dim3((unsigned)(tryb * c.dev->cus)), dim3(kThreads), 0, c.stream,
+                                       static_cast<const T *>(nullptr), static_cast<T *>(nullptr), (size_t)0,
+                                       static_cast<uint64_t *>(nullptr), static_cast<uint64_t *>(nullptr), 0u, 0u,
+                                       (uint32_t)(1u << 16), c.dev->abort_flag, 0, 0, c.dev->residency);
+                    if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
+                    uint32_t seen[2] = {0u, 1u};
+                    e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
+                    if (e != hipSuccess) return set_hip_error(e);
+                    if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
+                    if (seen[1] == 0u) verified = tryb;
+                }
+                if (verified < 1) return KS_ERR_WORKSPACE;
+                per_cu = verified;
             }
-            if (verified < 1) return KS_ERR_WORKSPACE;
-            per_cu = verified;
+            long long want = options().wgs_per_cu;
+            int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
+            size_t grid = (size_t)use * (size_t)c.dev->cus;
+            if (options().grid_mode == 1 || grid > tiles) grid = tiles;
+            options().last_grid = (long long)grid;
+            options().last_resident_per_cu = per_cu;
+            uint64_t *desc = static_cast<uint64_t *>(c.temp);
+            uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
+            if (c.clear_descriptors) {
+                const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
+                const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
+                hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
+            }
+            long long spin = options().spin_limit;
+            if (spin < 0) spin = 0;
+            if (spin > 0xffffffffll) spin = 0xffffffffll;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream,
+                               static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch,
+                               (uint32_t)tiles, (uint32_t)spin, c.dev->abort_flag, aligned, c.inclusive ? 1 : 0,
+                               static_cast<uint32_t *>(nullptr));
+            hipError_t e = hipGetLastError();
+            return e == hipSuccess ? KS_OK : set_hip_error(e);
         }
-        long long want = options().wgs_per_cu;
-        int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
-        size_t grid = (size_t)use * (size_t)c.dev->cus;
-        if (options().grid_mode == 1 || grid > tiles) grid = tiles;
-        options().last_grid = (long long)grid;
-        options().last_resident_per_cu = per_cu;
-        uint64_t *desc = static_cast<uint64_t *>(c.temp);
-        uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
-        if (c.clear_descriptors) {
-            const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
-            const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
-            hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
-        }
-        long long spin = options().spin_limit;
-        if (spin < 0) spin = 0;
-        if (spin > 0xffffffffll) spin = 0xffffffffll;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
-                           static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch, (uint32_t)tiles, (uint32_t)spin,
-                           c.dev->abort_flag, aligned, static_cast<uint32_t *>(nullptr));
-        hipError_t e = hipGetLastError();
-        return e == hipSuccess ? KS_OK : set_hip_error(e);
     }
 
-    template <int ROWS>
-    static int lookback_rows_dispatch(const ScanCall &c, int aligned) {
-        const bool pf = lookback_prefetch();
-        if (c.inclusive)
-            return pf ? launch_lookback<ROWS, true, true>(c, aligned) : launch_lookback<ROWS, true, false>(c, aligned);
-        return pf ? launch_lookback<ROWS, false, true>(c, aligned) : launch_lookback<ROWS, false, false>(c, aligned);
+    template <int WAVES, int ROWS>
+    static int lookback_pf_dispatch(const ScanCall &c, int aligned, bool pf) {
+        return pf ? launch_lookback<WAVES, ROWS, true>(c, aligned) : launch_lookback<WAVES, ROWS, false>(c, aligned);
+    }
+
+    template <int WAVES>
+    static int lookback_rows_dispatch(const ScanCall &c, int aligned, const Shape &s) {
+        switch (s.rows) {
+            case 4: return lookback_pf_dispatch<WAVES, 4>(c, aligned, s.prefetch);
+            case 8: return lookback_pf_dispatch<WAVES, 8>(c, aligned, s.prefetch);
+            case 16: return lookback_pf_dispatch<WAVES, 16>(c, aligned, s.prefetch);
+            default: return KS_ERR_INVALID_ARG;
+        }
     }
 
     static int run_lookback(const ScanCall &c, int aligned) {
-        switch (lookback_rows()) {
-            case 2: return lookback_rows_dispatch<2>(c, aligned);
-            case 4: return lookback_rows_dispatch<4>(c, aligned);
-            case 16: return lookback_rows_dispatch<16>(c, aligned);
-            default: return lookback_rows_dispatch<8>(c, aligned);
+        const Shape s = lookback_shape();
+        switch (s.waves) {
+            case 4: return lookback_rows_dispatch<4>(c, aligned, s);
+            case 8: return lookback_rows_dispatch<8>(c, aligned, s);
+            case 16: return lookback_rows_dispatch<16>(c, aligned, s);
+            default: return KS_ERR_INVALID_ARG;
         }
     }
 

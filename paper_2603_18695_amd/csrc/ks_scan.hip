@@ -190,6 +190,7 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "spin_limit")) return &o.spin_limit;
     if (!std::strcmp(name, "wgs_per_cu")) return &o.wgs_per_cu;
     if (!std::strcmp(name, "rows")) return &o.rows;
+    if (!std::strcmp(name, "waves")) return &o.waves;
     if (!std::strcmp(name, "prefetch")) return &o.prefetch;
     if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
     if (!std::strcmp(name, "last_grid")) return &o.last_grid;
@@ -202,7 +203,7 @@ int ks_set_option(const char *name, long long value) {
     if (!slot) return KS_ERR_INVALID_ARG;
     Options &o = options();
     if (slot == &o.last_grid || slot == &o.last_resident_per_cu) return KS_ERR_INVALID_ARG;   // read-only
-    if (slot == &o.rows && !(value == 0 || value == 2 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
+    if ((slot == &o.rows || slot == &o.waves) && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;

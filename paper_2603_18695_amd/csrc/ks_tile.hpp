@@ -2,7 +2,7 @@
 // thread's items in registers, and the per-wave combination (paper Sec. V-B,
 // second paragraph; Sec. IV-C for the wide loads and the items-per-thread idea).
 //
-// Register arrangement.  A workgroup of kWaves wave64s owns one tile.  Wave w
+// Register arrangement.  A workgroup of WAVES wave64s owns one tile.  Wave w
 // owns a contiguous run of 64*ROWS granules of 16 bytes; inside it, "row" j is
 // 64 consecutive granules and lane l holds granule l of every row.  Each global
 // access instruction of a wave therefore touches 1 KiB of consecutive bytes.
@@ -40,33 +40,64 @@ struct ThreadItems {
     A x[ROWS][G];
 };
 
+// The lane's granules as they come from memory, before conversion to the
+// accumulation type.  A prefetched tile is parked in this form: it costs
+// 4 registers per row whatever the accumulator's size.
+template <int ROWS>
+struct RawItems {
+    u32x4 v[ROWS];
+};
+
 // Load the lane's granules.  `first` = index of the first element of the lane's
 // row-0 granule.  vec: every granule is inside [0, n) and 16-byte aligned.
 // Otherwise element-wise, elements at or past n read as the identity.
 template <class IO, int ROWS, class Op>
-__device__ __forceinline__ void load_items(const IO *__restrict__ in, size_t first, size_t n, bool vec,
-                                           ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
-    using A = typename Op::acc;
+__device__ __forceinline__ void load_raw(const IO *__restrict__ in, size_t first, size_t n, bool vec,
+                                         RawItems<ROWS> &raw) {
     constexpr int G = TileShape<IO, ROWS>::G;
     if (vec) {
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             const u32x4 *p = reinterpret_cast<const u32x4 *>(in + first + (size_t)j * kWave * G);
-            u32x4 v = __builtin_nontemporal_load(p);
-            Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, v);
-#pragma unroll
-            for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(g.e[k]);
+            raw.v[j] = __builtin_nontemporal_load(p);
         }
     } else {
+        const IO fill = convert<IO>(Op::identity());
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
+            Granule<IO, G> g;
 #pragma unroll
             for (int k = 0; k < G; ++k) {
-                size_t i = first + (size_t)j * kWave * G + k;
-                it.x[j][k] = (i < n) ? convert<A>(in[i]) : Op::identity();
+                // unconditional in-bounds load, then a select on the value (a select between the
+                // two addresses would put `fill` in scratch memory)
+                const size_t i = first + (size_t)j * kWave * G + k;
+                const IO v = in[i < n ? i : 0];
+                g.e[k] = (i < n) ? v : fill;
             }
+            raw.v[j] = __builtin_bit_cast(u32x4, g);
         }
     }
+}
+
+template <class IO, int ROWS, class Op>
+__device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw,
+                                             ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+    using A = typename Op::acc;
+    constexpr int G = TileShape<IO, ROWS>::G;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, raw.v[j]);
+#pragma unroll
+        for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(g.e[k]);
+    }
+}
+
+template <class IO, int ROWS, class Op>
+__device__ __forceinline__ void load_items(const IO *__restrict__ in, size_t first, size_t n, bool vec,
+                                           ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+    RawItems<ROWS> raw;
+    load_raw<IO, ROWS, Op>(in, first, n, vec, raw);
+    unpack_items<IO, ROWS, Op>(raw, it);
 }
 
 template <class IO, int ROWS, class A>

@@ -105,6 +105,13 @@ def test_options_are_validated(ks):
     ks.ks_set_option("rows", 0)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("rows", 3)
+    ks.ks_set_option("waves", 16)
+    assert ks.ks_get_option("waves") == 16
+    ks.ks_set_option("waves", 0)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("waves", 2)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("last_grid", 1)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("no_such_option", 1)
     with pytest.raises(ks.KsError):

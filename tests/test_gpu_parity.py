@@ -18,7 +18,8 @@ pytestmark = pytest.mark.gpu
 def ks():
     import paper_2603_18695_amd as ks
     yield ks
-    for name, v in [("rows", 0), ("prefetch", -1), ("grid_mode", 0), ("wgs_per_cu", 0), ("spin_limit", 1 << 20)]:
+    for name, v in [("waves", 0), ("rows", 0), ("prefetch", -1), ("grid_mode", 0), ("wgs_per_cu", 0),
+                    ("spin_limit", 1 << 20)]:
         ks.ks_set_option(name, v)
 
 
@@ -27,16 +28,18 @@ def say(msg):
     sys.stdout.flush()
 
 
-def tile_elems(ks, dtype, rows):
-    return 256 * rows * (16 // ks.ks_elem_bytes(dtype))
+def tile_elems(ks, dtype, waves, rows):
+    return waves * 64 * rows * (16 // ks.ks_elem_bytes(dtype))
 
 
-def default_rows(dtype):
-    # library defaults: 16 sixteen-byte rows per thread, 8 where the accumulator is wider than the element
-    return 8 if dtype == "affine_f32" else 16
+def default_shape(ks, dtype):
+    """(waves, rows) the library picks for the look-back kernel of this element type."""
+    if dtype == "affine_f32":
+        return 8, 8
+    return {4: (16, 8), 8: (8, 16), 16: (4, 16)}[ks.ks_elem_bytes(dtype)]
 
 
-RTS_ROWS = 4   # tile of the reduce-then-scan kernels
+RTS_SHAPE = (4, 4)   # tile of the reduce-then-scan kernels
 
 
 def run(ks, dtype, op, x, inclusive=True, algo="auto", api="with_temp", in_place=False):
@@ -67,7 +70,7 @@ ALL_PAIRS = sorted(KINDS)
 
 @pytest.mark.parametrize("dtype,op", ALL_PAIRS)
 def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
-    for n in edge_sizes(tile_elems(ks, dtype, default_rows(dtype)), tile_elems(ks, dtype, RTS_ROWS)):
+    for n in edge_sizes(tile_elems(ks, dtype, *default_shape(ks, dtype)), tile_elems(ks, dtype, *RTS_SHAPE)):
         x = random_input(dtype, op, n, seed=1000 + n % 97)
         for inclusive in (True, False):
             ref = reference(dtype, op, x, inclusive)
@@ -82,7 +85,7 @@ def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
                                       ("mat2_u32", "mat2_mul")])
 def test_library_owned_workspace_back_to_back(ks, dtype, op):
     # ks_scan: epoch-tagged descriptors reused call after call, sizes going up and down
-    tile = tile_elems(ks, dtype, RTS_ROWS)
+    tile = tile_elems(ks, dtype, *RTS_SHAPE)
     for n in [300 * tile + 5, 7 * tile, 4000 * tile + 1, 3, 2 * tile, 3999 * tile + 63]:
         x = random_input(dtype, op, n, seed=n % 1013)
         for inclusive in (True, False):
@@ -130,7 +133,7 @@ def test_operand_order_is_kept_at_every_level(ks):
 
 def test_in_place_and_misaligned_pointers(ks):
     for dtype, op in [("i32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
-        tile = tile_elems(ks, dtype, default_rows(dtype))
+        tile = tile_elems(ks, dtype, *default_shape(ks, dtype))
         n = 37 * tile + 11
         x = random_input(dtype, op, n, seed=5)
         ref = reference(dtype, op, x, True)
@@ -153,24 +156,37 @@ def test_in_place_and_misaligned_pointers(ks):
             assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
 
 
-@pytest.mark.parametrize("rows", [2, 4, 8, 16])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("rows", [4, 8, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
-def test_lookback_variants(ks, rows, prefetch):
+def test_lookback_variants(ks, waves, rows, prefetch):
+    ks.ks_set_option("waves", waves)
     ks.ks_set_option("rows", rows)
     ks.ks_set_option("prefetch", prefetch)
+    ran = 0
     try:
         for dtype, op in [("f32", "sum"), ("i32", "sum"), ("u64", "sum"), ("affine_f32", "affine_compose"),
                           ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
-            tile = tile_elems(ks, dtype, rows)
-            for n in [tile * 5000 + 3, tile * 64 + 1]:
+            tile = tile_elems(ks, dtype, waves, rows)
+            # > 2 rounds of a 256-workgroup persistent grid, and the 64-tile window boundary
+            for n in [tile * 700 + 3, tile * 64 + 1]:
                 x = random_input(dtype, op, n, seed=rows * 10 + prefetch)
                 for inclusive in (True, False):
-                    say(f"[case] rows={rows} prefetch={prefetch} ({dtype},{op}) n={n} incl={inclusive}")
-                    got = run(ks, dtype, op, x, inclusive, algo="lookback")
-                    assert_matches(dtype, op, got, reference(dtype, op, x, inclusive), f"rows={rows} pf={prefetch}")
+                    say(f"[case] waves={waves} rows={rows} prefetch={prefetch} ({dtype},{op}) n={n} incl={inclusive}")
+                    try:
+                        got = run(ks, dtype, op, x, inclusive, algo="lookback")
+                    except ks.KsError as e:
+                        # shapes that do not fit the register file for this type are refused, never run
+                        assert e.status == ks.KS_ERR_UNSUPPORTED, e
+                        continue
+                    ran += 1
+                    assert_matches(dtype, op, got, reference(dtype, op, x, inclusive),
+                                   f"waves={waves} rows={rows} pf={prefetch}")
     finally:
+        ks.ks_set_option("waves", 0)
         ks.ks_set_option("rows", 0)
         ks.ks_set_option("prefetch", -1)
+    assert ran > 0 or (waves, rows) == (16, 16)
 
 
 def test_repeated_launches_give_identical_integer_results(ks):
