@@ -126,10 +126,10 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "spin_limit"   polls a look-back wave makes before giving up (default 1<<20)
  *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid
  *                  (0 = what the occupancy query allows; values above it are clamped)
- *   "waves"        wave64s per workgroup of the look-back kernel: 0 = the type's default,
- *                  else 4, 8 or 16
+ *   "waves"        wave64s per workgroup of the look-back kernel (one of them does the
+ *                  look-back, the others hold the tile): 0 = the type's default, else 4, 8 or 16
  *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
- *                  default, else 4, 8 or 16.  A (waves, rows, prefetch) combination that
+ *                  default, else 4, 8, 9 or 16.  A (waves, rows, prefetch) combination that
  *                  would not fit the register file for an element type makes the scan
  *                  call return KS_ERR_UNSUPPORTED
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,

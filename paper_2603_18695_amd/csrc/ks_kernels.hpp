@@ -23,7 +23,8 @@
 namespace ks {
 
 // Workgroup shapes: the reduce-then-scan kernels and the copy kernel use 4
-// waves; the look-back kernel is compiled for 4, 8 and 16 waves.
+// waves; the look-back kernel is compiled for 4, 8 and 16 waves, one of which
+// does the look-back and the others the data.
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 
@@ -195,12 +196,12 @@ __device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_t
     return carry;
 }
 
-template <class IO, int WAVES, int ROWS>
-__device__ __forceinline__ size_t lane_first_element(uint32_t tile) {
-    using S = TileShape<IO, ROWS>;
+// Byte offset, inside a tile, of the calling lane's row-0 granule; `dwave` is the
+// wave's index among the waves that hold data.
+template <int ROWS>
+__device__ __forceinline__ int lane_tile_bytes(int dwave) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    return (size_t)tile * (WAVES * S::WAVE_ELEMS) + (size_t)wave * S::WAVE_ELEMS + (size_t)lane * S::G;
+    return (dwave * (kWave * ROWS) + lane) * 16;
 }
 
 // Do all workgroups of this launch run at the same time?  Each one counts itself
@@ -237,17 +238,27 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 // are assigned; this removes any reliance on dispatch order without a ticket
 // atomic per tile: one device-scope atomic on a single address costs 12 ns here,
 // more than a tile's share of the run time).  Every wait is bounded by spin_limit.
+//
 // IO = element type in memory, Op::acc = type of registers and descriptors.
-// WAVES x ROWS fixes the tile: WAVES * 64 * ROWS granules of 16 bytes.  With
-// PREFETCH the next tile's granules are requested before the look-back wait and
-// parked unconverted.
+// A workgroup has WAVES wave64s.  Wave 0 talks to the descriptors (publish,
+// look-back).  In the 16-wave shape it does nothing else and waves 1..15 each
+// own a run of 64*ROWS granules of the tile: vector memory instructions of a
+// wave return in order, so a wave that also streams data sees every descriptor
+// poll queue behind its own prefetch.  Measured on MI355X the dedicated wave
+// is worth 7 % (float32 sum, n = 2^28: 5.70 -> 6.13 TB/s), more than the 1/16
+// of the registers it leaves unused; in the 4- and 8-wave shapes it would idle
+// 1/4 or 1/8 of the workgroup and wave 0 holds data like the others.
+// With PREFETCH the next tile's granules are requested before the look-back
+// wait and parked unconverted.
 // ---------------------------------------------------------------------------
-template <class IO, class Op, int WAVES, int ROWS, bool PREFETCH>
+constexpr bool dedicated_lookback_wave(int waves) { return waves >= 16; }
+constexpr int data_waves(int waves) { return dedicated_lookback_wave(waves) ? waves - 1 : waves; }
+
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
 __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
                                                                      size_t n, uint64_t *desc, uint64_t *xdesc,
                                                                      uint32_t epoch, uint32_t ntiles,
                                                                      uint32_t spin_limit, uint32_t *abort_flag,
-                                                                     int aligned, int inclusive,
                                                                      uint32_t *residency) {
     if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
         residency_check(residency, spin_limit);
@@ -256,42 +267,49 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     using Items = ThreadItems<A, ROWS, S::G>;
-    constexpr size_t TILE = (size_t)WAVES * S::WAVE_ELEMS;
+    constexpr bool DEDICATED = dedicated_lookback_wave(WAVES);
+    constexpr int DATA_WAVES = data_waves(WAVES);
+    constexpr size_t TILE = (size_t)DATA_WAVES * S::WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[WAVES];
     __shared__ typename WordsOf<A>::type s_prefix;
     __shared__ uint32_t s_ok;
     Op op;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
+    const bool data_wave = !DEDICATED || wave != 0;
+    const bool lookback_wave = wave == 0;
+    const int lane_bytes = lane_tile_bytes<ROWS>(DEDICATED ? (wave != 0 ? wave - 1 : 0) : wave);
 
     uint32_t tile = blockIdx.x;
     if (tile >= ntiles) return;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
     Items cur;
-    {
-        const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
-        load_items<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(tile), n, vec, cur);
+    if (data_wave) {
+        const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
+        load_items<IO, ROWS, Op>(w, lane_bytes, tile + 1 == ntiles, cur);
     }
     for (;;) {
-        const bool vec = aligned && ((size_t)(tile + 1) * TILE <= n);
-        WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+        WaveScan<A, ROWS> ws;
+        if (data_wave)
+            ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+        else
+            ws.wave_total = Op::identity();
         A aggregate;
         const A wave_carry = exchange_wave_totals<A, Op, WAVES>(s_tot, ws.wave_total, aggregate, op);
 
         // publish as early as possible: successors only need the aggregate
-        if (threadIdx.x == 0) {
+        if (lookback_wave && lane == 0) {
             desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
             if (tile == 0) desc_publish<A>(xdesc, 0, epoch, kPrefix, Op::identity());   // nothing before tile 0
         }
-
         const uint32_t next = tile + gridDim.x;
         RawItems<ROWS> nxt;
-        if (PREFETCH && next < ntiles) {
-            const bool nvec = aligned && ((size_t)(next + 1) * TILE <= n);
-            load_raw<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(next), n, nvec, nxt);
+        TileWindow wnext;
+        if (data_wave && PREFETCH && next < ntiles) {
+            wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
+            load_raw<ROWS>(wnext, lane_bytes, nxt);
         }
-
-        if (wave == 0) {
+        if (lookback_wave) {
             A excl = Op::identity();
             bool ok = true;
             if (tile != 0) {
@@ -305,21 +323,21 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
         }
         __syncthreads();
         if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
-        const A tile_prefix = from_words<A>(s_prefix);
 
-        if (inclusive)
-            apply_prefix<true, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
-        else
-            apply_prefix<false, A, ROWS, S::G, Op>(cur, ws, op(tile_prefix, wave_carry), op);
-        store_items<IO, ROWS, A>(out, lane_first_element<IO, WAVES, ROWS>(tile), n, vec, cur);
-
+        if (data_wave) {
+            const A prefix = op(from_words<A>(s_prefix), wave_carry);
+            apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, prefix, op);
+            store_items<IO, ROWS, A>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE), lane_bytes, cur);
+        }
         if (next >= ntiles) break;
         tile = next;
-        if (PREFETCH) {
-            unpack_items<IO, ROWS, Op>(nxt, cur);
-        } else {
-            const bool nvec = aligned && ((size_t)(tile + 1) * TILE <= n);
-            load_items<IO, ROWS, Op>(in, lane_first_element<IO, WAVES, ROWS>(tile), n, nvec, cur);
+        if (data_wave) {
+            if (PREFETCH) {
+                unpack_items<IO, ROWS, Op>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
+            } else {
+                const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
+                load_items<IO, ROWS, Op>(w, lane_bytes, tile + 1 == ntiles, cur);
+            }
         }
     }
 }
@@ -330,17 +348,16 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
 // ---------------------------------------------------------------------------
 template <class IO, class Op, int ROWS>
 __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restrict__ in, size_t n,
-                                                             typename Op::acc *__restrict__ aggregates,
-                                                             int aligned) {
+                                                             typename Op::acc *__restrict__ aggregates) {
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
     Op op;
     const size_t tile = blockIdx.x;
-    const bool vec = aligned && ((tile + 1) * TILE <= n);
+    const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(in, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
+    load_items<IO, ROWS, Op>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
     WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
     (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
@@ -351,23 +368,22 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
 // covers the whole input).  Otherwise seeds[tile] = combination of all earlier tiles.
 template <class IO, class Op, int ROWS, bool INCLUSIVE>
 __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict__ in, IO *__restrict__ out, size_t n,
-                                                           const typename Op::acc *__restrict__ seeds,
-                                                           int aligned) {
+                                                           const typename Op::acc *__restrict__ seeds) {
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
     Op op;
     const size_t tile = blockIdx.x;
-    const bool vec = aligned && ((tile + 1) * TILE <= n);
+    const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(in, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
+    load_items<IO, ROWS, Op>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
     WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
     const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
     const A seed = seeds ? seeds[tile] : Op::identity();
     apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(seed, wave_carry), op);
-    store_items<IO, ROWS, A>(out, lane_first_element<IO, kWaves, ROWS>((uint32_t)tile), n, vec, cur);
+    store_items<IO, ROWS, A>(tile_window<IO>(out, n, tile * TILE, TILE), lane_bytes, cur);
 }
 
 template <int UNUSED = 0>

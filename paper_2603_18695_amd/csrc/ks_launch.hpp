@@ -36,13 +36,12 @@ constexpr bool variant_fits() {
     return data + parked + other <= budget;
 }
 
-// Default shape per element class: the best measured on MI355X among the
-// variants that compile without register spills (float32 sum 2^28: 5.79 TB/s;
-// uint64 sum 2^27: 5.56; affine 2^26: 4.03; arg-max struct 2^26: 4.00).
+// Default shape per element class: the best measured on MI355X (float32 sum
+// 2^28: 6.2 TB/s; uint64 sum 2^27: 5.6; affine 2^26: 4.0; arg-max struct 2^26: 4.0).
 template <class T, class A>
 struct PairDefaults {
     static constexpr Shape shape() {
-        if (sizeof(A) == 4) return Shape{16, 8, true};                      // 128 KiB tile, 1 workgroup per CU
+        if (sizeof(A) == 4) return Shape{16, 9, true};                      // 15 data waves: 135 KiB tile, 1 workgroup per CU
         if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{8, 16, true};    // 128 KiB tile, 1 workgroup per CU
         if (sizeof(A) == sizeof(T)) return Shape{4, 16, true};              // 16-byte structs: 64 KiB tile, 2 per CU
         return Shape{8, 8, true};                                           // accumulator wider than the element
@@ -58,7 +57,7 @@ struct Pair {
     static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
 
     static size_t tile_elems(int rows) { return (size_t)kWaves * kWave * rows * (16 / sizeof(T)); }
-    static size_t shape_tile_elems(int waves, int rows) { return (size_t)waves * kWave * rows * (16 / sizeof(T)); }
+    static size_t shape_tile_elems(int waves, int rows) { return (size_t)data_waves(waves) * kWave * rows * (16 / sizeof(T)); }
 
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
@@ -66,7 +65,7 @@ struct Pair {
         Shape s = PairDefaults<T, A>::shape();
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
-        if (o.rows == 4 || o.rows == 8 || o.rows == 16) s.rows = (int)o.rows;
+        if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 16) s.rows = (int)o.rows;
         if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
         return s;
     }
@@ -96,12 +95,12 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
-    template <int WAVES, int ROWS, bool PREFETCH>
-    static int launch_lookback(const ScanCall &c, int aligned) {
+    template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+    static int launch_lookback(const ScanCall &c) {
         if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH>()) {
             return KS_ERR_UNSUPPORTED;   // this shape would spill registers for this element type
         } else {
-            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, PREFETCH>;
+            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>;
             constexpr int kThreads = WAVES * kWave;
             const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
@@ -122,7 +121,7 @@ struct Pair {
                     hipLaunchKernelGGL(kernel, dim3((unsigned)(tryb * c.dev->cus)), dim3(kThreads), 0, c.stream,
                                        static_cast<const T *>(nullptr), static_cast<T *>(nullptr), (size_t)0,
                                        static_cast<uint64_t *>(nullptr), static_cast<uint64_t *>(nullptr), 0u, 0u,
-                                       (uint32_t)(1u << 16), c.dev->abort_flag, 0, 0, c.dev->residency);
+                                       (uint32_t)(1u << 16), c.dev->abort_flag, c.dev->residency);
                     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
                     uint32_t seen[2] = {0u, 1u};
                     e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
@@ -151,74 +150,71 @@ struct Pair {
             if (spin > 0xffffffffll) spin = 0xffffffffll;
             hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream,
                                static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch,
-                               (uint32_t)tiles, (uint32_t)spin, c.dev->abort_flag, aligned, c.inclusive ? 1 : 0,
-                               static_cast<uint32_t *>(nullptr));
+                               (uint32_t)tiles, (uint32_t)spin, c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
             hipError_t e = hipGetLastError();
             return e == hipSuccess ? KS_OK : set_hip_error(e);
         }
     }
 
     template <int WAVES, int ROWS>
-    static int lookback_pf_dispatch(const ScanCall &c, int aligned, bool pf) {
-        return pf ? launch_lookback<WAVES, ROWS, true>(c, aligned) : launch_lookback<WAVES, ROWS, false>(c, aligned);
+    static int lookback_pf_dispatch(const ScanCall &c, bool pf) {
+        if (c.inclusive) return pf ? launch_lookback<WAVES, ROWS, true, true>(c) : launch_lookback<WAVES, ROWS, true, false>(c);
+        return pf ? launch_lookback<WAVES, ROWS, false, true>(c) : launch_lookback<WAVES, ROWS, false, false>(c);
     }
 
     template <int WAVES>
-    static int lookback_rows_dispatch(const ScanCall &c, int aligned, const Shape &s) {
+    static int lookback_rows_dispatch(const ScanCall &c, const Shape &s) {
         switch (s.rows) {
-            case 4: return lookback_pf_dispatch<WAVES, 4>(c, aligned, s.prefetch);
-            case 8: return lookback_pf_dispatch<WAVES, 8>(c, aligned, s.prefetch);
-            case 16: return lookback_pf_dispatch<WAVES, 16>(c, aligned, s.prefetch);
+            case 4: return lookback_pf_dispatch<WAVES, 4>(c, s.prefetch);
+            case 8: return lookback_pf_dispatch<WAVES, 8>(c, s.prefetch);
+            case 9: return lookback_pf_dispatch<WAVES, 9>(c, s.prefetch);
+            case 16: return lookback_pf_dispatch<WAVES, 16>(c, s.prefetch);
             default: return KS_ERR_INVALID_ARG;
         }
     }
 
-    static int run_lookback(const ScanCall &c, int aligned) {
+    static int run_lookback(const ScanCall &c) {
         const Shape s = lookback_shape();
         switch (s.waves) {
-            case 4: return lookback_rows_dispatch<4>(c, aligned, s);
-            case 8: return lookback_rows_dispatch<8>(c, aligned, s);
-            case 16: return lookback_rows_dispatch<16>(c, aligned, s);
+            case 4: return lookback_rows_dispatch<4>(c, s);
+            case 8: return lookback_rows_dispatch<8>(c, s);
+            case 16: return lookback_rows_dispatch<16>(c, s);
             default: return KS_ERR_INVALID_ARG;
         }
     }
 
     // ---- reduce-then-scan ----------------------------------------------------
-    static int launch_tile_scan(bool inclusive, const T *in, T *out, size_t n, const A *seeds, int aligned,
-                                hipStream_t s) {
+    static int launch_tile_scan(bool inclusive, const T *in, T *out, size_t n, const A *seeds, hipStream_t s) {
         const size_t tiles = ceil_div(n, tile_elems(kRtsRows));
         if (inclusive)
             hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, true>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in,
-                               out, n, seeds, aligned);
+                               out, n, seeds);
         else
             hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, false>), dim3((unsigned)tiles), dim3(kBlock), 0, s,
-                               in, out, n, seeds, aligned);
+                               in, out, n, seeds);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
     }
 
-    static int run_rts(bool inclusive, const T *in, T *out, size_t n, int aligned, char *temp, size_t temp_bytes,
-                       hipStream_t s) {
+    static int run_rts(bool inclusive, const T *in, T *out, size_t n, char *temp, size_t temp_bytes, hipStream_t s) {
         const size_t tile = tile_elems(kRtsRows);
         const size_t tiles = ceil_div(n, tile);
-        if (tiles <= 1) return launch_tile_scan(inclusive, in, out, n, nullptr, aligned, s);
+        if (tiles <= 1) return launch_tile_scan(inclusive, in, out, n, nullptr, s);
         const size_t need = align_up(tiles * sizeof(A), 256);
         if (need > temp_bytes) return KS_ERR_WORKSPACE;
         A *agg = reinterpret_cast<A *>(temp);
-        hipLaunchKernelGGL((tile_reduce_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in, n, agg,
-                           aligned);
+        hipLaunchKernelGGL((tile_reduce_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in, n, agg);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return set_hip_error(e);
         // aggregates -> exclusive prefixes of the tiles, in place (scratch is 256-byte aligned)
-        int st = Pair<A, Op>::run_rts(false, agg, agg, tiles, 1, temp + need, temp_bytes - need, s);
+        int st = Pair<A, Op>::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
         if (st != KS_OK) return st;
-        return launch_tile_scan(inclusive, in, out, n, agg, aligned, s);
+        return launch_tile_scan(inclusive, in, out, n, agg, s);
     }
 
     static int run(const ScanCall &c) {
-        const int aligned = (((uintptr_t)c.in | (uintptr_t)c.out) & 15u) == 0 ? 1 : 0;
-        if (c.algo == KS_ALGO_LOOKBACK) return run_lookback(c, aligned);
-        return run_rts(c.inclusive != 0, static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n, aligned,
+        if (c.algo == KS_ALGO_LOOKBACK) return run_lookback(c);
+        return run_rts(c.inclusive != 0, static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n,
                        static_cast<char *>(c.temp), c.temp_bytes, c.stream);
     }
 

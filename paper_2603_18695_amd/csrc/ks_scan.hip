@@ -203,7 +203,8 @@ int ks_set_option(const char *name, long long value) {
     if (!slot) return KS_ERR_INVALID_ARG;
     Options &o = options();
     if (slot == &o.last_grid || slot == &o.last_resident_per_cu) return KS_ERR_INVALID_ARG;   // read-only
-    if ((slot == &o.rows || slot == &o.waves) && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.waves && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.rows && !(value == 0 || value == 4 || value == 8 || value == 9 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;

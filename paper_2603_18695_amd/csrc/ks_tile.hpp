@@ -1,4 +1,4 @@
-// Tile-level pieces of the scan: coalesced 16-byte global access, the scan of a
+// Tile-level pieces of the scan: coalesced 16-byte buffer access, the scan of a
 // thread's items in registers, and the per-wave combination (paper Sec. V-B,
 // second paragraph; Sec. IV-C for the wide loads and the items-per-thread idea).
 //
@@ -48,39 +48,46 @@ struct RawItems {
     u32x4 v[ROWS];
 };
 
-// Load the lane's granules.  `first` = index of the first element of the lane's
-// row-0 granule.  vec: every granule is inside [0, n) and 16-byte aligned.
-// Otherwise element-wise, elements at or past n read as the identity.
-template <class IO, int ROWS, class Op>
-__device__ __forceinline__ void load_raw(const IO *__restrict__ in, size_t first, size_t n, bool vec,
-                                         RawItems<ROWS> &raw) {
-    constexpr int G = TileShape<IO, ROWS>::G;
-    if (vec) {
-#pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-            const u32x4 *p = reinterpret_cast<const u32x4 *>(in + first + (size_t)j * kWave * G);
-            raw.v[j] = __builtin_nontemporal_load(p);
-        }
-    } else {
-        const IO fill = convert<IO>(Op::identity());
-#pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-            Granule<IO, G> g;
-#pragma unroll
-            for (int k = 0; k < G; ++k) {
-                // unconditional in-bounds load, then a select on the value (a select between the
-                // two addresses would put `fill` in scratch memory)
-                const size_t i = first + (size_t)j * kWave * G + k;
-                const IO v = in[i < n ? i : 0];
-                g.e[k] = (i < n) ? v : fill;
-            }
-            raw.v[j] = __builtin_bit_cast(u32x4, g);
-        }
-    }
+// One tile of `in` or `out` seen through a buffer resource: base = first element
+// of the tile, extent = the tile's valid bytes.  The hardware range-checks every
+// dword of a buffer access against the extent: reads past it return zero and
+// writes past it are dropped, so the ragged last tile and pointers that are only
+// element-aligned go through the same 16-byte instructions as everything else
+// (the paper's Sec. IV-D decomposes misaligned accesses in software instead).
+struct TileWindow {
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t valid_bytes;
+};
+
+template <class IO>
+__device__ __forceinline__ TileWindow tile_window(const IO *base, size_t n, size_t tile_first, size_t tile_elems) {
+    const size_t left = n > tile_first ? n - tile_first : 0;
+    const uint32_t valid = (uint32_t)((left < tile_elems ? left : tile_elems) * sizeof(IO));
+    TileWindow w;
+    // raw buffer (stride 0), 32-bit data format, no swizzle: the gfx90a / gfx94x / gfx950 encoding
+    w.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<IO *>(base + tile_first), 0, (int)valid, 0x00020000);
+    w.valid_bytes = valid;
+    return w;
 }
 
+constexpr int kNonTemporal = 2;   // "nt" bit of the buffer instructions' cache policy
+
+// Load the lane's granules.  lane_bytes = byte offset of the lane's row-0 granule
+// inside the tile; rows are 1 KiB apart.  (Signed arithmetic on purpose: it lets the
+// compiler put the row offset into the instruction's immediate field, so that
+// four rows share one address register.)
+template <int ROWS>
+__device__ __forceinline__ void load_raw(const TileWindow &w, int lane_bytes, RawItems<ROWS> &raw) {
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j)
+        raw.v[j] = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, lane_bytes + j * (kWave * 16), 0, kNonTemporal);
+}
+
+// Raw granules -> accumulation type.  In a partial tile the elements past the
+// end (read as zero by the hardware) become the operator's identity.
 template <class IO, int ROWS, class Op>
-__device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw,
+__device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw, int lane_bytes, uint32_t valid_bytes,
+                                             bool partial,
                                              ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
     using A = typename Op::acc;
     constexpr int G = TileShape<IO, ROWS>::G;
@@ -90,38 +97,37 @@ __device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw,
 #pragma unroll
         for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(g.e[k]);
     }
-}
-
-template <class IO, int ROWS, class Op>
-__device__ __forceinline__ void load_items(const IO *__restrict__ in, size_t first, size_t n, bool vec,
-                                           ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
-    RawItems<ROWS> raw;
-    load_raw<IO, ROWS, Op>(in, first, n, vec, raw);
-    unpack_items<IO, ROWS, Op>(raw, it);
-}
-
-template <class IO, int ROWS, class A>
-__device__ __forceinline__ void store_items(IO *__restrict__ out, size_t first, size_t n, bool vec,
-                                            const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it) {
-    constexpr int G = TileShape<IO, ROWS>::G;
-    if (vec) {
-#pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-            Granule<IO, G> g;
-#pragma unroll
-            for (int k = 0; k < G; ++k) g.e[k] = convert<IO>(it.x[j][k]);
-            u32x4 *p = reinterpret_cast<u32x4 *>(out + first + (size_t)j * kWave * G);
-            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, g), p);
-        }
-    } else {
+    if (partial) {
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
 #pragma unroll
             for (int k = 0; k < G; ++k) {
-                size_t i = first + (size_t)j * kWave * G + k;
-                if (i < n) out[i] = convert<IO>(it.x[j][k]);
+                const int at = lane_bytes + j * (kWave * 16) + k * (int)sizeof(IO);
+                if ((uint32_t)at >= valid_bytes) it.x[j][k] = Op::identity();
             }
         }
+    }
+}
+
+template <class IO, int ROWS, class Op>
+__device__ __forceinline__ void load_items(const TileWindow &w, int lane_bytes, bool partial,
+                                           ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+    RawItems<ROWS> raw;
+    load_raw<ROWS>(w, lane_bytes, raw);
+    unpack_items<IO, ROWS, Op>(raw, lane_bytes, w.valid_bytes, partial, it);
+}
+
+template <class IO, int ROWS, class A>
+__device__ __forceinline__ void store_items(const TileWindow &w, int lane_bytes,
+                                            const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it) {
+    constexpr int G = TileShape<IO, ROWS>::G;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        Granule<IO, G> g;
+#pragma unroll
+        for (int k = 0; k < G; ++k) g.e[k] = convert<IO>(it.x[j][k]);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, g), w.rsrc,
+                                               lane_bytes + j * (kWave * 16), 0, kNonTemporal);
     }
 }
 
