@@ -37,13 +37,13 @@ constexpr bool variant_fits() {
 }
 
 // Default shape per element class: the best measured on MI355X (float32 sum
-// 2^28: 6.2 TB/s; uint64 sum 2^27: 5.6; affine 2^26: 4.0; arg-max struct 2^26: 4.0).
+// 2^28: 6.2 TB/s; uint64 sum 2^27: 5.3; affine 2^26: 4.2; arg-max struct 2^26: 4.2).
 template <class T, class A>
 struct PairDefaults {
     static constexpr Shape shape() {
         if (sizeof(A) == 4) return Shape{16, 9, true};                      // 15 data waves: 135 KiB tile, 1 workgroup per CU
         if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{8, 16, true};    // 128 KiB tile, 1 workgroup per CU
-        if (sizeof(A) == sizeof(T)) return Shape{4, 16, true};              // 16-byte structs: 64 KiB tile, 2 per CU
+        if (sizeof(A) == sizeof(T)) return Shape{8, 16, true};              // 16-byte structs: 128 KiB tile
         return Shape{8, 8, true};                                           // accumulator wider than the element
     }
 };

@@ -38,7 +38,7 @@ def default_shape(ks, dtype):
     """(waves, rows) the library picks for the look-back kernel of this element type."""
     if dtype == "affine_f32":
         return 8, 8
-    return {4: (16, 9), 8: (8, 16), 16: (4, 16)}[ks.ks_elem_bytes(dtype)]
+    return {4: (16, 9), 8: (8, 16), 16: (8, 16)}[ks.ks_elem_bytes(dtype)]
 
 
 RTS_SHAPE = (4, 4)   # tile of the reduce-then-scan kernels
