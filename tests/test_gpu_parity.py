@@ -211,6 +211,34 @@ def test_repeated_launches_give_identical_integer_results(ks):
     ks.ks_scan_check()
 
 
+def test_abandoned_wait_is_reported_and_the_next_call_is_clean(ks):
+    # A spin limit of zero makes the first workgroup that has to wait give up.  Every workgroup must
+    # still exit (the call returns), the check reports the timeout once, and later calls are unaffected.
+    for dtype, op in [("f32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count")]:
+        tile = tile_elems(ks, dtype, *default_shape(ks, dtype))
+        n = 900 * tile + 7
+        x = random_input(dtype, op, n, seed=77)
+        d_in = to_device(x)
+        d_out = torch.empty_like(d_in)
+        ks.ks_set_option("spin_limit", 0)
+        try:
+            say(f"[case] spin_limit=0 ({dtype},{op}) n={n}")
+            ks.ks_scan(d_in, d_out, dtype=dtype, op=op)
+            try:
+                ks.ks_scan_check()
+                timed_out = False      # legal: nobody happened to wait
+            except ks.KsError as e:
+                assert e.status == ks.KS_ERR_TIMEOUT, e
+                timed_out = True
+            say(f"[done] spin_limit=0 ({dtype},{op}): timed_out={timed_out}")
+        finally:
+            ks.ks_set_option("spin_limit", 1 << 20)
+        ks.ks_scan_check()             # the flag was cleared by the check that reported it
+        for api in ("plain", "with_temp"):
+            got = run(ks, dtype, op, x, True, algo="lookback", api=api)
+            assert_matches(dtype, op, got, reference(dtype, op, x, True), f"after timeout ({dtype},{op}) {api}")
+
+
 # ---------------------------------------------------------------- the five benchmark configurations, full size
 
 def _full_config(ks, name, n=None, api="plain", algo="auto"):
