@@ -10,8 +10,9 @@
  * General conventions
  *   - `in`, `out`, `temp` are DEVICE pointers owned by the caller.  `in` and
  *     `out` hold n contiguous elements of the given dtype and must be aligned
- *     to the element's alignment (4, 8 or 8/16 bytes, see ks_dtype); 16-byte
- *     aligned pointers take the vectorised path, others a slower correct one.
+ *     to the element's alignment (4 or 8 bytes, see ks_dtype).  Nothing more
+ *     is needed: every access is a range-checked 16-byte buffer instruction,
+ *     so slices that start at any element run at the same speed.
  *   - in == out (exactly in place) is allowed; any other overlap is rejected.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise (except ks_scan_check)
@@ -129,11 +130,14 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "waves"        wave64s per workgroup of the look-back kernel (one of them does the
  *                  look-back, the others hold the tile): 0 = the type's default, else 4, 8 or 16
  *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
- *                  default, else 4, 8, 9 or 16.  A (waves, rows, prefetch) combination that
+ *                  default, else 4, 8, 9, 12 or 16.  A (waves, rows, prefetch) combination that
  *                  would not fit the register file for an element type makes the scan
  *                  call return KS_ERR_UNSUPPORTED
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
+ *   "split"        16-wave shape only: 1 = the look-back wave and the data waves run
+ *                  separate loops (fewer registers, for wide element types), 0 = one
+ *                  common loop, -1 = the type's default
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
  *                  workgroup per tile, which is only deadlock-free if the hardware
  *                  starts workgroups in index order (experimental; waits stay bounded)

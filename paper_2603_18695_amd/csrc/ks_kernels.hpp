@@ -254,16 +254,138 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 constexpr bool dedicated_lookback_wave(int waves) { return waves >= 16; }
 constexpr int data_waves(int waves) { return dedicated_lookback_wave(waves) ? waves - 1 : waves; }
 
-template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
-                                                                     size_t n, uint64_t *desc, uint64_t *xdesc,
-                                                                     uint32_t epoch, uint32_t ntiles,
-                                                                     uint32_t spin_limit, uint32_t *abort_flag,
-                                                                     uint32_t *residency) {
-    if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
-        residency_check(residency, spin_limit);
-        return;
+// What the waves of a workgroup share.
+template <class A, int WAVES>
+struct TileExchange {
+    typename WordsOf<A>::type tot[WAVES];     // per wave: combination of its run
+    typename WordsOf<A>::type carry[WAVES];   // per wave: combination of the runs before it (16-wave shape)
+    typename WordsOf<A>::type prefix;         // exclusive prefix of the tile, from the look-back
+    uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
+};
+
+// Arguments of the look-back kernel that its loops pass around.
+struct LookbackArgs {
+    size_t n;
+    uint64_t *desc, *xdesc;
+    uint32_t epoch, ntiles, spin_limit;
+    uint32_t *abort_flag;
+};
+
+// First thing wave 0 does once the tile's aggregate is known: successors only
+// need the aggregate, so it goes out before anything else is queued.
+template <class A, class Op>
+__device__ __forceinline__ void publish_aggregate(const LookbackArgs &a, uint32_t tile, const A &aggregate) {
+    if ((threadIdx.x & (kWave - 1)) != 0) return;
+    if (tile == 0) {
+        desc_publish<A>(a.desc, 0, a.epoch, kPrefix, aggregate);
+        desc_publish<A>(a.xdesc, 0, a.epoch, kPrefix, Op::identity());   // nothing before tile 0
+    } else {
+        desc_publish<A>(a.desc, tile, a.epoch, kPartial, aggregate);
     }
+}
+
+// Find the tile's exclusive prefix, publish its inclusive prefix, and hand the
+// exclusive prefix to the other waves through x.  Called by wave 0 only.
+template <class A, class Op, int WAVES>
+__device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t tile, uint32_t m, const A &aggregate,
+                                               TileExchange<A, WAVES> &x) {
+    const int lane = threadIdx.x & (kWave - 1);
+    Op op;
+    A excl = Op::identity();
+    bool ok = true;
+    if (tile != 0) {
+        ok = lookback<A, Op>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, excl);
+        if (ok && lane == 0) desc_publish<A>(a.desc, tile, a.epoch, kPrefix, op(excl, aggregate));
+    }
+    if (lane == 0) {
+        x.prefix = to_words(excl);
+        x.ok = ok ? 1u : 0u;
+    }
+}
+
+// 16-wave shape, wave 0: no data.  Per tile: barrier (the data waves' totals are
+// in LDS), scan them (lane l takes the total of data wave l: the inclusive scan
+// gives the tile's aggregate, the exclusive one every data wave's carry), publish,
+// look back, hand the prefix over, barrier.  The two loops below execute the
+// same number of barriers per tile and leave together.
+template <class A, class Op, int WAVES>
+__device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileExchange<A, WAVES> &x) {
+    Op op;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t m = (a.ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
+    for (uint32_t loop_tile = blockIdx.x;;) {
+        const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
+        __syncthreads();
+        A mine = Op::identity();
+        if (lane < WAVES - 1) mine = from_words<A>(x.tot[lane + 1]);
+        const A upto = wave_inclusive_scan(mine, op);
+        const A aggregate = read_lane(upto, WAVES - 2);
+        const A before = wave_shift_up(upto, Op::identity());
+        if (lane < WAVES - 1) x.carry[lane + 1] = to_words(before);
+        publish_aggregate<A, Op>(a, tile, aggregate);
+        resolve_prefix<A, Op, WAVES>(a, tile, m, aggregate, x);
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        const uint32_t next = tile + gridDim.x;
+        if (next >= a.ntiles) return;
+        loop_tile = next;
+    }
+}
+
+// 16-wave shape, waves 1..15: the data.  Kept apart from the look-back code so
+// that the registers of the tile and of the parked next tile do not have to
+// coexist with the look-back's temporaries (one register allocation serves the
+// whole kernel; in one common loop the two add up and wide element types spill).
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+__device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__restrict__ out, const LookbackArgs &a,
+                                               TileExchange<typename Op::acc, WAVES> &x) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
+    Op op;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
+    const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);
+    ThreadItems<A, ROWS, S::G> cur;
+    load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE), lane_bytes,
+                             blockIdx.x + 1 == a.ntiles, cur);
+    for (uint32_t loop_tile = blockIdx.x;;) {
+        // The tile index is the same in every lane; saying so keeps it, and the buffer resources
+        // derived from it, in scalar registers.
+        const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
+        // from here on `cur` holds the scan of the wave's run alone
+        const A wave_total = scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
+        if (lane == 0) x.tot[wave] = to_words(wave_total);
+        __syncthreads();
+        const uint32_t next = tile + gridDim.x;
+        RawItems<ROWS> nxt;
+        TileWindow wnext;
+        if (PREFETCH && next < a.ntiles) {
+            wnext = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
+            load_raw<ROWS, true>(wnext, lane_bytes, nxt);
+        }
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
+        apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, cur,
+                                                prefix, op);
+        if (next >= a.ntiles) return;
+        loop_tile = next;
+        if (PREFETCH) {
+            unpack_items<IO, ROWS, Op, true>(nxt, lane_bytes, wnext.valid_bytes, next + 1 == a.ntiles, cur);
+        } else {
+            load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)next * TILE, TILE), lane_bytes,
+                                     next + 1 == a.ntiles, cur);
+        }
+    }
+}
+
+// One loop for all waves: wave 0 looks back, and holds data as well unless the
+// shape has a dedicated look-back wave.
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+__device__ __forceinline__ void common_wave_loop(const IO *__restrict__ in, IO *__restrict__ out, size_t n,
+                                                 uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
+                                                 uint32_t spin_limit, uint32_t *abort_flag) {
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
     using Items = ThreadItems<A, ROWS, S::G>;
@@ -281,12 +403,11 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
     const int lane_bytes = lane_tile_bytes<ROWS>(DEDICATED ? (wave != 0 ? wave - 1 : 0) : wave);
 
     uint32_t tile = blockIdx.x;
-    if (tile >= ntiles) return;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
     Items cur;
     if (data_wave) {
         const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
-        load_items<IO, ROWS, Op>(w, lane_bytes, tile + 1 == ntiles, cur);
+        load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles, cur);
     }
     for (;;) {
         WaveScan<A, ROWS> ws;
@@ -307,7 +428,7 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
         TileWindow wnext;
         if (data_wave && PREFETCH && next < ntiles) {
             wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
-            load_raw<ROWS>(wnext, lane_bytes, nxt);
+            load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
             A excl = Op::identity();
@@ -326,19 +447,45 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
 
         if (data_wave) {
             const A prefix = op(from_words<A>(s_prefix), wave_carry);
-            apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, prefix, op);
-            store_items<IO, ROWS, A>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE), lane_bytes, cur);
+            finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
+            apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE),
+                                                           lane_bytes, cur, prefix, op);
         }
         if (next >= ntiles) break;
         tile = next;
         if (data_wave) {
             if (PREFETCH) {
-                unpack_items<IO, ROWS, Op>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
+                unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
             } else {
                 const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
-                load_items<IO, ROWS, Op>(w, lane_bytes, tile + 1 == ntiles, cur);
+                load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles, cur);
             }
         }
+    }
+}
+
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool SPLIT>
+__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
+                                                                     size_t n, uint64_t *desc, uint64_t *xdesc,
+                                                                     uint32_t epoch, uint32_t ntiles,
+                                                                     uint32_t spin_limit, uint32_t *abort_flag,
+                                                                     uint32_t *residency) {
+    if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
+        residency_check(residency, spin_limit);
+        return;
+    }
+    using A = typename Op::acc;
+    if (blockIdx.x >= ntiles) return;
+    if constexpr (dedicated_lookback_wave(WAVES) && SPLIT) {
+        __shared__ TileExchange<A, WAVES> x;
+        const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
+        if (threadIdx.x < kWave)
+            lookback_wave_loop<A, Op, WAVES>(a, x);
+        else
+            data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
+    } else {
+        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, n, desc, xdesc, epoch, ntiles, spin_limit,
+                                                                   abort_flag);
     }
 }
 
@@ -357,8 +504,8 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
     const size_t tile = blockIdx.x;
     const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
-    WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
+    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
     (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
     if (threadIdx.x == 0) aggregates[tile] = aggregate;
@@ -377,13 +524,14 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict_
     const size_t tile = blockIdx.x;
     const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
-    WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
+    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
     A aggregate;
     const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+    finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
     const A seed = seeds ? seeds[tile] : Op::identity();
-    apply_prefix<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op(seed, wave_carry), op);
-    store_items<IO, ROWS, A>(tile_window<IO>(out, n, tile * TILE, TILE), lane_bytes, cur);
+    apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, tile * TILE, TILE), lane_bytes, cur,
+                                               op(seed, wave_carry), op);
 }
 
 template <int UNUSED = 0>

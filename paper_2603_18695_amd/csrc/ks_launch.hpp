@@ -13,39 +13,55 @@ inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 
 // Shape of the look-back kernel's workgroup and tile.  Measured on MI355X
 // (float32 sum, n = 2^28): 4 waves x 4 rows 3.8 TB/s, 4 x 8 4.6, 4 x 16 5.2,
-// 16 x 8 5.7, 12 x 10 5.8 -- the fewer and larger the tiles, the less the
-// look-back costs, and one 1024-thread workgroup per compute unit with the
-// next tile prefetched keeps 256 KiB of data resident per compute unit.
+// 16 x 8 5.7, 16 x 9 with a dedicated look-back wave 6.2 -- the fewer and larger
+// the tiles, the less the look-back costs, and one 1024-thread workgroup per
+// compute unit with the next tile prefetched keeps 270 KiB of data resident per
+// compute unit.
 struct Shape {
     int waves, rows;
     bool prefetch;
+    bool split;   // 16 waves only: separate loops for the look-back wave and the data waves
 };
 
 // Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
 // registers; the tile needs 4 * ROWS * (acc size / element size) of them, the
-// parked next tile 4 * ROWS, the rest goes to addresses, wave-scan temporaries
-// and descriptors.  The bound is loose: variants close to it may spill a few
-// registers (they stay correct); the defaults below were checked not to.
-template <class T, class A, int WAVES, int ROWS, bool PREFETCH>
+// parked next tile 4 * ROWS, the rest goes to addresses and wave-scan temporaries.
+// The bound is loose: variants close to it may spill a few registers (they stay
+// correct); the defaults below were checked not to.
+template <class T, class A, int WAVES, int ROWS, bool PREFETCH, bool SPLIT>
 constexpr bool variant_fits() {
+    if (SPLIT && !dedicated_lookback_wave(WAVES)) return false;   // nothing to separate
+    if (WAVES == 16 && ROWS == 4) return false;                   // never competitive, not compiled
     constexpr int per_wave = 512 / (WAVES / 4 > 0 ? WAVES / 4 : 1);
     constexpr int budget = per_wave > 256 ? 256 : per_wave;
     constexpr int data = 4 * ROWS * (int)(sizeof(A) / sizeof(T));
     constexpr int parked = PREFETCH ? 4 * ROWS : 0;
-    constexpr int other = 40 + 12 * (int)(sizeof(A) / 4);
+    // in the common loop the look-back's temporaries live next to the data, in separate loops they do not
+    constexpr int other = SPLIT ? 24 + 6 * (int)(sizeof(A) / 4) : 40 + 12 * (int)(sizeof(A) / 4);
     return data + parked + other <= budget;
 }
 
-// Default shape per element class: the best measured on MI355X (float32 sum
-// 2^28: 6.2 TB/s; uint64 sum 2^27: 5.3; affine 2^26: 4.2; arg-max struct 2^26: 4.2).
+// Default shape per element class: the best measured on MI355X.
+//   4-byte elements    16 waves, 9 rows, prefetch, common loop    float32 sum 2^28: 6.2 TB/s
+//   8-byte elements    16 waves, 9 rows, prefetch, separate loops uint64 sum 2^27:  5.6 TB/s
+//   16-byte elements   16 waves, 12 rows, separate loops          (no register spills for any of them)
+//     arg-max struct   16 waves, 16 rows, separate loops          2^26: 5.1 TB/s
+//   affine (double accumulator, 8-byte element)  16 waves, 8 rows, separate loops   2^26: 4.7 TB/s
+// The 4-byte kernels keep the common loop: with their small register footprint
+// nothing is gained from separating the loops, and the compiler's schedule of
+// the common loop measured 5 % faster (6.25 against 5.9 TB/s).
 template <class T, class A>
 struct PairDefaults {
     static constexpr Shape shape() {
-        if (sizeof(A) == 4) return Shape{16, 9, true};                      // 15 data waves: 135 KiB tile, 1 workgroup per CU
-        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{8, 16, true};    // 128 KiB tile, 1 workgroup per CU
-        if (sizeof(A) == sizeof(T)) return Shape{8, 16, true};              // 16-byte structs: 128 KiB tile
-        return Shape{8, 8, true};                                           // accumulator wider than the element
+        if (sizeof(A) == 4) return Shape{16, 9, true, false};
+        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{16, 9, true, true};
+        if (sizeof(A) == sizeof(T)) return Shape{16, 12, false, true};
+        return Shape{16, 8, false, true};
     }
+};
+template <>
+struct PairDefaults<ArgmaxI32Cnt64, ArgmaxI32Cnt64> {
+    static constexpr Shape shape() { return Shape{16, 16, false, true}; }
 };
 
 // T = element type in memory; A = Op::acc = type of aggregates, seeds and descriptors.
@@ -65,8 +81,10 @@ struct Pair {
         Shape s = PairDefaults<T, A>::shape();
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
-        if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 16) s.rows = (int)o.rows;
+        if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
         if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
+        if (o.split >= 0) s.split = o.split != 0;
+        if (!dedicated_lookback_wave(s.waves)) s.split = false;
         return s;
     }
 
@@ -95,12 +113,12 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
-    template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+    template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool SPLIT>
     static int launch_lookback(const ScanCall &c) {
-        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH>()) {
+        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH, SPLIT>()) {
             return KS_ERR_UNSUPPORTED;   // this shape would spill registers for this element type
         } else {
-            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>;
+            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, SPLIT>;
             constexpr int kThreads = WAVES * kWave;
             const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
@@ -156,19 +174,29 @@ struct Pair {
         }
     }
 
+    template <int WAVES, int ROWS, bool SPLIT>
+    static int lookback_flags_dispatch(const ScanCall &c, bool pf) {
+        if (c.inclusive)
+            return pf ? launch_lookback<WAVES, ROWS, true, true, SPLIT>(c) : launch_lookback<WAVES, ROWS, true, false, SPLIT>(c);
+        return pf ? launch_lookback<WAVES, ROWS, false, true, SPLIT>(c) : launch_lookback<WAVES, ROWS, false, false, SPLIT>(c);
+    }
+
     template <int WAVES, int ROWS>
-    static int lookback_pf_dispatch(const ScanCall &c, bool pf) {
-        if (c.inclusive) return pf ? launch_lookback<WAVES, ROWS, true, true>(c) : launch_lookback<WAVES, ROWS, true, false>(c);
-        return pf ? launch_lookback<WAVES, ROWS, false, true>(c) : launch_lookback<WAVES, ROWS, false, false>(c);
+    static int lookback_pf_dispatch(const ScanCall &c, const Shape &s) {
+        if constexpr (dedicated_lookback_wave(WAVES)) {
+            if (s.split) return lookback_flags_dispatch<WAVES, ROWS, true>(c, s.prefetch);
+        }
+        return lookback_flags_dispatch<WAVES, ROWS, false>(c, s.prefetch);
     }
 
     template <int WAVES>
     static int lookback_rows_dispatch(const ScanCall &c, const Shape &s) {
         switch (s.rows) {
-            case 4: return lookback_pf_dispatch<WAVES, 4>(c, s.prefetch);
-            case 8: return lookback_pf_dispatch<WAVES, 8>(c, s.prefetch);
-            case 9: return lookback_pf_dispatch<WAVES, 9>(c, s.prefetch);
-            case 16: return lookback_pf_dispatch<WAVES, 16>(c, s.prefetch);
+            case 4: return lookback_pf_dispatch<WAVES, 4>(c, s);
+            case 8: return lookback_pf_dispatch<WAVES, 8>(c, s);
+            case 9: return lookback_pf_dispatch<WAVES, 9>(c, s);
+            case 12: return lookback_pf_dispatch<WAVES, 12>(c, s);
+            case 16: return lookback_pf_dispatch<WAVES, 16>(c, s);
             default: return KS_ERR_INVALID_ARG;
         }
     }

@@ -192,6 +192,7 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "rows")) return &o.rows;
     if (!std::strcmp(name, "waves")) return &o.waves;
     if (!std::strcmp(name, "prefetch")) return &o.prefetch;
+    if (!std::strcmp(name, "split")) return &o.split;
     if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
     if (!std::strcmp(name, "last_grid")) return &o.last_grid;
     if (!std::strcmp(name, "last_resident_per_cu")) return &o.last_resident_per_cu;
@@ -204,11 +205,12 @@ int ks_set_option(const char *name, long long value) {
     Options &o = options();
     if (slot == &o.last_grid || slot == &o.last_resident_per_cu) return KS_ERR_INVALID_ARG;   // read-only
     if (slot == &o.waves && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
-    if (slot == &o.rows && !(value == 0 || value == 4 || value == 8 || value == 9 || value == 16)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.rows && !(value == 0 || value == 4 || value == 8 || value == 9 || value == 12 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;
     if (slot == &o.prefetch && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.split && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
     *slot = value;
     return KS_OK;
 }

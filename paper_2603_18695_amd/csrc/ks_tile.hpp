@@ -72,20 +72,34 @@ __device__ __forceinline__ TileWindow tile_window(const IO *base, size_t n, size
 
 constexpr int kNonTemporal = 2;   // "nt" bit of the buffer instructions' cache policy
 
+// The row offsets (multiples of 1 KiB) fit the buffer instructions' 12-bit
+// immediate field four rows at a time, but only if the additions are still next
+// to the instruction when it is selected: inside the tile loop the compiler
+// would hoist them and keep one address register per row.  With PIN the offset
+// passes through an empty asm statement, which pins the additions to the loop
+// body and saves those registers; callers that have registers to spare leave
+// it off (the register allocation and the waits the compiler derives from it
+// change with it, and the 4-byte kernels measured 8 % slower with it).  (Signed
+// arithmetic on purpose: unsigned offsets are not folded into the immediate.)
+template <bool PIN>
+__device__ __forceinline__ int pinned(int lane_bytes) {
+    if (PIN) asm volatile("" : "+v"(lane_bytes));
+    return lane_bytes;
+}
+
 // Load the lane's granules.  lane_bytes = byte offset of the lane's row-0 granule
-// inside the tile; rows are 1 KiB apart.  (Signed arithmetic on purpose: it lets the
-// compiler put the row offset into the instruction's immediate field, so that
-// four rows share one address register.)
-template <int ROWS>
+// inside the tile; rows are 1 KiB apart.
+template <int ROWS, bool PIN>
 __device__ __forceinline__ void load_raw(const TileWindow &w, int lane_bytes, RawItems<ROWS> &raw) {
+    const int at = pinned<PIN>(lane_bytes);
 #pragma unroll
     for (int j = 0; j < ROWS; ++j)
-        raw.v[j] = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, lane_bytes + j * (kWave * 16), 0, kNonTemporal);
+        raw.v[j] = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, at + j * (kWave * 16), 0, kNonTemporal);
 }
 
 // Raw granules -> accumulation type.  In a partial tile the elements past the
 // end (read as zero by the hardware) become the operator's identity.
-template <class IO, int ROWS, class Op>
+template <class IO, int ROWS, class Op, bool PIN>
 __device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw, int lane_bytes, uint32_t valid_bytes,
                                              bool partial,
                                              ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
@@ -98,47 +112,39 @@ __device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw, int lane
         for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(g.e[k]);
     }
     if (partial) {
+        const int at0 = pinned<PIN>(lane_bytes);   // keeps the element offsets out of the registers of full tiles
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
 #pragma unroll
             for (int k = 0; k < G; ++k) {
-                const int at = lane_bytes + j * (kWave * 16) + k * (int)sizeof(IO);
+                const int at = at0 + j * (kWave * 16) + k * (int)sizeof(IO);
                 if ((uint32_t)at >= valid_bytes) it.x[j][k] = Op::identity();
             }
         }
     }
 }
 
-template <class IO, int ROWS, class Op>
+template <class IO, int ROWS, class Op, bool PIN>
 __device__ __forceinline__ void load_items(const TileWindow &w, int lane_bytes, bool partial,
                                            ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
     RawItems<ROWS> raw;
-    load_raw<ROWS>(w, lane_bytes, raw);
-    unpack_items<IO, ROWS, Op>(raw, lane_bytes, w.valid_bytes, partial, it);
+    load_raw<ROWS, PIN>(w, lane_bytes, raw);
+    unpack_items<IO, ROWS, Op, PIN>(raw, lane_bytes, w.valid_bytes, partial, it);
 }
 
-template <class IO, int ROWS, class A>
-__device__ __forceinline__ void store_items(const TileWindow &w, int lane_bytes,
-                                            const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it) {
-    constexpr int G = TileShape<IO, ROWS>::G;
-#pragma unroll
-    for (int j = 0; j < ROWS; ++j) {
-        Granule<IO, G> g;
-#pragma unroll
-        for (int k = 0; k < G; ++k) g.e[k] = convert<IO>(it.x[j][k]);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, g), w.rsrc,
-                                               lane_bytes + j * (kWave * 16), 0, kNonTemporal);
-    }
-}
-
-// Result of scanning one wave's run in registers.
+// First half of the scan of one wave's run: what the rest of the workgroup is
+// waiting for.  In place, it.x[j][k] becomes the inclusive fold of the lane's
+// granule up to k; lane_base[j] = combination of everything in the run before
+// the lane's granule in row j; wave_total = combination of the whole run (the
+// same value in every lane).  The items themselves are finished by
+// finish_wave_run, after the total has been handed on: how soon a tile's
+// aggregate is published decides how long other tiles wait for it.
 template <class A, int ROWS>
 struct WaveScan {
-    A lane_base[ROWS];   // combination of everything in the wave's run before the lane's granule in row j
-    A wave_total;        // combination of the whole run (same in every lane)
+    A lane_base[ROWS];
+    A wave_total;
 };
 
-// In place: it.x[j][k] becomes the inclusive fold of the lane's granule up to k.
 template <class A, int ROWS, int G, class Op>
 __device__ __forceinline__ WaveScan<A, ROWS> scan_wave_run(ThreadItems<A, ROWS, G> &it, Op op) {
     WaveScan<A, ROWS> r;
@@ -150,11 +156,11 @@ __device__ __forceinline__ WaveScan<A, ROWS> scan_wave_run(ThreadItems<A, ROWS, 
         inc[j] = it.x[j][G - 1];
     }
 #pragma unroll
-    for (int j = 0; j < ROWS; ++j) inc[j] = wave_inclusive_scan(inc[j], op);
+    for (int j = 0; j < ROWS; ++j) inc[j] = wave_inclusive_scan(inc[j], op);   // granule totals, lanes 0..l
     A carry = Op::identity();   // rows before row j
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-        A before_lane = wave_shift_up(inc[j], Op::identity());
+        const A before_lane = wave_shift_up(inc[j], Op::identity());
         r.lane_base[j] = op(carry, before_lane);
         carry = op(carry, read_lane(inc[j], kWave - 1));
     }
@@ -162,14 +168,16 @@ __device__ __forceinline__ WaveScan<A, ROWS> scan_wave_run(ThreadItems<A, ROWS, 
     return r;
 }
 
-// Turn the thread's items into final outputs given `prefix` = combination of
-// everything before this wave's run (tile prefix and earlier waves).
+// Second half: it.x[j][k] becomes the scan of the wave's run alone, inclusive
+// or exclusive (the very first element of the run then becomes the identity).
+// After this only the items stay in registers: what comes from outside the run
+// (earlier waves, earlier tiles) is one value that apply_prefix_and_store puts
+// in front of every item.
 template <bool INCLUSIVE, class A, int ROWS, int G, class Op>
-__device__ __forceinline__ void apply_prefix(ThreadItems<A, ROWS, G> &it, const WaveScan<A, ROWS> &ws,
-                                             const A &prefix, Op op) {
+__device__ __forceinline__ void finish_wave_run(ThreadItems<A, ROWS, G> &it, const WaveScan<A, ROWS> &ws, Op op) {
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-        const A base = op(prefix, ws.lane_base[j]);
+        const A base = ws.lane_base[j];
         if (INCLUSIVE) {
 #pragma unroll
             for (int k = 0; k < G; ++k) it.x[j][k] = op(base, it.x[j][k]);
@@ -178,6 +186,56 @@ __device__ __forceinline__ void apply_prefix(ThreadItems<A, ROWS, G> &it, const 
             for (int k = G - 1; k >= 1; --k) it.x[j][k] = op(base, it.x[j][k - 1]);
             it.x[j][0] = base;
         }
+    }
+}
+
+// Both halves in one pass, row by row, for callers that do not need the wave
+// total before the items are finished: no lane_base array is kept, which for
+// one-element granules (16-byte types) saves as many registers as the tile
+// itself takes.  Returns the combination of the whole run.
+template <bool INCLUSIVE, class A, int ROWS, int G, class Op>
+__device__ __forceinline__ A scan_wave_run_in_place(ThreadItems<A, ROWS, G> &it, Op op) {
+    A carry = Op::identity();   // rows before row j
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+#pragma unroll
+        for (int k = 1; k < G; ++k) it.x[j][k] = op(it.x[j][k - 1], it.x[j][k]);
+        const A inc = wave_inclusive_scan(it.x[j][G - 1], op);   // granule totals, lanes 0..l
+        if (INCLUSIVE && G == 1) {
+            it.x[j][0] = (j == 0) ? inc : op(carry, inc);
+        } else {
+            const A before_lane = wave_shift_up(inc, Op::identity());
+            const A base = (j == 0) ? before_lane : op(carry, before_lane);
+            if (INCLUSIVE) {
+#pragma unroll
+                for (int k = 0; k < G; ++k) it.x[j][k] = op(base, it.x[j][k]);
+            } else {
+#pragma unroll
+                for (int k = G - 1; k >= 1; --k) it.x[j][k] = op(base, it.x[j][k - 1]);
+                it.x[j][0] = base;
+            }
+        }
+        const A row_total = read_lane(inc, kWave - 1);
+        carry = (j == 0) ? row_total : op(carry, row_total);
+    }
+    return carry;
+}
+
+// Final outputs: `prefix` (combination of everything before this wave's run)
+// in front of every item, converted to the memory type and stored.
+template <class IO, int ROWS, class A, class Op, bool PIN>
+__device__ __forceinline__ void apply_prefix_and_store(const TileWindow &w, int lane_bytes,
+                                                       const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it,
+                                                       const A &prefix, Op op) {
+    constexpr int G = TileShape<IO, ROWS>::G;
+    const int at = pinned<PIN>(lane_bytes);
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        Granule<IO, G> g;
+#pragma unroll
+        for (int k = 0; k < G; ++k) g.e[k] = convert<IO>(op(prefix, it.x[j][k]));
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, g), w.rsrc, at + j * (kWave * 16), 0,
+                                               kNonTemporal);
     }
 }
 

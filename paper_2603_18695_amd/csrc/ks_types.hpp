@@ -102,10 +102,12 @@ struct MaxOp {
     __device__ __forceinline__ T operator()(T l, T r) const { return r > l ? r : l; }
 };
 
-// Apply l first, then r.  Carried in double: the offset b of a long composition
-// is a sum with heavy cancellation (it crosses zero while its terms stay O(100)),
-// so float32 intermediates cannot hold 1e-3 absolute accuracy over millions of
-// elements; the float32 inputs and outputs are converted at the memory boundary.
+// Apply l first, then r.  Carried in double: the offset b of a composition is a
+// sum with heavy cancellation (it crosses zero while partial sums over a few
+// hundred elements already reach several thousand, where float32 resolves no
+// better than 5e-4), so float32 intermediates cannot hold 1e-3 absolute accuracy,
+// not even inside one wave's run (tried: worst error 1.2e-3 at n = 5e5).  The
+// float32 inputs and outputs are converted at the memory boundary.
 struct AffineComposeOp {
     using acc = AffineF64;
     __device__ static AffineF64 identity() { return AffineF64{1.0, 0.0}; }
@@ -147,7 +149,7 @@ struct QuatMulOp {   // Hamilton product l * r
     }
 };
 
-// ---- memory type <-> accumulation type ---------------------------------------
+// ---- conversions between memory type and accumulation type ---------------------
 
 template <class To, class From>
 struct Convert {
