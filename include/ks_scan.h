@@ -135,9 +135,11 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *                  call return KS_ERR_UNSUPPORTED
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
- *   "split"        16-wave shape only: 1 = the look-back wave and the data waves run
- *                  separate loops (fewer registers, for wide element types), 0 = one
- *                  common loop, -1 = the type's default
+ *   "form"         16-wave shape only: 0 = one common loop for all waves, 1 = the
+ *                  look-back wave and the data waves run loops of their own (fewer
+ *                  registers, for wide element types), 2 = as 1, and every lane scans
+ *                  consecutive elements after an exchange through LDS (rows 8 or 9);
+ *                  -1 = the type's default
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
  *                  workgroup per tile, which is only deadlock-free if the hardware
  *                  starts workgroups in index order (experimental; waits stay bounded)

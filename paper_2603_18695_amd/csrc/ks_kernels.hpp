@@ -357,6 +357,9 @@ __device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__
         const A wave_total = scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
+        // The next tile is requested only now, after the totals are out: requested before the scan
+        // (the registers would be free) it measured 5-12 % slower, the descriptor traffic of the
+        // look-back wave then queues behind 135 KiB of loads in this compute unit's memory pipeline.
         const uint32_t next = tile + gridDim.x;
         RawItems<ROWS> nxt;
         TileWindow wnext;
@@ -376,6 +379,62 @@ __device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__
         } else {
             load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)next * TILE, TILE), lane_bytes,
                                      next + 1 == a.ntiles, cur);
+        }
+    }
+}
+
+// The data waves of the 16-wave shape in the blocked arrangement (ks_tile.hpp):
+// same protocol and barriers as data_wave_loop, but every wave passes its
+// granules through its LDS region `stage + (wave - 1) * Stage<ROWS>::SLOTS` on
+// the way in and on the way out, and scans ROWS consecutive granules per lane.
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+__device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in, IO *__restrict__ out,
+                                                       const LookbackArgs &a, TileExchange<typename Op::acc, WAVES> &x,
+                                                       u32x4 *stage) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
+    Op op;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
+    const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);   // striped view: global loads and stores
+    const int run_bytes = (wave - 1) * (kWave * ROWS * 16);   // start of the wave's run inside the tile
+    u32x4 *region = stage + (wave - 1) * Stage<ROWS>::SLOTS;
+    RawItems<ROWS> raw;
+    uint32_t valid_bytes;
+    {
+        const TileWindow w = tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE);
+        load_raw<ROWS, true>(w, lane_bytes, raw);
+        valid_bytes = w.valid_bytes;
+    }
+    for (uint32_t loop_tile = blockIdx.x;;) {
+        const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);   // see data_wave_loop
+        striped_to_blocked<ROWS>(region, raw);
+        ThreadItems<A, ROWS, S::G> cur;
+        unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
+        A lane_before;
+        const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
+        if (lane == 0) x.tot[wave] = to_words(wave_total);
+        __syncthreads();
+        const uint32_t next = tile + gridDim.x;
+        if (PREFETCH && next < a.ntiles) {   // after the totals are out, see data_wave_loop
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
+            load_raw<ROWS, true>(w, lane_bytes, raw);
+            valid_bytes = w.valid_bytes;
+        }
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
+        RawItems<ROWS> result;
+        apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
+        blocked_to_striped<ROWS>(region, result);
+        store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
+        if (next >= a.ntiles) return;
+        loop_tile = next;
+        if (!PREFETCH) {
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
+            load_raw<ROWS, true>(w, lane_bytes, raw);
+            valid_bytes = w.valid_bytes;
         }
     }
 }
@@ -464,7 +523,12 @@ __device__ __forceinline__ void common_wave_loop(const IO *__restrict__ in, IO *
     }
 }
 
-template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool SPLIT>
+// FORM: which loop the kernel runs (see above).
+constexpr int kFormCommon = 0;     // one loop for all waves
+constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in loops of their own, striped items
+constexpr int kFormBlocked = 2;    // the same with the blocked arrangement (LDS exchange)
+
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
 __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
                                                                      size_t n, uint64_t *desc, uint64_t *xdesc,
                                                                      uint32_t epoch, uint32_t ntiles,
@@ -476,13 +540,21 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *_
     }
     using A = typename Op::acc;
     if (blockIdx.x >= ntiles) return;
-    if constexpr (dedicated_lookback_wave(WAVES) && SPLIT) {
+    if constexpr (dedicated_lookback_wave(WAVES) && FORM != kFormCommon) {
         __shared__ TileExchange<A, WAVES> x;
         const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
-        if (threadIdx.x < kWave)
-            lookback_wave_loop<A, Op, WAVES>(a, x);
-        else
-            data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
+        if constexpr (FORM == kFormBlocked) {
+            __shared__ u32x4 stage[(WAVES - 1) * Stage<ROWS>::SLOTS];
+            if (threadIdx.x < kWave)
+                lookback_wave_loop<A, Op, WAVES>(a, x);
+            else
+                blocked_data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, stage);
+        } else {
+            if (threadIdx.x < kWave)
+                lookback_wave_loop<A, Op, WAVES>(a, x);
+            else
+                data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
+        }
     } else {
         common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, n, desc, xdesc, epoch, ntiles, spin_limit,
                                                                    abort_flag);

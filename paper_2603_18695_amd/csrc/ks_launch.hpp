@@ -20,7 +20,7 @@ inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 struct Shape {
     int waves, rows;
     bool prefetch;
-    bool split;   // 16 waves only: separate loops for the look-back wave and the data waves
+    int form;     // kFormCommon / kFormSeparate / kFormBlocked (the last two: 16 waves only)
 };
 
 // Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
@@ -28,10 +28,13 @@ struct Shape {
 // parked next tile 4 * ROWS, the rest goes to addresses and wave-scan temporaries.
 // The bound is loose: variants close to it may spill a few registers (they stay
 // correct); the defaults below were checked not to.
-template <class T, class A, int WAVES, int ROWS, bool PREFETCH, bool SPLIT>
+template <class T, class A, int WAVES, int ROWS, bool PREFETCH, int FORM>
 constexpr bool variant_fits() {
+    constexpr bool SPLIT = FORM != kFormCommon;
     if (SPLIT && !dedicated_lookback_wave(WAVES)) return false;   // nothing to separate
     if (WAVES == 16 && ROWS == 4) return false;                   // never competitive, not compiled
+    if (FORM == kFormBlocked)   // bounded by LDS; every element type compiles without spills at 8 and 9 rows
+        return (size_t)(WAVES - 1) * Stage<ROWS>::SLOTS * 16 <= 150 * 1024;
     constexpr int per_wave = 512 / (WAVES / 4 > 0 ? WAVES / 4 : 1);
     constexpr int budget = per_wave > 256 ? 256 : per_wave;
     constexpr int data = 4 * ROWS * (int)(sizeof(A) / sizeof(T));
@@ -41,27 +44,20 @@ constexpr bool variant_fits() {
     return data + parked + other <= budget;
 }
 
-// Default shape per element class: the best measured on MI355X.
-//   4-byte elements    16 waves, 9 rows, prefetch, common loop    float32 sum 2^28: 6.2 TB/s
-//   8-byte elements    16 waves, 9 rows, prefetch, separate loops uint64 sum 2^27:  5.6 TB/s
-//   16-byte elements   16 waves, 12 rows, separate loops          (no register spills for any of them)
-//     arg-max struct   16 waves, 16 rows, separate loops          2^26: 5.1 TB/s
-//   affine (double accumulator, 8-byte element)  16 waves, 8 rows, separate loops   2^26: 4.7 TB/s
+// Default shape per element class: the best measured on MI355X, always 15 data
+// waves + 1 look-back wave, 9 rows, next tile prefetched.
+//   4-byte elements   common loop                            float32 sum 2^28: 6.25 TB/s
+//   everything wider  separate loops, blocked arrangement    uint64 sum 2^27: 5.7 TB/s,
+//                     affine 2^26: 5.1, arg-max struct 2^26: 5.3
 // The 4-byte kernels keep the common loop: with their small register footprint
 // nothing is gained from separating the loops, and the compiler's schedule of
-// the common loop measured 5 % faster (6.25 against 5.9 TB/s).
+// the common loop measured 4-5 % faster (6.25 against 6.0 TB/s; blocked 5.8).
 template <class T, class A>
 struct PairDefaults {
     static constexpr Shape shape() {
-        if (sizeof(A) == 4) return Shape{16, 9, true, false};
-        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{16, 9, true, true};
-        if (sizeof(A) == sizeof(T)) return Shape{16, 12, false, true};
-        return Shape{16, 8, false, true};
+        if (sizeof(A) == 4) return Shape{16, 9, true, kFormCommon};
+        return Shape{16, 9, true, kFormBlocked};
     }
-};
-template <>
-struct PairDefaults<ArgmaxI32Cnt64, ArgmaxI32Cnt64> {
-    static constexpr Shape shape() { return Shape{16, 16, false, true}; }
 };
 
 // T = element type in memory; A = Op::acc = type of aggregates, seeds and descriptors.
@@ -83,8 +79,8 @@ struct Pair {
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
         if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
         if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
-        if (o.split >= 0) s.split = o.split != 0;
-        if (!dedicated_lookback_wave(s.waves)) s.split = false;
+        if (o.form >= 0) s.form = (int)o.form;
+        if (!dedicated_lookback_wave(s.waves)) s.form = kFormCommon;
         return s;
     }
 
@@ -113,12 +109,12 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
-    template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool SPLIT>
+    template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
     static int launch_lookback(const ScanCall &c) {
-        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH, SPLIT>()) {
+        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH, FORM>()) {
             return KS_ERR_UNSUPPORTED;   // this shape would spill registers for this element type
         } else {
-            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, SPLIT>;
+            auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM>;
             constexpr int kThreads = WAVES * kWave;
             const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
@@ -174,19 +170,20 @@ struct Pair {
         }
     }
 
-    template <int WAVES, int ROWS, bool SPLIT>
+    template <int WAVES, int ROWS, int FORM>
     static int lookback_flags_dispatch(const ScanCall &c, bool pf) {
         if (c.inclusive)
-            return pf ? launch_lookback<WAVES, ROWS, true, true, SPLIT>(c) : launch_lookback<WAVES, ROWS, true, false, SPLIT>(c);
-        return pf ? launch_lookback<WAVES, ROWS, false, true, SPLIT>(c) : launch_lookback<WAVES, ROWS, false, false, SPLIT>(c);
+            return pf ? launch_lookback<WAVES, ROWS, true, true, FORM>(c) : launch_lookback<WAVES, ROWS, true, false, FORM>(c);
+        return pf ? launch_lookback<WAVES, ROWS, false, true, FORM>(c) : launch_lookback<WAVES, ROWS, false, false, FORM>(c);
     }
 
     template <int WAVES, int ROWS>
     static int lookback_pf_dispatch(const ScanCall &c, const Shape &s) {
         if constexpr (dedicated_lookback_wave(WAVES)) {
-            if (s.split) return lookback_flags_dispatch<WAVES, ROWS, true>(c, s.prefetch);
+            if (s.form == kFormSeparate) return lookback_flags_dispatch<WAVES, ROWS, kFormSeparate>(c, s.prefetch);
+            if (s.form == kFormBlocked) return lookback_flags_dispatch<WAVES, ROWS, kFormBlocked>(c, s.prefetch);
         }
-        return lookback_flags_dispatch<WAVES, ROWS, false>(c, s.prefetch);
+        return lookback_flags_dispatch<WAVES, ROWS, kFormCommon>(c, s.prefetch);
     }
 
     template <int WAVES>

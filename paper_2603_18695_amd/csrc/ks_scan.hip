@@ -192,7 +192,7 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "rows")) return &o.rows;
     if (!std::strcmp(name, "waves")) return &o.waves;
     if (!std::strcmp(name, "prefetch")) return &o.prefetch;
-    if (!std::strcmp(name, "split")) return &o.split;
+    if (!std::strcmp(name, "form")) return &o.form;
     if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
     if (!std::strcmp(name, "last_grid")) return &o.last_grid;
     if (!std::strcmp(name, "last_resident_per_cu")) return &o.last_resident_per_cu;
@@ -210,7 +210,7 @@ int ks_set_option(const char *name, long long value) {
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;
     if (slot == &o.prefetch && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
-    if (slot == &o.split && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.form && !(value >= -1 && value <= 2)) return KS_ERR_INVALID_ARG;
     *slot = value;
     return KS_OK;
 }

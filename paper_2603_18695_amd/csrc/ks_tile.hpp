@@ -239,4 +239,137 @@ __device__ __forceinline__ void apply_prefix_and_store(const TileWindow &w, int 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Blocked arrangement.  The striped arrangement above costs one 64-lane scan per
+// row: about 90 vector instructions per KiB for a 16-byte element, half a tile
+// period at full memory rate.  Here each wave passes its granules through a
+// private LDS region so that lane l ends up with ROWS CONSECUTIVE granules of
+// the run (global accesses stay striped and coalesced, paper Sec. IV-C; the
+// exchange replaces the shuffles of Sec. IV-A by LDS).  Element order inside a
+// wave is then (lane, granule, position): a serial scan in registers and ONE
+// 64-lane scan of the lane totals per tile.
+//
+// LDS layout of a wave's region, in 16-byte slots: granule g of the run (g =
+// row * 64 + lane in the striped view, g = lane * ROWS + i in the blocked view)
+// sits at slot (g / ROWS) * STRIDE + g % ROWS with STRIDE = ROWS | 1: an odd
+// lane stride keeps the blocked 16-byte accesses of 16 neighbouring lanes on
+// distinct banks.  A wave's LDS instructions execute in order, and the wait
+// between the two phases makes that explicit; no other wave touches the region,
+// so no barrier is needed.
+// ---------------------------------------------------------------------------
+template <int ROWS>
+struct Stage {
+    static constexpr int STRIDE = ROWS | 1;
+    static constexpr int SLOTS = kWave * STRIDE;   // per wave
+};
+
+constexpr int kWaitLds = 0xC07F;   // s_waitcnt lgkmcnt(0), other counters untouched (gfx9 encoding)
+
+template <int ROWS>
+__device__ __forceinline__ int stage_slot_of_striped(int row, int lane) {
+    const int g = row * kWave + lane;
+    return (g / ROWS) * Stage<ROWS>::STRIDE + g % ROWS;
+}
+
+// Registers hold the striped view on entry and the blocked view on return.
+template <int ROWS>
+__device__ __forceinline__ void striped_to_blocked(u32x4 *region, RawItems<ROWS> &r) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) region[stage_slot_of_striped<ROWS>(j, lane)] = r.v[j];
+    __builtin_amdgcn_s_waitcnt(kWaitLds);
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) r.v[i] = region[lane * Stage<ROWS>::STRIDE + i];
+}
+
+template <int ROWS>
+__device__ __forceinline__ void blocked_to_striped(u32x4 *region, RawItems<ROWS> &r) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) region[lane * Stage<ROWS>::STRIDE + i] = r.v[i];
+    __builtin_amdgcn_s_waitcnt(kWaitLds);
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) r.v[j] = region[stage_slot_of_striped<ROWS>(j, lane)];
+}
+
+// Blocked raw granules -> accumulation type; x[i][k] = element k of the lane's
+// i-th consecutive granule.  run_bytes = byte offset of the wave's run inside
+// the tile (for the identity fix-up of a partial tile).
+template <class IO, int ROWS, class Op>
+__device__ __forceinline__ void unpack_blocked(const RawItems<ROWS> &raw, int run_bytes, uint32_t valid_bytes, bool partial,
+                                               ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+    using A = typename Op::acc;
+    constexpr int G = TileShape<IO, ROWS>::G;
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+        Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, raw.v[i]);
+#pragma unroll
+        for (int k = 0; k < G; ++k) it.x[i][k] = convert<A>(g.e[k]);
+    }
+    if (partial) {
+        const int lane = threadIdx.x & (kWave - 1);
+        const int at0 = pinned<true>(run_bytes + lane * (ROWS * 16));
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) {
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                const int at = at0 + i * 16 + k * (int)sizeof(IO);
+                if ((uint32_t)at >= valid_bytes) it.x[i][k] = Op::identity();
+            }
+        }
+    }
+}
+
+// Serial inclusive scan of the lane's ROWS * G consecutive elements, then one
+// wave scan of the lane totals.  Returns the combination of the whole run;
+// lane_before = combination of the lanes before this one.
+template <class A, int ROWS, int G, class Op>
+__device__ __forceinline__ A scan_blocked_run(ThreadItems<A, ROWS, G> &it, A &lane_before, Op op) {
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            if (i == 0 && k == 0) continue;
+            const A &prev = (k == 0) ? it.x[i - 1][G - 1] : it.x[i][k - 1];
+            it.x[i][k] = op(prev, it.x[i][k]);
+        }
+    }
+    const A upto = wave_inclusive_scan(it.x[ROWS - 1][G - 1], op);
+    lane_before = wave_shift_up(upto, Op::identity());
+    return read_lane(upto, kWave - 1);
+}
+
+// Final outputs of the blocked view as raw granules: `before` (everything
+// before this lane's first element) in front of every item, shifted by one
+// element for the exclusive scan.
+template <bool INCLUSIVE, class IO, int ROWS, class A, class Op>
+__device__ __forceinline__ void apply_blocked(const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it, const A &before, Op op,
+                                              RawItems<ROWS> &out) {
+    constexpr int G = TileShape<IO, ROWS>::G;
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+        Granule<IO, G> g;
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            if (INCLUSIVE) {
+                g.e[k] = convert<IO>(op(before, it.x[i][k]));
+            } else if (i == 0 && k == 0) {
+                g.e[k] = convert<IO>(before);
+            } else {
+                const A &prev = (k == 0) ? it.x[i - 1][G - 1] : it.x[i][k - 1];
+                g.e[k] = convert<IO>(op(before, prev));
+            }
+        }
+        out.v[i] = __builtin_bit_cast(u32x4, g);
+    }
+}
+
+template <int ROWS, bool PIN>
+__device__ __forceinline__ void store_raw(const TileWindow &w, int lane_bytes, const RawItems<ROWS> &raw) {
+    const int at = pinned<PIN>(lane_bytes);
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j)
+        __builtin_amdgcn_raw_buffer_store_b128(raw.v[j], w.rsrc, at + j * (kWave * 16), 0, kNonTemporal);
+}
+
 }  // namespace ks

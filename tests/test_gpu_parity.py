@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 def ks():
     import paper_2603_18695_amd as ks
     yield ks
-    for name, v in [("waves", 0), ("rows", 0), ("prefetch", -1), ("split", -1), ("grid_mode", 0), ("wgs_per_cu", 0),
+    for name, v in [("waves", 0), ("rows", 0), ("prefetch", -1), ("form", -1), ("grid_mode", 0), ("wgs_per_cu", 0),
                     ("spin_limit", 1 << 20)]:
         ks.ks_set_option(name, v)
 
@@ -36,11 +36,7 @@ def tile_elems(ks, dtype, waves, rows, lookback=True):
 
 def default_shape(ks, dtype):
     """(waves, rows) the library picks for the look-back kernel of this element type."""
-    if dtype == "affine_f32":
-        return 16, 8
-    if dtype == "argmax_i32_cnt64":
-        return 16, 16
-    return {4: (16, 9), 8: (16, 9), 16: (16, 12)}[ks.ks_elem_bytes(dtype)]
+    return 16, 9
 
 
 RTS_SHAPE = (4, 4)   # tile of the reduce-then-scan kernels
@@ -160,14 +156,14 @@ def test_in_place_and_misaligned_pointers(ks):
             assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
 
 
-@pytest.mark.parametrize("waves,split", [(4, 0), (8, 0), (16, 0), (16, 1)])
+@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2)])
 @pytest.mark.parametrize("rows", [4, 8, 9, 12, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
-def test_lookback_variants(ks, waves, split, rows, prefetch):
+def test_lookback_variants(ks, waves, form, rows, prefetch):
     ks.ks_set_option("waves", waves)
     ks.ks_set_option("rows", rows)
     ks.ks_set_option("prefetch", prefetch)
-    ks.ks_set_option("split", split)
+    ks.ks_set_option("form", form)
     ran = 0
     try:
         for dtype, op in [("f32", "sum"), ("i32", "sum"), ("u64", "sum"), ("affine_f32", "affine_compose"),
@@ -177,7 +173,7 @@ def test_lookback_variants(ks, waves, split, rows, prefetch):
             for n in [tile * 700 + 3, tile * 64 + 1]:
                 x = random_input(dtype, op, n, seed=rows * 10 + prefetch)
                 for inclusive in (True, False):
-                    say(f"[case] waves={waves} split={split} rows={rows} prefetch={prefetch} ({dtype},{op}) n={n} incl={inclusive}")
+                    say(f"[case] waves={waves} form={form} rows={rows} prefetch={prefetch} ({dtype},{op}) n={n} incl={inclusive}")
                     try:
                         got = run(ks, dtype, op, x, inclusive, algo="lookback")
                     except ks.KsError as e:
@@ -191,7 +187,7 @@ def test_lookback_variants(ks, waves, split, rows, prefetch):
         ks.ks_set_option("waves", 0)
         ks.ks_set_option("rows", 0)
         ks.ks_set_option("prefetch", -1)
-        ks.ks_set_option("split", -1)
+        ks.ks_set_option("form", -1)
     if ran == 0:
         pytest.skip("no element type fits this shape; every call was refused with KS_ERR_UNSUPPORTED")
 
