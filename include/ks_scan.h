@@ -79,6 +79,18 @@ typedef enum {
 } ks_algo;
 
 /*
+ * Element-wise maps T -> T for the map-fused scan (paper Sec. IV-A: the
+ * high-level interface scan(f, op, src)).  The map is applied as elements are
+ * loaded; the output has the input's element type.
+ */
+typedef enum {
+    KS_MAP_IDENTITY = 0,
+    KS_MAP_SQUARE = 1,  /* x * x (integers wrap)                                            */
+    KS_MAP_ABS = 2,     /* |x| (the most negative integer maps to itself)                   */
+    KS_MAP_NONZERO = 3  /* x != 0 ? 1 : 0, e.g. sum scan = positions of a stream compaction */
+} ks_map;
+
+/*
  * Scan n elements of `in` into `out` on `stream` (paper Sec. V-B).
  * Uses a library-owned workspace cached per (device, stream); the first call on
  * a stream, or a call needing a larger workspace, allocates device memory (and
@@ -92,6 +104,20 @@ typedef enum {
  */
 int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n,
             void *stream);
+
+/*
+ * Map-fused scan (paper Sec. IV-A, scan(f, op, src)):
+ *     out[i] = f(in[0]) op f(in[1]) op ... op f(in[i])     (inclusive)
+ * with f one of ks_map; arguments, workspace, stream behaviour and errors as for
+ * ks_scan.  KS_MAP_IDENTITY is ks_scan.  Instantiated (dtype, map, op) triples:
+ * see ks_map_supported; others return KS_ERR_UNSUPPORTED.  Mapped scans run in
+ * the element class's default kernel shape (the tuning options do not apply).
+ */
+int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void *in, void *out,
+                size_t n, void *stream);
+
+/* 1 if ks_scan_map accepts this (dtype, map, op), else 0. */
+int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op);
 
 /*
  * Bytes of device scratch ks_scan_with_temp needs for this problem (the paper's

@@ -152,6 +152,41 @@ def scan(op: str, dt: str | None, x: np.ndarray, inclusive: bool = True) -> np.n
     return ScanStream(op, dt, inclusive).feed(x)
 
 
+def apply_map(name: str, x: np.ndarray) -> np.ndarray:
+    """The element-wise map f of the map-fused scan ``scan(f, op, src)`` (paper Sec. IV-A).
+
+    identity: x;  square: x * x (integers wrap in their own width; float32 inputs are squared in
+    float64, where the product of two float32 values is exact);  abs: |x| (the most negative integer
+    maps to itself);  nonzero: 1 where x != 0 else 0, in x's type.
+    """
+    x = np.asarray(x)
+    if name == "identity":
+        return x
+    if name == "square":
+        if np.issubdtype(x.dtype, np.floating):
+            y = x.astype(np.float64)
+            return y * y
+        with np.errstate(over="ignore"):
+            u = x.view(np.dtype(f"u{x.dtype.itemsize}"))
+            return (u * u).view(x.dtype)
+    if name == "abs":
+        if np.issubdtype(x.dtype, np.floating):
+            return np.abs(x)
+        with np.errstate(over="ignore"):
+            return np.where(x < 0, (0 - x.view(np.dtype(f"u{x.dtype.itemsize}"))).view(x.dtype), x)
+    if name == "nonzero":
+        return (x != 0).astype(x.dtype)
+    raise ValueError(f"unknown map {name!r}")
+
+
+def mapped_scan(map_name: str, op: str, dt: str, x: np.ndarray, inclusive: bool = True) -> np.ndarray:
+    """out[i] = f(x[0]) op ... op f(x[i]) (paper Sec. IV-A): the map, then the plain sequential scan."""
+    y = apply_map(map_name, x)
+    if y.dtype == np.float64 and dt == "f32":
+        dt = "f64"   # squares of float32 values, held exactly in float64
+    return scan(op, dt, np.ascontiguousarray(y), inclusive)
+
+
 def fold_scan(op, xs, inclusive=True, identity=None):
     """Pure-Python left fold over arbitrary objects: the definition itself.
 

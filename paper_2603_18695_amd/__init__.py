@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libks_scan.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it with `python -m paper_2603_18695_amd.build` "
+        f"{LIB_PATH} is missing: build it with `python paper_2603_18695_amd/build.py` "
         "(hipcc, --offload-arch=gfx950). There is no fallback path.")
 
 _lib = ctypes.CDLL(LIB_PATH)
@@ -31,14 +31,20 @@ DTYPES = {"i32": 0, "u32": 1, "i64": 2, "u64": 3, "f32": 4, "f64": 5, "affine_f3
           "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9}
 OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "mat2_mul": 5, "quat_mul": 6}
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
+MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3}
 
-EXPORTS = ["ks_scan", "ks_scan_temp_bytes", "ks_scan_with_temp", "ks_scan_check", "ks_pair_supported",
+EXPORTS = ["ks_scan", "ks_scan_map", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+           "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
 
 _vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan.restype = _i
+_lib.ks_scan_map.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.ks_scan_map.restype = _i
+_lib.ks_map_supported.argtypes = [_i, _i, _i]
+_lib.ks_map_supported.restype = _i
 _lib.ks_scan_temp_bytes.argtypes = [_i, _i, _i, _sz]
 _lib.ks_scan_temp_bytes.restype = _sz
 _lib.ks_scan_with_temp.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp, _sz, _vp]
@@ -108,6 +114,22 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
         _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
                             _stream_ptr(stream)), "ks_scan")
     return out
+
+
+def ks_scan_map(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, map: str, op: str, inclusive: bool = True,
+                stream=None) -> torch.Tensor:
+    """out = scan(op, map(inp)): the map-fused scan, library-owned workspace.  Asynchronous on the stream."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != n:
+        raise ValueError("inp and out differ in size")
+    with torch.cuda.device(inp.device):
+        _check(_lib.ks_scan_map(DTYPES[dtype], MAPS[map], OPS[op], int(bool(inclusive)), inp.data_ptr(),
+                                out.data_ptr(), n, _stream_ptr(stream)), "ks_scan_map")
+    return out
+
+
+def ks_map_supported(dtype: str, map: str, op: str) -> bool:
+    return bool(_lib.ks_map_supported(DTYPES[dtype], MAPS[map], OPS[op]))
 
 
 def ks_scan_temp_bytes(*, dtype: str, op: str, n: int, algo: str = "auto") -> int:

@@ -75,6 +75,7 @@ struct Pair {
 
     static Shape lookback_shape() {
         Shape s = PairDefaults<T, A>::shape();
+        if (MapOf<Op>::mapped) return s;
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
         if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
@@ -103,7 +104,8 @@ struct Pair {
         if (m > tile) {
             m = ceil_div(m, tile);
             total = align_up(m * sizeof(A), 256);
-            if (m > Pair<A, Op>::tile_elems(kRtsRows)) total += Pair<A, Op>::temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, m);
+            using Upper = Pair<A, typename MapOf<Op>::unmapped>;
+            if (m > Upper::tile_elems(kRtsRows)) total += Upper::temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, m);
         }
         return total > 0 ? total : 256;
     }
@@ -199,6 +201,11 @@ struct Pair {
     }
 
     static int run_lookback(const ScanCall &c) {
+        if constexpr (MapOf<Op>::mapped) {
+            // mapped pairs are compiled in their element class's default shape only
+            constexpr Shape d = PairDefaults<T, A>::shape();
+            return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
+        }
         const Shape s = lookback_shape();
         switch (s.waves) {
             case 4: return lookback_rows_dispatch<4>(c, s);
@@ -232,7 +239,9 @@ struct Pair {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return set_hip_error(e);
         // aggregates -> exclusive prefixes of the tiles, in place (scratch is 256-byte aligned)
-        int st = Pair<A, Op>::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
+        // (the map has been applied by the reduction; the levels above combine plain accumulators)
+        using Upper = Pair<A, typename MapOf<Op>::unmapped>;
+        int st = Upper::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
         if (st != KS_OK) return st;
         return launch_tile_scan(inclusive, in, out, n, agg, s);
     }

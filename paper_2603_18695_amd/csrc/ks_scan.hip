@@ -22,6 +22,7 @@ const PairEntry *pair_entry_i32(int, int);
 const PairEntry *pair_entry_i64(int, int);
 const PairEntry *pair_entry_float(int, int);
 const PairEntry *pair_entry_struct(int, int);
+const PairEntry *pair_entry_mapped(int, int, int);
 
 const PairEntry *pair_entry(int dtype, int op) {
     if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT) return nullptr;
@@ -116,14 +117,14 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
     return e->run(c);
 }
 
-int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
-    const PairEntry *e = nullptr;
-    int st = validate(dtype, op, in, out, n, &e);
-    if (st != KS_OK || n == 0) return st;
+// Common part of ks_scan and ks_scan_map: library-owned, epoch-tagged workspace per (device, stream).
+static int scan_with_library_workspace(const PairEntry *e, int inclusive, const void *in, void *out, size_t n,
+                                       void *stream) {
     const ks_algo algo = e->pick_algo(n);
     const size_t need = e->temp_bytes(algo, n);
     std::lock_guard<std::mutex> lock(g_mutex);
     const DeviceInfo *dev = nullptr;
+    int st;
     if ((st = device_info(&dev)) != KS_OK) return st;
     Workspace &ws = g_workspaces[std::make_pair(dev->device, (hipStream_t)stream)];
     bool fresh = false;
@@ -150,6 +151,30 @@ int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, 
     if (algo == KS_ALGO_LOOKBACK) ++ws.epoch;
     ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, ws.epoch, false, dev};
     return e->run(c);
+}
+
+int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
+    const PairEntry *e = nullptr;
+    int st = validate(dtype, op, in, out, n, &e);
+    if (st != KS_OK || n == 0) return st;
+    return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void *in, void *out, size_t n,
+                void *stream) {
+    if (map == KS_MAP_IDENTITY) return ks_scan(dtype, op, inclusive, in, out, n, stream);
+    const PairEntry *plain = nullptr;
+    int st = validate(dtype, op, in, out, n, &plain);   // pointers, alignment, overlap: as for the plain pair
+    if (st != KS_OK) return st;
+    const PairEntry *e = pair_entry_mapped((int)dtype, (int)map, (int)op);
+    if (!e) return KS_ERR_UNSUPPORTED;
+    if (n == 0) return KS_OK;
+    return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {
+    if (map == KS_MAP_IDENTITY) return ks_pair_supported(dtype, op);
+    return pair_entry_mapped((int)dtype, (int)map, (int)op) ? 1 : 0;
 }
 
 size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n) {

@@ -97,7 +97,8 @@ __device__ __forceinline__ void load_raw(const TileWindow &w, int lane_bytes, Ra
         raw.v[j] = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, at + j * (kWave * 16), 0, kNonTemporal);
 }
 
-// Raw granules -> accumulation type.  In a partial tile the elements past the
+// Raw granules -> accumulation type, through the operator's map if it has one
+// (scan(f, op, src), paper Sec. IV-A).  In a partial tile the elements past the
 // end (read as zero by the hardware) become the operator's identity.
 template <class IO, int ROWS, class Op, bool PIN>
 __device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw, int lane_bytes, uint32_t valid_bytes,
@@ -109,7 +110,7 @@ __device__ __forceinline__ void unpack_items(const RawItems<ROWS> &raw, int lane
     for (int j = 0; j < ROWS; ++j) {
         Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, raw.v[j]);
 #pragma unroll
-        for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(g.e[k]);
+        for (int k = 0; k < G; ++k) it.x[j][k] = convert<A>(typename MapOf<Op>::type()(g.e[k]));
     }
     if (partial) {
         const int at0 = pinned<PIN>(lane_bytes);   // keeps the element offsets out of the registers of full tiles
@@ -304,7 +305,7 @@ __device__ __forceinline__ void unpack_blocked(const RawItems<ROWS> &raw, int ru
     for (int i = 0; i < ROWS; ++i) {
         Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, raw.v[i]);
 #pragma unroll
-        for (int k = 0; k < G; ++k) it.x[i][k] = convert<A>(g.e[k]);
+        for (int k = 0; k < G; ++k) it.x[i][k] = convert<A>(typename MapOf<Op>::type()(g.e[k]));
     }
     if (partial) {
         const int lane = threadIdx.x & (kWave - 1);

@@ -149,6 +149,52 @@ struct QuatMulOp {   // Hamilton product l * r
     }
 };
 
+// ---- maps: scan(f, op, src) ----------------------------------------------------
+// Paper Sec. IV-A, the high-level interface: out[i] = f(src[0]) op ... op f(src[i]).
+// A map is a stateless functor T -> T applied to every element as it is loaded;
+// MappedOp<Op, Map> is Op with that map attached, and is what the kernels see.
+struct IdentityMap {
+    template <class T>
+    __device__ __forceinline__ T operator()(const T &x) const { return x; }
+};
+struct SquareMap {   // x * x; integers wrap
+    __device__ __forceinline__ float operator()(float x) const { return x * x; }
+    __device__ __forceinline__ double operator()(double x) const { return x * x; }
+    __device__ __forceinline__ int32_t operator()(int32_t x) const { return (int32_t)((uint32_t)x * (uint32_t)x); }
+    __device__ __forceinline__ uint32_t operator()(uint32_t x) const { return x * x; }
+    __device__ __forceinline__ int64_t operator()(int64_t x) const { return (int64_t)((uint64_t)x * (uint64_t)x); }
+    __device__ __forceinline__ uint64_t operator()(uint64_t x) const { return x * x; }
+};
+struct AbsMap {      // |x|; the most negative integer maps to itself (two's complement)
+    __device__ __forceinline__ float operator()(float x) const { return __builtin_fabsf(x); }
+    __device__ __forceinline__ double operator()(double x) const { return __builtin_fabs(x); }
+    __device__ __forceinline__ int32_t operator()(int32_t x) const { return x < 0 ? (int32_t)(0u - (uint32_t)x) : x; }
+    __device__ __forceinline__ int64_t operator()(int64_t x) const { return x < 0 ? (int64_t)(0ull - (uint64_t)x) : x; }
+};
+struct NonzeroMap {  // 1 where x != 0, else 0: a sum scan of it numbers the kept elements of a compaction
+    template <class T>
+    __device__ __forceinline__ T operator()(const T &x) const { return x != T(0) ? T(1) : T(0); }
+};
+
+template <class Op, class Map>
+struct MappedOp : Op {
+    using map = Map;
+    using unmapped = Op;
+};
+
+template <class Op, class = void>
+struct MapOf {
+    using type = IdentityMap;
+    using unmapped = Op;
+    static constexpr bool mapped = false;
+};
+template <class Op>
+struct MapOf<Op, decltype((void)sizeof(typename Op::map))> {
+    using type = typename Op::map;
+    using unmapped = typename Op::unmapped;
+    static constexpr bool mapped = true;
+};
+
 // ---- conversions between memory type and accumulation type ---------------------
 
 template <class To, class From>

@@ -56,6 +56,22 @@ def test_enums_and_sizes(ks):
     assert not ks.ks_pair_supported("affine_f32", "sum")
 
 
+def test_map_triples(ks):
+    for triple in [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
+                   ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]:
+        assert ks.ks_map_supported(*triple), triple
+    assert ks.ks_map_supported("u64", "identity", "sum")          # identity = the plain pair
+    assert not ks.ks_map_supported("affine_f32", "square", "affine_compose")
+    assert not ks.ks_map_supported("f32", "nonzero", "min")
+    lib = ks.raw_library()
+    # an unknown triple is refused before any GPU work; n == 0 of a known one is a no-op
+    assert lib.ks_scan_map(ks.DTYPES["f32"], ks.MAPS["nonzero"], ks.OPS["min"], 1, 0x10000000, 0x20000000, 16, None) \
+        == ks.KS_ERR_UNSUPPORTED
+    assert lib.ks_scan_map(ks.DTYPES["f32"], ks.MAPS["square"], ks.OPS["sum"], 1, None, None, 0, None) == ks.KS_OK
+    assert lib.ks_scan_map(ks.DTYPES["f32"], ks.MAPS["square"], ks.OPS["sum"], 1, None, 0x20000000, 16, None) \
+        == ks.KS_ERR_INVALID_ARG
+
+
 def test_validation_returns_before_any_gpu_work(ks):
     lib = ks.raw_library()
     F32, SUM, AFF = ks.DTYPES["f32"], ks.OPS["sum"], ks.OPS["affine_compose"]
@@ -116,6 +132,11 @@ def test_options_are_validated(ks):
         ks.ks_set_option("no_such_option", 1)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("grid_mode", 5)
+    ks.ks_set_option("form", 2)
+    assert ks.ks_get_option("form") == 2
+    ks.ks_set_option("form", -1)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("form", 3)
     assert ks.ks_get_option("no_such_option") == -1
 
 

@@ -9,6 +9,7 @@ import torch
 
 import ks_inputs
 import oracle
+from parity import FLOAT_TOL as FLOAT_TOL_PAIRS
 from parity import KINDS, assert_matches, random_input, reference, to_device, to_host
 
 pytestmark = pytest.mark.gpu
@@ -238,6 +239,48 @@ def test_abandoned_wait_is_reported_and_the_next_call_is_clean(ks):
         for api in ("plain", "with_temp"):
             got = run(ks, dtype, op, x, True, algo="lookback", api=api)
             assert_matches(dtype, op, got, reference(dtype, op, x, True), f"after timeout ({dtype},{op}) {api}")
+
+
+MAP_TRIPLES = [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
+               ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]
+
+
+@pytest.mark.parametrize("dtype,map_name,op", MAP_TRIPLES)
+def test_map_fused_scan(ks, dtype, map_name, op):
+    # scan(f, op, src): sizes around the look-back tile, the 64-tile window and the single-workgroup path
+    tile = tile_elems(ks, dtype, *default_shape(ks, dtype))
+    rts = tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)
+    oop, odt, npdt, _ = KINDS[(dtype, op)]
+    rng = np.random.default_rng(99)
+    for n in [1, 5, rts - 1, rts, rts + 1, tile - 1, tile + 1, 64 * tile + 1, 300 * tile + 12345]:
+        if np.issubdtype(npdt, np.integer):
+            x = (rng.integers(0, 3, size=n) * rng.integers(-1000, 1000, size=n)).astype(npdt)   # one third zeros
+        else:
+            x = rng.uniform(-2.0, 2.0, size=n).astype(npdt)
+        for inclusive in (True, False):
+            say(f"[case] map-fused ({dtype},{map_name},{op}) n={n} inclusive={inclusive}")
+            ref = oracle.mapped_scan(map_name, oop, odt, x, inclusive)
+            d_in = to_device(x)
+            d_out = torch.empty_like(d_in)
+            ks.ks_scan_map(d_in, d_out, dtype=dtype, map=map_name, op=op, inclusive=inclusive)
+            ks.ks_scan_check()
+            got = to_host(d_out, x.dtype)
+            if (dtype, op) in FLOAT_TOL_PAIRS:      # float sums: tolerance against the oracle's float64 answer
+                assert_matches(dtype, op, got, ref, f"map ({dtype},{map_name},{op}) n={n} incl={inclusive}")
+            else:
+                assert got.tobytes() == ref.tobytes(), (dtype, map_name, op, n, inclusive,
+                                                        int(np.flatnonzero(got != ref)[0]))
+    # the identity map is the plain scan
+    x = random_input(dtype, op, 3 * tile + 5, seed=3)
+    d_in = to_device(x)
+    a, b = torch.empty_like(d_in), torch.empty_like(d_in)
+    ks.ks_scan_map(d_in, a, dtype=dtype, map="identity", op=op)
+    ks.ks_scan(d_in, b, dtype=dtype, op=op)
+    ks.ks_scan_check()
+    if (dtype, op) in FLOAT_TOL_PAIRS:
+        assert torch.allclose(a, b, rtol=1e-4, atol=1e-3)
+    else:
+        assert torch.equal(a, b)
 
 
 # ---------------------------------------------------------------- the five benchmark configurations, full size

@@ -465,3 +465,55 @@ def test_input_recipe_is_stable_and_in_range():
     assert s["v"].min() >= 0 and s["v"].max() < 1 << 20
     # chunked generation: chunks() concatenated is whole()
     assert np.array_equal(np.concatenate(list(ks_inputs.chunks("f32_sum", 5000))), ks_inputs.whole("f32_sum", 5000))
+
+
+# ---------------------------------------------------------------- map-fused scan, scan(f, op, src) (paper Sec. IV-A)
+
+def test_mapped_scan_with_identity_map_is_the_plain_scan():
+    x = np.random.default_rng(5).integers(-9, 9, size=1000, dtype=np.int32)
+    assert np.array_equal(oracle.mapped_scan("identity", "sum", "i32", x), oracle.scan("sum", "i32", x))
+
+
+def test_square_sum_closed_form_sum_of_squares():
+    n = 5000
+    x = np.arange(1, n + 1, dtype=np.int32)
+    got = oracle.mapped_scan("square", "sum", "i32", x)
+    want = np.array([(k * (k + 1) * (2 * k + 1) // 6) % (1 << 32) for k in range(1, n + 1)], dtype=np.uint64)
+    assert np.array_equal(got.view(np.uint32).astype(np.uint64), want)      # wraps from k = 1861 on
+    # float32 inputs: squares exact in float64, prefix sums exact while they stay below 2^53
+    xf = np.arange(1, 2001, dtype=np.float32)
+    gotf = oracle.mapped_scan("square", "sum", "f32", xf)
+    assert gotf.dtype == np.float64
+    assert gotf.tolist() == [float(k * (k + 1) * (2 * k + 1) // 6) for k in range(1, 2001)]
+    # exclusive: shifted, zero in front
+    ex = oracle.mapped_scan("square", "sum", "f32", xf, inclusive=False)
+    assert ex[0] == 0.0 and np.array_equal(ex[1:], gotf[:-1])
+
+
+def test_square_map_rounds_nothing_for_float32_inputs():
+    x = np.random.default_rng(6).uniform(-3, 3, size=1000).astype(np.float32)
+    y = oracle.apply_map("square", x)
+    assert all(Fraction(float(a)) ** 2 == Fraction(float(b)) for a, b in zip(x[:200], y[:200]))
+
+
+def test_abs_max_is_running_maximum_of_magnitudes():
+    x = np.random.default_rng(7).normal(size=4000).astype(np.float32)
+    got = oracle.mapped_scan("abs", "max", "f32", x)
+    assert np.array_equal(got, np.maximum.accumulate(np.abs(x)))
+    assert np.all(np.diff(got) >= 0) and np.all(got >= np.abs(x))
+    xi = np.array([3, -7, 5, np.iinfo(np.int32).min, 9], dtype=np.int32)
+    # |INT32_MIN| wraps to itself, which is below every other magnitude in a signed maximum
+    assert oracle.mapped_scan("abs", "max", "i32", xi).tolist() == [3, 7, 7, 7, 9]
+
+
+def test_nonzero_sum_numbers_the_kept_elements_of_a_compaction():
+    rng = np.random.default_rng(8)
+    x = (rng.integers(0, 3, size=3000) * rng.integers(-5, 6, size=3000)).astype(np.int32)
+    excl = oracle.mapped_scan("nonzero", "sum", "i32", x, inclusive=False)
+    incl = oracle.mapped_scan("nonzero", "sum", "i32", x, inclusive=True)
+    kept = np.flatnonzero(x)
+    assert np.array_equal(excl[kept], np.arange(len(kept), dtype=np.int32))   # position of each kept element
+    assert incl[-1] == len(kept) and np.array_equal(incl, np.cumsum(x != 0).astype(np.int32))
+    compacted = np.empty(len(kept), dtype=np.int32)
+    compacted[excl[kept]] = x[kept]
+    assert np.array_equal(compacted, x[x != 0])
