@@ -89,6 +89,21 @@ def _stream_ptr(stream) -> int:
     return int(stream.cuda_stream)
 
 
+class _OnDeviceOf:
+    """Make the tensor's device current for the call; free when it already is (the common case)."""
+
+    def __init__(self, t: torch.Tensor):
+        self._guard = None if t.device.index == torch.cuda.current_device() else torch.cuda.device(t.device)
+
+    def __enter__(self):
+        if self._guard is not None:
+            self._guard.__enter__()
+
+    def __exit__(self, *exc):
+        if self._guard is not None:
+            self._guard.__exit__(*exc)
+
+
 def _nbytes(t: torch.Tensor) -> int:
     return t.numel() * t.element_size()
 
@@ -110,7 +125,7 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
     n = _elements(inp, dtype)
     if _elements(out, dtype) != n:
         raise ValueError("inp and out differ in size")
-    with torch.cuda.device(inp.device):
+    with _OnDeviceOf(inp):
         _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
                             _stream_ptr(stream)), "ks_scan")
     return out
@@ -122,7 +137,7 @@ def ks_scan_map(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, map: str, o
     n = _elements(inp, dtype)
     if _elements(out, dtype) != n:
         raise ValueError("inp and out differ in size")
-    with torch.cuda.device(inp.device):
+    with _OnDeviceOf(inp):
         _check(_lib.ks_scan_map(DTYPES[dtype], MAPS[map], OPS[op], int(bool(inclusive)), inp.data_ptr(),
                                 out.data_ptr(), n, _stream_ptr(stream)), "ks_scan_map")
     return out
@@ -144,7 +159,7 @@ def ks_scan_with_temp(inp: torch.Tensor, out: torch.Tensor, temp: torch.Tensor, 
         raise ValueError("inp and out differ in size")
     if not temp.is_cuda or not temp.is_contiguous():
         raise ValueError("temp must be a contiguous device tensor")
-    with torch.cuda.device(inp.device):
+    with _OnDeviceOf(inp):
         _check(_lib.ks_scan_with_temp(DTYPES[dtype], OPS[op], int(bool(inclusive)), ALGOS[algo], inp.data_ptr(),
                                       out.data_ptr(), n, temp.data_ptr(), _nbytes(temp), _stream_ptr(stream)),
                "ks_scan_with_temp")
