@@ -400,11 +400,17 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);   // striped view: global loads and stores
     const int run_bytes = (wave - 1) * (kWave * ROWS * 16);   // start of the wave's run inside the tile
     u32x4 *region = stage + (wave - 1) * Stage<ROWS>::SLOTS;
+    // When to request the next tile: for 16-byte elements before the scan (the registers are free
+    // once the tile is unpacked, and their scan is long enough for the read stream to run dry:
+    // arg-max struct 5.25 -> 5.5 TB/s), otherwise after the totals are out (see data_wave_loop;
+    // requested early, float32, uint64 and the affine type measured 1-10 % slower).
+    constexpr bool EARLY = PREFETCH && sizeof(IO) == 16;
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
         const TileWindow w = tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE);
         load_raw<ROWS, true>(w, lane_bytes, raw);
+        if (EARLY) settle<ROWS>(raw);
         valid_bytes = w.valid_bytes;
     }
     for (uint32_t loop_tile = blockIdx.x;;) {
@@ -412,12 +418,19 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
         striped_to_blocked<ROWS>(region, raw);
         ThreadItems<A, ROWS, S::G> cur;
         unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
+        if constexpr (EARLY) {
+            if (tile + gridDim.x < a.ntiles) {
+                const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
+                load_raw<ROWS, true>(w, lane_bytes, raw);
+                valid_bytes = w.valid_bytes;
+            }
+        }
         A lane_before;
         const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
         const uint32_t next = tile + gridDim.x;
-        if (PREFETCH && next < a.ntiles) {   // after the totals are out, see data_wave_loop
+        if (PREFETCH && !EARLY && next < a.ntiles) {
             const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
             valid_bytes = w.valid_bytes;
@@ -431,6 +444,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
         store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
         if (next >= a.ntiles) return;
         loop_tile = next;
+        if (EARLY) settle<ROWS>(raw);   // the wait for the early request belongs here, after the stores
         if (!PREFETCH) {
             const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
