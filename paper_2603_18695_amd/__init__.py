@@ -33,7 +33,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3}
 
-EXPORTS = ["ks_scan", "ks_scan_map", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -43,6 +43,8 @@ _lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan.restype = _i
 _lib.ks_scan_map.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_map.restype = _i
+_lib.ks_scan_strided.argtypes = [_i, _i, _i, _vp, _sz, _vp, _sz, _sz, _vp]
+_lib.ks_scan_strided.restype = _i
 _lib.ks_map_supported.argtypes = [_i, _i, _i]
 _lib.ks_map_supported.restype = _i
 _lib.ks_scan_temp_bytes.argtypes = [_i, _i, _i, _sz]
@@ -140,6 +142,19 @@ def ks_scan_map(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, map: str, o
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan_map(DTYPES[dtype], MAPS[map], OPS[op], int(bool(inclusive)), inp.data_ptr(),
                                 out.data_ptr(), n, _stream_ptr(stream)), "ks_scan_map")
+    return out
+
+
+def ks_scan_strided(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, n: int, in_stride: int = 1,
+                    out_stride: int = 1, inclusive: bool = True, stream=None) -> torch.Tensor:
+    """Scan of the strided views inp[::in_stride][:n] -> out[::out_stride][:n] of two contiguous device buffers
+    (strides in elements of `dtype`)."""
+    for t, stride in ((inp, in_stride), (out, out_stride)):
+        if n > 0 and _elements(t, dtype) < (n - 1) * stride + 1:
+            raise ValueError("tensor too small for the requested view")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_scan_strided(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), in_stride,
+                                    out.data_ptr(), out_stride, n, _stream_ptr(stream)), "ks_scan_strided")
     return out
 
 

@@ -51,6 +51,9 @@ struct PairEntry {
     size_t (*temp_bytes)(ks_algo algo, size_t n);
     ks_algo (*pick_algo)(size_t n);
     int (*run)(const ScanCall &call);   // returns ks_status; HIP failures via set_hip_error
+    // strided views: element i at in[i * in_stride] / out[i * out_stride]; temp as for reduce-then-scan
+    int (*run_strided)(int inclusive, const void *in, size_t in_stride, void *out, size_t out_stride, size_t n,
+                       void *temp, size_t temp_bytes, hipStream_t stream);
 };
 
 int set_hip_error(hipError_t e);   // records e, returns KS_ERR_HIP

@@ -620,6 +620,48 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict_
                                                op(seed, wave_carry), op);
 }
 
+// The same two kernels for a strided view at the lowest level (element i at
+// base[i * stride]); the aggregates and everything above them are contiguous
+// and go through the kernels above.
+template <class IO, class Op, int ROWS>
+__global__ __launch_bounds__(kBlock) void tile_reduce_strided_kernel(const IO *__restrict__ in, size_t in_stride,
+                                                                     size_t n,
+                                                                     typename Op::acc *__restrict__ aggregates) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    Op op;
+    const size_t tile = blockIdx.x;
+    ThreadItems<A, ROWS, S::G> cur;
+    load_items_strided<IO, ROWS, Op>(in, in_stride, n, tile * TILE + (threadIdx.x >> 6) * (size_t)S::WAVE_ELEMS, cur);
+    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    A aggregate;
+    (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+    if (threadIdx.x == 0) aggregates[tile] = aggregate;
+}
+
+template <class IO, class Op, int ROWS, bool INCLUSIVE>
+__global__ __launch_bounds__(kBlock) void tile_scan_strided_kernel(const IO *in, size_t in_stride, IO *out,
+                                                                   size_t out_stride, size_t n,
+                                                                   const typename Op::acc *__restrict__ seeds) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    Op op;
+    const size_t tile = blockIdx.x;
+    const size_t run_first = tile * TILE + (threadIdx.x >> 6) * (size_t)S::WAVE_ELEMS;
+    ThreadItems<A, ROWS, S::G> cur;
+    load_items_strided<IO, ROWS, Op>(in, in_stride, n, run_first, cur);
+    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    A aggregate;
+    const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+    finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
+    const A seed = seeds ? seeds[tile] : Op::identity();
+    apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, n, run_first, cur, op(seed, wave_carry), op);
+}
+
 template <int UNUSED = 0>
 __global__ void fill_zero_kernel(uint64_t *p, size_t words) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

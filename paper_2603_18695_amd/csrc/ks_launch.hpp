@@ -246,6 +246,40 @@ struct Pair {
         return launch_tile_scan(inclusive, in, out, n, agg, s);
     }
 
+    // Strided view at the lowest level, contiguous aggregates above it.  temp as for reduce-then-scan.
+    static int run_strided(bool inclusive, const T *in, size_t in_stride, T *out, size_t out_stride, size_t n,
+                           char *temp, size_t temp_bytes, hipStream_t s) {
+        const size_t tile = tile_elems(kRtsRows);
+        const size_t tiles = ceil_div(n, tile);
+        A *agg = nullptr;
+        if (tiles > 1) {
+            const size_t need = align_up(tiles * sizeof(A), 256);
+            if (need > temp_bytes) return KS_ERR_WORKSPACE;
+            agg = reinterpret_cast<A *>(temp);
+            hipLaunchKernelGGL((tile_reduce_strided_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s,
+                               in, in_stride, n, agg);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return set_hip_error(e);
+            using Upper = Pair<A, typename MapOf<Op>::unmapped>;
+            int st = Upper::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
+            if (st != KS_OK) return st;
+        }
+        if (inclusive)
+            hipLaunchKernelGGL((tile_scan_strided_kernel<T, Op, kRtsRows, true>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                               s, in, in_stride, out, out_stride, n, agg);
+        else
+            hipLaunchKernelGGL((tile_scan_strided_kernel<T, Op, kRtsRows, false>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                               s, in, in_stride, out, out_stride, n, agg);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? KS_OK : set_hip_error(e);
+    }
+
+    static int run_strided_entry(int inclusive, const void *in, size_t in_stride, void *out, size_t out_stride, size_t n,
+                                 void *temp, size_t temp_bytes, hipStream_t s) {
+        return run_strided(inclusive != 0, static_cast<const T *>(in), in_stride, static_cast<T *>(out), out_stride, n,
+                           static_cast<char *>(temp), temp_bytes, s);
+    }
+
     static int run(const ScanCall &c) {
         if (c.algo == KS_ALGO_LOOKBACK) return run_lookback(c);
         return run_rts(c.inclusive != 0, static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n,
@@ -253,7 +287,8 @@ struct Pair {
     }
 
     static const PairEntry *entry() {
-        static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run};
+        static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
+                                    &Pair::run_strided_entry};
         return &e;
     }
 };

@@ -52,6 +52,10 @@ struct Workspace {
     void *ptr = nullptr;
     size_t bytes = 0;
     uint32_t epoch = 0;   // last epoch handed out; descriptors carry (epoch << 2 | state)
+    // Aggregates of the strided path live in a buffer of their own: plain values written over the
+    // tagged descriptors above could be mistaken for a descriptor of a later epoch.
+    void *plain_ptr = nullptr;
+    size_t plain_bytes = 0;
 };
 std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
 
@@ -170,6 +174,43 @@ int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void 
     if (!e) return KS_ERR_UNSUPPORTED;
     if (n == 0) return KS_OK;
     return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, size_t in_stride, void *out,
+                    size_t out_stride, size_t n, void *stream) {
+    if (in_stride == 1 && out_stride == 1) return ks_scan(dtype, op, inclusive, in, out, n, stream);
+    if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
+    const PairEntry *e = pair_entry(dtype, op);
+    if (!e) return KS_ERR_UNSUPPORTED;
+    if (n == 0) return KS_OK;
+    if (!in || !out || in_stride == 0 || out_stride == 0) return KS_ERR_INVALID_ARG;
+    if (n > ((size_t)1 << 40) || in_stride > ((size_t)1 << 20) || out_stride > ((size_t)1 << 20)) return KS_ERR_INVALID_ARG;
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if ((a % e->elem_align) || (b % e->elem_align)) return KS_ERR_MISALIGNED;
+    // byte spans of the two views; the same view in place is fine, any other overlap of the spans is refused
+    const size_t span_in = ((n - 1) * in_stride + 1) * e->elem_bytes, span_out = ((n - 1) * out_stride + 1) * e->elem_bytes;
+    const bool same_view = a == b && in_stride == out_stride;
+    if (!same_view && a < b + span_out && b < a + span_in) return KS_ERR_OVERLAP;
+    const size_t need = e->temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, n);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    int st;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    Workspace &ws = g_workspaces[std::make_pair(dev->device, (hipStream_t)stream)];
+    if (ws.plain_bytes < need) {
+        if (ws.plain_ptr) (void)hipFree(ws.plain_ptr);   // waits for the device: nothing in flight uses it
+        ws.plain_ptr = nullptr;
+        ws.plain_bytes = 0;
+        const size_t want = need < ((size_t)1 << 16) ? ((size_t)1 << 16) : need;
+        hipError_t he = hipMalloc(&ws.plain_ptr, want);
+        if (he != hipSuccess) {
+            ws.plain_ptr = nullptr;
+            set_hip_error(he);
+            return KS_ERR_WORKSPACE;
+        }
+        ws.plain_bytes = want;
+    }
+    return e->run_strided(inclusive, in, in_stride, out, out_stride, n, ws.plain_ptr, ws.plain_bytes, (hipStream_t)stream);
 }
 
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {

@@ -72,6 +72,20 @@ def test_map_triples(ks):
         == ks.KS_ERR_INVALID_ARG
 
 
+def test_strided_validation(ks):
+    lib = ks.raw_library()
+    f32, su = ks.DTYPES["f32"], ks.OPS["sum"]
+    A, B = 0x10000000, 0x20000000
+    assert lib.ks_scan_strided(f32, su, 1, A, 3, B, 2, 0, None) == ks.KS_OK                     # n == 0: nothing to do
+    assert lib.ks_scan_strided(f32, su, 1, A, 0, B, 2, 16, None) == ks.KS_ERR_INVALID_ARG       # zero stride
+    assert lib.ks_scan_strided(f32, su, 1, A, 1 << 21, B, 2, 16, None) == ks.KS_ERR_INVALID_ARG   # stride limit
+    assert lib.ks_scan_strided(f32, su, 1, None, 3, B, 2, 16, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan_strided(f32, su, 1, A + 2, 3, B, 2, 16, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan_strided(f32, su, 1, A, 3, A + 4, 3, 16, None) == ks.KS_ERR_OVERLAP       # interleaved columns
+    assert lib.ks_scan_strided(f32, su, 1, A, 3, A, 2, 16, None) == ks.KS_ERR_OVERLAP           # same base, other stride
+    assert lib.ks_scan_strided(ks.DTYPES["f32"], ks.OPS["affine_compose"], 1, A, 3, B, 2, 16, None) == ks.KS_ERR_UNSUPPORTED
+
+
 def test_validation_returns_before_any_gpu_work(ks):
     lib = ks.raw_library()
     F32, SUM, AFF = ks.DTYPES["f32"], ks.OPS["sum"], ks.OPS["affine_compose"]

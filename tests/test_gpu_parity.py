@@ -283,6 +283,45 @@ def test_map_fused_scan(ks, dtype, map_name, op):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("dtype,op", [("i32", "sum"), ("f32", "sum"), ("u64", "max"),
+                                      ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")])
+def test_strided_views(ks, dtype, op):
+    # one column of a row-major [n, stride] matrix in, another layout out; the rest must stay untouched
+    rts = tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)
+    sizes = [1, 2, rts - 1, rts, rts + 1, 5 * rts + 3]
+    if dtype == "i32":
+        sizes.append(rts * rts + 5)      # two levels of aggregates
+    for n in sizes:
+        for in_stride, out_stride in [(3, 1), (1, 2), (5, 5)]:
+            x = random_input(dtype, op, n, seed=n % 89 + in_stride)
+            words = ks.ks_elem_bytes(dtype) // 4          # device storage in 32-bit words per element
+            host = to_device(x).reshape(n, -1).view(torch.int32).reshape(n, words)
+            d_in = torch.full((n, in_stride, words), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            d_in[:, 0, :] = host
+            sentinel = 0x3C3C3C3C
+            d_out = torch.full((n, out_stride, words), sentinel, dtype=torch.int32, device="cuda")
+            for inclusive in (True, False):
+                say(f"[case] strided ({dtype},{op}) n={n} strides=({in_stride},{out_stride}) inclusive={inclusive}")
+                d_out.fill_(sentinel)
+                ks.ks_scan_strided(d_in, d_out, dtype=dtype, op=op, n=n, in_stride=in_stride,
+                                   out_stride=out_stride, inclusive=inclusive)
+                ks.ks_scan_check()
+                got_words = d_out[:, 0, :].contiguous()
+                got = to_host(got_words.view(to_device(x).dtype).reshape(to_device(x).shape), x.dtype)
+                assert_matches(dtype, op, got, reference(dtype, op, x, inclusive),
+                               f"strided ({dtype},{op}) n={n} ({in_stride},{out_stride}) incl={inclusive}")
+                if out_stride > 1:
+                    assert bool((d_out[:, 1:, :] == sentinel).all()), "elements between the strides were written"
+            if in_stride == out_stride:      # the same view in place
+                say(f"[case] strided in place ({dtype},{op}) n={n} stride={in_stride}")
+                ks.ks_scan_strided(d_in, d_in, dtype=dtype, op=op, n=n, in_stride=in_stride, out_stride=in_stride)
+                ks.ks_scan_check()
+                got_words = d_in[:, 0, :].contiguous()
+                got = to_host(got_words.view(to_device(x).dtype).reshape(to_device(x).shape), x.dtype)
+                assert_matches(dtype, op, got, reference(dtype, op, x, True), f"strided in place ({dtype},{op}) n={n}")
+                assert bool((d_in[:, 1:, :] == 0x5A5A5A5A).all())
+
+
 # ---------------------------------------------------------------- the five benchmark configurations, full size
 
 def _full_config(ks, name, n=None, api="plain", algo="auto"):
