@@ -3,7 +3,9 @@
 //   scan_lookback_kernel   single pass, decoupled look-back (paper Sec. V-B)
 //   tile_reduce_kernel     reduce-then-scan, first kernel: one aggregate per tile
 //   tile_scan_kernel       reduce-then-scan, last kernel: scan a tile from a seed
+//   tile_*_strided_kernel  the same two for strided views (paper Sec. IV-C)
 //   fill_zero_kernel       clears caller-provided descriptors
+//   copy_kernel            vectorised copy, the bandwidth ceiling (paper Sec. IV-C)
 //
 // Tile descriptors (paper Sec. V-B: per-tile aggregate, inclusive prefix and a
 // partial / prefix status flag; Sec. IV-B for the hazard the flag guards).  The
@@ -250,6 +252,12 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 // 1/4 or 1/8 of the workgroup and wave 0 holds data like the others.
 // With PREFETCH the next tile's granules are requested before the look-back
 // wait and parked unconverted.
+//
+// The tile loop exists in three forms (template parameter FORM, below): one
+// common loop for all waves; for the 16-wave shape, loops of their own for the
+// look-back wave and the data waves, which keeps the look-back's registers
+// apart from the tile's; and the latter with the blocked arrangement of
+// ks_tile.hpp.  Which one a type uses by default was measured (ks_launch.hpp).
 // ---------------------------------------------------------------------------
 constexpr bool dedicated_lookback_wave(int waves) { return waves >= 16; }
 constexpr int data_waves(int waves) { return dedicated_lookback_wave(waves) ? waves - 1 : waves; }
@@ -258,7 +266,7 @@ constexpr int data_waves(int waves) { return dedicated_lookback_wave(waves) ? wa
 template <class A, int WAVES>
 struct TileExchange {
     typename WordsOf<A>::type tot[WAVES];     // per wave: combination of its run
-    typename WordsOf<A>::type carry[WAVES];   // per wave: combination of the runs before it (16-wave shape)
+    typename WordsOf<A>::type carry[WAVES];   // per wave: combination of the runs before it (separate loops)
     typename WordsOf<A>::type prefix;         // exclusive prefix of the tile, from the look-back
     uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
 };

@@ -2,14 +2,17 @@
 // thread's items in registers, and the per-wave combination (paper Sec. V-B,
 // second paragraph; Sec. IV-C for the wide loads and the items-per-thread idea).
 //
-// Register arrangement.  A workgroup of WAVES wave64s owns one tile.  Wave w
-// owns a contiguous run of 64*ROWS granules of 16 bytes; inside it, "row" j is
-// 64 consecutive granules and lane l holds granule l of every row.  Each global
-// access instruction of a wave therefore touches 1 KiB of consecutive bytes.
-// Element order inside a wave is (row, lane, position in granule), so the scan
-// is: fold inside each granule, one wave scan per row over the granule totals,
-// then a short serial chain over the ROWS row totals.  Operand order is kept at
-// every level, so non-commutative operators are safe.
+// Striped register arrangement (first part of the file).  A workgroup owns one
+// tile; each of its data waves owns a contiguous run of 64*ROWS granules of 16
+// bytes; inside it, "row" j is 64 consecutive granules and lane l holds granule
+// l of every row.  Each global access instruction of a wave therefore touches
+// 1 KiB of consecutive bytes.  Element order inside a wave is (row, lane,
+// position in granule), so the scan is: fold inside each granule, one wave scan
+// per row over the granule totals, then a short serial chain over the ROWS row
+// totals.  Operand order is kept at every level, so non-commutative operators
+// are safe.  The blocked arrangement (second part) keeps the striped global
+// accesses and exchanges the granules through LDS so that a lane holds ROWS
+// consecutive granules; strided views (last part) access single elements.
 //
 // IO is the element type in memory, A = Op::acc the type held in registers.
 #pragma once
