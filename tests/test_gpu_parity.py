@@ -322,6 +322,25 @@ def test_strided_views(ks, dtype, op):
                 assert bool((d_in[:, 1:, :] == 0x5A5A5A5A).all())
 
 
+def test_more_than_2_pow_32_elements(ks):
+    # 64-bit index arithmetic end to end: all-ones int32, closed form out[i] = i + 1 (mod 2^32), checked
+    # on the device chunk by chunk (16 GiB in, 16 GiB out; the sums wrap exactly once, at element 2^32 - 1)
+    n = (1 << 32) + 12345
+    say(f"[case] int32 all-ones n={n} (> 2^32 elements)")
+    d_in = torch.ones(n, dtype=torch.int32, device="cuda")
+    d_out = torch.empty_like(d_in)
+    ks.ks_scan(d_in, d_out, dtype="i32", op="sum")
+    ks.ks_scan_check()
+    step = 1 << 28
+    for at in range(0, n, step):
+        m = min(step, n - at)
+        want = (torch.arange(at + 1, at + 1 + m, dtype=torch.int64, device="cuda") & 0xFFFFFFFF)
+        got = d_out[at:at + m].to(torch.int64) & 0xFFFFFFFF
+        assert torch.equal(got, want), f"mismatch in chunk at {at}"
+    del d_in, d_out
+    torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------- the five benchmark configurations, full size
 
 def _full_config(ks, name, n=None, api="plain", algo="auto"):
