@@ -361,9 +361,16 @@ __device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__
         // The tile index is the same in every lane; saying so keeps it, and the buffer resources
         // derived from it, in scalar registers.
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
-        // from here on `cur` holds the scan of the wave's run alone
-        const A wave_total = scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
-        if (lane == 0) x.tot[wave] = to_words(wave_total);
+        // Commutative operators: the run's total first, by the shortest route, and the scan itself
+        // after the barrier (see reduce_wave_run_any_order).  From the scan on `cur` holds the scan
+        // of the wave's run alone.
+        if constexpr (Op::commutative) {
+            const A wave_total = reduce_wave_run_any_order<A, ROWS, S::G, Op>(cur, op);
+            if (lane == 0) x.tot[wave] = to_words(wave_total);
+        } else {
+            const A wave_total = scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
+            if (lane == 0) x.tot[wave] = to_words(wave_total);
+        }
         __syncthreads();
         // The next tile is requested only now, after the totals are out: requested before the scan
         // (the registers would be free) it measured 5-12 % slower, the descriptor traffic of the
@@ -375,6 +382,7 @@ __device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__
             wnext = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, true>(wnext, lane_bytes, nxt);
         }
+        if constexpr (Op::commutative) (void)scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
         const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
@@ -413,6 +421,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
     // arg-max struct 5.25 -> 5.5 TB/s), otherwise after the totals are out (see data_wave_loop;
     // requested early, float32, uint64 and the affine type measured 1-10 % slower).
     constexpr bool EARLY = PREFETCH && sizeof(IO) == 16;
+    constexpr bool TOTAL_FIRST = Op::commutative && !EARLY;   // uint64 sum: 5.73 -> 5.94 TB/s
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
@@ -423,26 +432,51 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
     }
     for (uint32_t loop_tile = blockIdx.x;;) {
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);   // see data_wave_loop
-        striped_to_blocked<ROWS>(region, raw);
         ThreadItems<A, ROWS, S::G> cur;
-        unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
-        if constexpr (EARLY) {
-            if (tile + gridDim.x < a.ntiles) {
+        A lane_before;
+        if constexpr (TOTAL_FIRST) {
+            // Commutative operators: the run's total straight from the striped registers while the
+            // LDS takes the granules, so that the totals are out (and the next tile requested) before
+            // the exchange and the scan (see reduce_wave_run_any_order).
+            const bool partial = tile + 1 == a.ntiles;
+            const uint32_t tile_valid_bytes = valid_bytes;
+            stage_striped<ROWS>(region, raw);
+            {
+                ThreadItems<A, ROWS, S::G> striped;
+                unpack_items<IO, ROWS, Op, true>(raw, lane_bytes, tile_valid_bytes, partial, striped);
+                const A wave_total = reduce_wave_run_any_order<A, ROWS, S::G, Op>(striped, op);
+                if (lane == 0) x.tot[wave] = to_words(wave_total);
+            }
+            __syncthreads();
+            RawItems<ROWS> blocked;
+            fetch_blocked<ROWS>(region, blocked);
+            if (PREFETCH && tile + gridDim.x < a.ntiles) {
+                const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
+                load_raw<ROWS, true>(w, lane_bytes, raw);
+                valid_bytes = w.valid_bytes;
+            }
+            unpack_blocked<IO, ROWS, Op>(blocked, run_bytes, tile_valid_bytes, partial, cur);
+            (void)scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
+        } else {
+            striped_to_blocked<ROWS>(region, raw);
+            unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
+            if constexpr (EARLY) {
+                if (tile + gridDim.x < a.ntiles) {
+                    const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
+                    load_raw<ROWS, true>(w, lane_bytes, raw);
+                    valid_bytes = w.valid_bytes;
+                }
+            }
+            const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
+            if (lane == 0) x.tot[wave] = to_words(wave_total);
+            __syncthreads();
+            if (PREFETCH && !EARLY && tile + gridDim.x < a.ntiles) {
                 const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
                 load_raw<ROWS, true>(w, lane_bytes, raw);
                 valid_bytes = w.valid_bytes;
             }
         }
-        A lane_before;
-        const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
-        if (lane == 0) x.tot[wave] = to_words(wave_total);
-        __syncthreads();
         const uint32_t next = tile + gridDim.x;
-        if (PREFETCH && !EARLY && next < a.ntiles) {
-            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
-            load_raw<ROWS, true>(w, lane_bytes, raw);
-            valid_bytes = w.valid_bytes;
-        }
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
         const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);

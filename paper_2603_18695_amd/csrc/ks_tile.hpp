@@ -205,6 +205,28 @@ __device__ __forceinline__ void finish_wave_run(ThreadItems<A, ROWS, G> &it, con
     }
 }
 
+// Combination of a whole wave's run for a COMMUTATIVE operator, by the shortest
+// route: every lane folds its own items, one wave reduction.  The time from the
+// arrival of a tile to the publication of its aggregate is on the critical path
+// of the whole scan (the next tile is only requested once the totals are out,
+// and other tiles wait for the aggregate), so the separate-loop forms take this
+// route first and scan afterwards, while the look-back wave is busy.  The value
+// can differ from the scan's own total in the last bits for floating point (a
+// different association); every output is still a valid association of its
+// prefix.  Items are not modified.
+template <class A, int ROWS, int G, class Op>
+__device__ __forceinline__ A reduce_wave_run_any_order(const ThreadItems<A, ROWS, G> &it, Op op) {
+    static_assert(Op::commutative, "order-free reduction needs a commutative operator");
+    A mine = it.x[0][0];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+#pragma unroll
+        for (int k = 0; k < G; ++k)
+            if (j != 0 || k != 0) mine = op(mine, it.x[j][k]);
+    }
+    return read_lane(wave_inclusive_scan(mine, op), kWave - 1);
+}
+
 // Both halves in one pass, row by row, for callers that do not need the wave
 // total before the items are finished: no lane_base array is kept, which for
 // one-element granules (16-byte types) saves as many registers as the tile
@@ -287,15 +309,28 @@ __device__ __forceinline__ int stage_slot_of_striped(int row, int lane) {
     return (g / ROWS) * Stage<ROWS>::STRIDE + g % ROWS;
 }
 
+// Striped view in registers -> the wave's LDS region ...
+template <int ROWS>
+__device__ __forceinline__ void stage_striped(u32x4 *region, const RawItems<ROWS> &striped) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) region[stage_slot_of_striped<ROWS>(j, lane)] = striped.v[j];
+}
+
+// ... and back out as the blocked view.
+template <int ROWS>
+__device__ __forceinline__ void fetch_blocked(const u32x4 *region, RawItems<ROWS> &blocked) {
+    const int lane = threadIdx.x & (kWave - 1);
+    __builtin_amdgcn_s_waitcnt(kWaitLds);
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) blocked.v[i] = region[lane * Stage<ROWS>::STRIDE + i];
+}
+
 // Registers hold the striped view on entry and the blocked view on return.
 template <int ROWS>
 __device__ __forceinline__ void striped_to_blocked(u32x4 *region, RawItems<ROWS> &r) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int j = 0; j < ROWS; ++j) region[stage_slot_of_striped<ROWS>(j, lane)] = r.v[j];
-    __builtin_amdgcn_s_waitcnt(kWaitLds);
-#pragma unroll
-    for (int i = 0; i < ROWS; ++i) r.v[i] = region[lane * Stage<ROWS>::STRIDE + i];
+    stage_striped<ROWS>(region, r);
+    fetch_blocked<ROWS>(region, r);
 }
 
 template <int ROWS>

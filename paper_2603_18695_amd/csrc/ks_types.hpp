@@ -1,6 +1,7 @@
 // Element types and operators of the scan library (device side).
 //
 // An operator is a stateless functor with
+//     static constexpr bool commutative;  // may totals be formed in any order? (never assumed otherwise)
 //     using acc = ...;                    // type the scan is carried out in
 //     static acc identity();              // op(identity, x) == x bit for bit
 //     acc operator()(acc l, acc r) const; // l = accumulated (earlier), r = later
@@ -71,6 +72,7 @@ template <> struct Limits<double>   { __device__ static double   lo() { return -
 
 template <class T>
 struct SumOp {
+    static constexpr bool commutative = true;
     using acc = T;
     __device__ static T identity() { return T(0); }
     __device__ __forceinline__ T operator()(T l, T r) const { return l + r; }
@@ -78,12 +80,14 @@ struct SumOp {
 // signed integer sums wrap: add in the unsigned type
 template <>
 struct SumOp<int32_t> {
+    static constexpr bool commutative = true;
     using acc = int32_t;
     __device__ static int32_t identity() { return 0; }
     __device__ __forceinline__ int32_t operator()(int32_t l, int32_t r) const { return (int32_t)((uint32_t)l + (uint32_t)r); }
 };
 template <>
 struct SumOp<int64_t> {
+    static constexpr bool commutative = true;
     using acc = int64_t;
     __device__ static int64_t identity() { return 0; }
     __device__ __forceinline__ int64_t operator()(int64_t l, int64_t r) const { return (int64_t)((uint64_t)l + (uint64_t)r); }
@@ -91,12 +95,14 @@ struct SumOp<int64_t> {
 
 template <class T>
 struct MinOp {
+    static constexpr bool commutative = true;
     using acc = T;
     __device__ static T identity() { return Limits<T>::hi(); }
     __device__ __forceinline__ T operator()(T l, T r) const { return r < l ? r : l; }
 };
 template <class T>
 struct MaxOp {
+    static constexpr bool commutative = true;
     using acc = T;
     __device__ static T identity() { return Limits<T>::lo(); }
     __device__ __forceinline__ T operator()(T l, T r) const { return r > l ? r : l; }
@@ -109,6 +115,7 @@ struct MaxOp {
 // not even inside one wave's run (tried: worst error 1.2e-3 at n = 5e5).  The
 // float32 inputs and outputs are converted at the memory boundary.
 struct AffineComposeOp {
+    static constexpr bool commutative = false;
     using acc = AffineF64;
     __device__ static AffineF64 identity() { return AffineF64{1.0, 0.0}; }
     __device__ __forceinline__ AffineF64 operator()(AffineF64 l, AffineF64 r) const {
@@ -117,6 +124,7 @@ struct AffineComposeOp {
 };
 
 struct ArgmaxCountOp {
+    static constexpr bool commutative = true;   // the better (v, idx) wins whichever side it is on; counts add
     using acc = ArgmaxI32Cnt64;
     __device__ static ArgmaxI32Cnt64 identity() { return ArgmaxI32Cnt64{INT32_MIN, INT32_MAX, 0}; }
     __device__ __forceinline__ ArgmaxI32Cnt64 operator()(ArgmaxI32Cnt64 l, ArgmaxI32Cnt64 r) const {
@@ -130,6 +138,7 @@ struct ArgmaxCountOp {
 };
 
 struct Mat2MulOp {
+    static constexpr bool commutative = false;
     using acc = Mat2U32;
     __device__ static Mat2U32 identity() { return Mat2U32{1u, 0u, 0u, 1u}; }
     __device__ __forceinline__ Mat2U32 operator()(Mat2U32 l, Mat2U32 r) const {
@@ -139,6 +148,7 @@ struct Mat2MulOp {
 };
 
 struct QuatMulOp {   // Hamilton product l * r
+    static constexpr bool commutative = false;
     using acc = QuatF32;
     __device__ static QuatF32 identity() { return QuatF32{1.0f, 0.0f, 0.0f, 0.0f}; }
     __device__ __forceinline__ QuatF32 operator()(QuatF32 l, QuatF32 r) const {
