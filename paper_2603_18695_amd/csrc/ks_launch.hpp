@@ -47,7 +47,7 @@ constexpr bool variant_fits() {
 // Default shape per element class: the best measured on MI355X, always 15 data
 // waves + 1 look-back wave, 9 rows, next tile prefetched.
 //   4-byte elements   common loop                            float32 sum 2^28: 6.25 TB/s
-//   everything wider  separate loops, blocked arrangement    uint64 sum 2^27: 5.7 TB/s,
+//   everything wider  separate loops, blocked arrangement    uint64 sum 2^27: 5.8 TB/s,
 //                     affine 2^26: 5.1, arg-max struct 2^26: 5.5
 // The 4-byte kernels keep the common loop: with their small register footprint
 // nothing is gained from separating the loops, and the compiler's schedule of
