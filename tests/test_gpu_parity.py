@@ -322,6 +322,37 @@ def test_strided_views(ks, dtype, op):
                 assert bool((d_in[:, 1:, :] == 0x5A5A5A5A).all())
 
 
+def test_two_streams_at_once(ks):
+    # calls on different streams use different workspaces and may overlap on the device; each stream's
+    # results must be those of its own inputs
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    tile = tile_elems(ks, "i32", *default_shape(ks, "i32"))
+    n1, n2 = 900 * tile + 17, 700 * tile_elems(ks, "u64", *default_shape(ks, "u64")) + 5
+    x1 = ks_inputs.whole("int32_sum", n1)
+    x2 = random_input("u64", "sum", n2, seed=21)
+    r1, r2 = reference("i32", "sum", x1, True), reference("u64", "sum", x2, False)
+    d1, d2 = to_device(x1), to_device(x2)
+    o1, o2 = torch.empty_like(d1), torch.empty_like(d2)
+    want1, want2 = to_device(r1), to_device(r2)
+    torch.cuda.synchronize()
+    for it in range(20):
+        if it % 5 == 0:
+            say(f"[case] two streams, iteration {it}")
+        o1.zero_()
+        o2.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            ks.ks_scan(d1, o1, dtype="i32", op="sum", inclusive=True)
+        with torch.cuda.stream(s2):
+            ks.ks_scan(d2, o2, dtype="u64", op="sum", inclusive=False)
+        with torch.cuda.stream(s1):
+            ks.ks_scan(d1, o1, dtype="i32", op="sum", inclusive=True)
+        ks.ks_scan_check(s1)
+        ks.ks_scan_check(s2)
+        assert torch.equal(o1, want1), it
+        assert torch.equal(o2, want2), it
+
+
 def test_more_than_2_pow_32_elements(ks):
     # 64-bit index arithmetic end to end: all-ones int32, closed form out[i] = i + 1 (mod 2^32), checked
     # on the device chunk by chunk (16 GiB in, 16 GiB out; the sums wrap exactly once, at element 2^32 - 1)
