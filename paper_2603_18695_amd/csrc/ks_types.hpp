@@ -108,12 +108,13 @@ struct MaxOp {
     __device__ __forceinline__ T operator()(T l, T r) const { return r > l ? r : l; }
 };
 
-// Apply l first, then r.  Carried in double: the offset b of a composition is a
-// sum with heavy cancellation (it crosses zero while partial sums over a few
-// hundred elements already reach several thousand, where float32 resolves no
-// better than 5e-4), so float32 intermediates cannot hold 1e-3 absolute accuracy,
-// not even inside one wave's run (tried: worst error 1.2e-3 at n = 5e5).  The
-// float32 inputs and outputs are converted at the memory boundary.
+// Apply l first, then r.  Carried in double: the offset b of a long composition
+// is a cancelling sum that reaches 1e2..1e3 in magnitude and crosses zero, and
+// every later composition multiplies it by a: an a carried in float32 (relative
+// error 1e-6 after a thousand factors) then costs 1e-3 absolute, the whole error
+// bar.  Tried with float32 inside one wave's run and double only above it: worst
+// error 1.2e-3 at n = 5e5, outside the bar.  The float32 inputs and outputs are
+// converted at the memory boundary.
 struct AffineComposeOp {
     static constexpr bool commutative = false;
     using acc = AffineF64;
