@@ -345,7 +345,7 @@ __device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileEx
 // coexist with the look-back's temporaries (one register allocation serves the
 // whole kernel; in one common loop the two add up and wide element types spill).
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__restrict__ out, const LookbackArgs &a,
+__device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const LookbackArgs &a,
                                                TileExchange<typename Op::acc, WAVES> &x) {
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;
@@ -404,7 +404,7 @@ __device__ __forceinline__ void data_wave_loop(const IO *__restrict__ in, IO *__
 // granules through its LDS region `stage + (wave - 1) * Stage<ROWS>::SLOTS` on
 // the way in and on the way out, and scans ROWS consecutive granules per lane.
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in, IO *__restrict__ out,
+__device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
                                                        const LookbackArgs &a, TileExchange<typename Op::acc, WAVES> &x,
                                                        u32x4 *stage) {
     using A = typename Op::acc;
@@ -498,7 +498,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *__restrict__ in
 // One loop for all waves: wave 0 looks back, and holds data as well unless the
 // shape has a dedicated look-back wave.
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__device__ __forceinline__ void common_wave_loop(const IO *__restrict__ in, IO *__restrict__ out, size_t n,
+__device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n,
                                                  uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
                                                  uint32_t spin_limit, uint32_t *abort_flag) {
     using A = typename Op::acc;
@@ -585,7 +585,7 @@ constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in
 constexpr int kFormBlocked = 2;    // the same with the blocked arrangement (LDS exchange)
 
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
-__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *__restrict__ in, IO *__restrict__ out,
+__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out,
                                                                      size_t n, uint64_t *desc, uint64_t *xdesc,
                                                                      uint32_t epoch, uint32_t ntiles,
                                                                      uint32_t spin_limit, uint32_t *abort_flag,
@@ -642,7 +642,7 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
 // seeds == nullptr: every tile starts from the identity (used when one tile
 // covers the whole input).  Otherwise seeds[tile] = combination of all earlier tiles.
 template <class IO, class Op, int ROWS, bool INCLUSIVE>
-__global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *__restrict__ in, IO *__restrict__ out, size_t n,
+__global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out, size_t n,
                                                            const typename Op::acc *__restrict__ seeds) {
     using A = typename Op::acc;
     using S = TileShape<IO, ROWS>;

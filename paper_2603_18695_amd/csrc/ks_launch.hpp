@@ -3,6 +3,8 @@
 // the reduce-then-scan recursion.  Instantiated once per pair in ks_pairs_*.hip.
 #pragma once
 
+#include <map>
+
 #include "ks_host.hpp"
 #include "ks_kernels.hpp"
 
@@ -121,7 +123,9 @@ struct Pair {
             const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
             if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
-            static int per_cu = 0;   // resident workgroups per compute unit for this variant, as verified below
+            // resident workgroups per compute unit of this variant, per device, as verified below
+            static std::map<int, int> verified_per_cu;
+            int &per_cu = verified_per_cu[c.dev->device];
             if (per_cu == 0) {
                 int nb = 0;
                 hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kThreads, 0);
