@@ -422,6 +422,10 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     // requested early, float32, uint64 and the affine type measured 1-10 % slower).
     constexpr bool EARLY = PREFETCH && sizeof(IO) == 16;
     constexpr bool TOTAL_FIRST = Op::commutative && !EARLY;   // uint64 sum: 5.73 -> 5.94 TB/s
+    // 16-byte elements with an accumulator of the same size (arg-max +1.5 %, quaternions +3.5 %,
+    // 2x2 matrices +5 %); 8-byte ones lose (float64 sum -8 %: the second pass of additions costs
+    // more than the LDS trip it takes off the path after the barrier).
+    constexpr bool BACK_EARLY = sizeof(IO) == 16 && sizeof(A) == sizeof(IO);
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
@@ -477,13 +481,30 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
             }
         }
         const uint32_t next = tile + gridDim.x;
-        __syncthreads();
-        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-        const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
-        RawItems<ROWS> result;
-        apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
-        blocked_to_striped<ROWS>(region, result);
-        store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
+        if constexpr (BACK_EARLY) {
+            // Where the accumulator has the element's size, the way back through LDS is taken while the
+            // look-back wave is busy: the wave-local results (lane_before in front of every item) go
+            // back to the striped arrangement now, and after the barrier only the tile's prefix is
+            // put in front of them, as in the striped loop.
+            RawItems<ROWS> local;
+            apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, lane_before, op, local);
+            blocked_to_striped<ROWS>(region, local);
+            ThreadItems<A, ROWS, S::G> striped;
+            unpack_items<IO, ROWS, typename MapOf<Op>::unmapped, true>(local, lane_bytes, 0u, false, striped);
+            __syncthreads();
+            if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+            const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
+            apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE),
+                                                          lane_bytes, striped, prefix, op);
+        } else {
+            __syncthreads();
+            if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+            const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
+            RawItems<ROWS> result;
+            apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
+            blocked_to_striped<ROWS>(region, result);
+            store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
+        }
         if (next >= a.ntiles) return;
         loop_tile = next;
         if (EARLY) settle<ROWS>(raw);   // the wait for the early request belongs here, after the stores
