@@ -106,6 +106,9 @@ class _OnDeviceOf:
             self._guard.__exit__(*exc)
 
 
+_ELEM_BYTES: dict = {}
+
+
 def _nbytes(t: torch.Tensor) -> int:
     return t.numel() * t.element_size()
 
@@ -115,7 +118,9 @@ def _elements(t: torch.Tensor, dtype: str) -> int:
         raise ValueError("ks_scan works on device tensors only")
     if not t.is_contiguous():
         raise ValueError("tensor must be contiguous")
-    eb = _lib.ks_elem_bytes(DTYPES[dtype])
+    eb = _ELEM_BYTES.get(dtype)
+    if eb is None:   # asked of the library once per dtype: this runs on every call
+        eb = _ELEM_BYTES[dtype] = int(_lib.ks_elem_bytes(DTYPES[dtype]))
     if _nbytes(t) % eb:
         raise ValueError(f"tensor of {_nbytes(t)} bytes is not a whole number of {dtype} elements")
     return _nbytes(t) // eb

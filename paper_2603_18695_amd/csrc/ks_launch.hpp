@@ -54,11 +54,26 @@ constexpr bool variant_fits() {
 // The 4-byte kernels keep the common loop: with their small register footprint
 // nothing is gained from separating the loops, and the compiler's schedule of
 // the common loop measured 4-5 % faster (6.25 against 6.0 TB/s; blocked 5.8).
+//
+// Small inputs (up to kSmallInputBytes) of 4- and 8-byte elements take 4 waves x 8
+// rows instead: 32 KiB tiles spread the input over more compute units, and the run
+// time of a small scan is one workgroup's load -> store latency plus the look-back
+// chain.  Kernel time under rocprofv3, small against large shape: int32 sum 64 KiB
+// 3.3 / 4.9 us, 256 KiB 4.2 / 5.7, 1 MiB 5.0 / 6.5, 4 MiB 6.6 / 6.8, 8 MiB 7.2 / 7.2;
+// uint64 sum 64 KiB 3.9 / 4.8, 1 MiB 5.5 / 6.2, 8 MiB 7.6 / 8.3; affine 1 MiB 6.1 / 7.0.
+// 16-byte elements keep the large blocked shape at every size (arg-max 64 KiB
+// 6.3 / 5.9 us, 4 MiB 10.1 / 7.8: the striped scan of the small shape costs more
+// than the spreading gains).
 template <class T, class A>
 struct PairDefaults {
     static constexpr Shape shape() {
         if (sizeof(A) == 4) return Shape{16, 9, true, kFormCommon};
         return Shape{16, 9, true, kFormBlocked};
+    }
+    static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
+    static constexpr size_t kSmallInputBytes = (size_t)8 << 20;
+    static constexpr Shape shape_for(size_t n) {
+        return sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes ? small_shape() : shape();
     }
 };
 
@@ -75,8 +90,8 @@ struct Pair {
 
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
-    static Shape lookback_shape() {
-        Shape s = PairDefaults<T, A>::shape();
+    static Shape lookback_shape(size_t n) {
+        Shape s = PairDefaults<T, A>::shape_for(n);
         if (MapOf<Op>::mapped) return s;
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
@@ -206,11 +221,16 @@ struct Pair {
 
     static int run_lookback(const ScanCall &c) {
         if constexpr (MapOf<Op>::mapped) {
-            // mapped pairs are compiled in their element class's default shape only
+            // mapped pairs are compiled in their element class's two default shapes only
             constexpr Shape d = PairDefaults<T, A>::shape();
+            constexpr Shape sm = PairDefaults<T, A>::small_shape();
+            if constexpr (sizeof(T) < 16) {
+                if (c.n * sizeof(T) <= PairDefaults<T, A>::kSmallInputBytes)
+                    return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
+            }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
         }
-        const Shape s = lookback_shape();
+        const Shape s = lookback_shape(c.n);
         switch (s.waves) {
             case 4: return lookback_rows_dispatch<4>(c, s);
             case 8: return lookback_rows_dispatch<8>(c, s);

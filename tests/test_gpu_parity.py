@@ -35,8 +35,14 @@ def tile_elems(ks, dtype, waves, rows, lookback=True):
     return data_waves * 64 * rows * (16 // ks.ks_elem_bytes(dtype))
 
 
-def default_shape(ks, dtype):
-    """(waves, rows) the library picks for the look-back kernel of this element type."""
+SMALL_INPUT_BYTES = 8 << 20   # up to here the default look-back shape of 4- and 8-byte elements is SMALL_SHAPE
+SMALL_SHAPE = (4, 8)
+
+
+def default_shape(ks, dtype, n=None):
+    """(waves, rows) the library picks for the look-back kernel of this element type and size."""
+    if n is not None and ks.ks_elem_bytes(dtype) < 16 and n * ks.ks_elem_bytes(dtype) <= SMALL_INPUT_BYTES:
+        return SMALL_SHAPE
     return 16, 9
 
 
@@ -71,7 +77,8 @@ ALL_PAIRS = sorted(KINDS)
 
 @pytest.mark.parametrize("dtype,op", ALL_PAIRS)
 def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
-    for n in edge_sizes(tile_elems(ks, dtype, *default_shape(ks, dtype)), tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)):
+    for n in edge_sizes(tile_elems(ks, dtype, *default_shape(ks, dtype)), tile_elems(ks, dtype, *SMALL_SHAPE),
+                        tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)):
         x = random_input(dtype, op, n, seed=1000 + n % 97)
         for inclusive in (True, False):
             ref = reference(dtype, op, x, inclusive)
@@ -93,6 +100,21 @@ def test_library_owned_workspace_back_to_back(ks, dtype, op):
             say(f"[case] pair=({dtype},{op}) n={n} inclusive={inclusive} api=plain")
             got = run(ks, dtype, op, x, inclusive, api="plain")
             assert_matches(dtype, op, got, reference(dtype, op, x, inclusive), f"plain ({dtype},{op}) n={n}")
+
+
+@pytest.mark.parametrize("dtype,op", [("i32", "sum"), ("f64", "sum"), ("argmax_i32_cnt64", "argmax_count")])
+def test_default_shape_switches_with_the_input_size(ks, dtype, op):
+    # at and just above the size where the default look-back shape changes from small to large tiles
+    at = SMALL_INPUT_BYTES // ks.ks_elem_bytes(dtype)
+    for n in (at - 1, at, at + 1):
+        x = random_input(dtype, op, n, seed=77)
+        ref = reference(dtype, op, x, True)
+        say(f"[case] pair=({dtype},{op}) n={n} default shape at the small-input limit")
+        got = run(ks, dtype, op, x, algo="lookback")
+        # both tile counts are below the number of resident workgroups, so the grid tells the tile size
+        tile = tile_elems(ks, dtype, *default_shape(ks, dtype, n))
+        assert ks.ks_get_option("last_grid") == -(-n // tile), (n, tile)
+        assert_matches(dtype, op, got, ref, f"({dtype},{op}) n={n}")
 
 
 def test_closed_forms_on_the_gpu(ks):
