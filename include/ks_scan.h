@@ -146,6 +146,11 @@ size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n);
  * 256-byte aligned, of at least ks_scan_temp_bytes(...) bytes, whose previous
  * contents do not matter.  Allocates nothing.  The scratch may be reused by a
  * later call on the same stream; two calls in flight at once need two buffers.
+ * The call only launches kernels (the descriptors are cleared by one, not by a
+ * memset), so it may be recorded into a HIP graph and replayed; make one
+ * ordinary call with the same dtype, op and shape options first: the first use
+ * of a kernel variant on a device runs a one-off check that synchronises the
+ * stream and cannot be captured.
  */
 int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, const void *in,
                       void *out, size_t n, void *temp, size_t temp_bytes, void *stream);

@@ -148,7 +148,12 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
         fresh = true;
     }
     if (fresh || ws.epoch >= kMaxEpoch) {
-        hipError_t he = hipMemsetAsync(ws.ptr, 0, ws.bytes, (hipStream_t)stream);
+        // a fill kernel, not hipMemsetAsync: the call may be recorded into a HIP graph by the caller
+        const size_t words = ws.bytes / sizeof(uint64_t);
+        const size_t blocks = (words + 255) / 256;
+        hipLaunchKernelGGL((fill_zero_kernel<0>), dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0,
+                           (hipStream_t)stream, static_cast<uint64_t *>(ws.ptr), words);
+        hipError_t he = hipGetLastError();
         if (he != hipSuccess) return set_hip_error(he);
         ws.epoch = 0;
     }

@@ -375,6 +375,38 @@ def test_two_streams_at_once(ks):
         assert torch.equal(o2, want2), it
 
 
+def test_hip_graph_replays_match_eager_results(ks):
+    # ks_scan_with_temp allocates nothing and clears its descriptors with a kernel, so a caller may
+    # record it into a HIP graph (after one eager call, which runs the one-off residency check of
+    # the kernel variant).  Every replay, with fresh input contents and eager work in between, must
+    # give what the eager call gives for the same input.
+    for dtype, op, n in (("f32", "sum", 3_000_017), ("u64", "sum", 1_500_003), ("i32", "max", 70_001)):
+        xs = [random_input(dtype, op, n, seed=40 + r) for r in range(4)]
+        refs = [reference(dtype, op, x, True) for x in xs]
+        d_in = to_device(xs[0])
+        d_out = torch.empty_like(d_in)
+        temp = torch.empty(ks.ks_scan_temp_bytes(dtype=dtype, op=op, n=n, algo="lookback"), dtype=torch.uint8,
+                           device="cuda")
+        say(f"[case] hip graph ({dtype},{op}) n={n}: eager warm-up")
+        ks.ks_scan_with_temp(d_in, d_out, temp, dtype=dtype, op=op, inclusive=True, algo="lookback")
+        ks.ks_scan_check()
+        assert_matches(dtype, op, to_host(d_out, xs[0].dtype), refs[0], "eager")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ks.ks_scan_with_temp(d_in, d_out, temp, dtype=dtype, op=op, inclusive=True, algo="lookback")
+        for r in range(4):
+            say(f"[case] hip graph ({dtype},{op}) n={n}: replay {r}")
+            d_in.copy_(to_device(xs[r]))
+            d_out.zero_()
+            temp.fill_(0x5A + r)          # eager work on the buffers between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ks.ks_scan_check()
+            assert_matches(dtype, op, to_host(d_out, xs[r].dtype), refs[r], f"replay {r}")
+        del graph
+
+
 def test_more_than_2_pow_32_elements(ks):
     # 64-bit index arithmetic end to end: all-ones int32, closed form out[i] = i + 1 (mod 2^32), checked
     # on the device chunk by chunk (16 GiB in, 16 GiB out; the sums wrap exactly once, at element 2^32 - 1)
