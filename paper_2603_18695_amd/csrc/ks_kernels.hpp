@@ -271,6 +271,18 @@ struct TileExchange {
     uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
 };
 
+// How long the data waves of the separate loops hold the request for the next tile back after the
+// barrier that hands the wave totals over, in units of 64 cycles (s_sleep).  The compute unit's L1
+// returns loads in order, so once the 135 KiB of the next tile are requested every poll of the
+// look-back wave comes back behind them, 6-7 us later; the pause lets the aggregate go out and the
+// first polls return before that.  Measured on MI355X (TB/s, pause 0 / 12 / 24 / 32 / 48 / 96):
+// uint64 sum 5.99 / 6.12 / 6.15 / 6.14 / 6.11 / 5.75, affine 5.14 / 5.82 / 5.84 / 5.82 / 5.81 / 5.53,
+// arg-max struct 5.5 / 5.66 / 5.86 / 6.05 / 6.05 / 5.69, quaternions 5.3 / 5.60 / 5.90 / 5.91 / 5.89 / 5.70.
+// Releasing the request by a flag in LDS as soon as the aggregate is out, or when the look-back is
+// done (bounded), measured 1-5 % below the fixed pause.  The common loop does not need it: its
+// look-back wave publishes while the other waves still fold the totals.
+constexpr int kPrefetchHold = 32;
+
 // Arguments of the look-back kernel that its loops pass around.
 struct LookbackArgs {
     size_t n;
@@ -379,6 +391,7 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
         RawItems<ROWS> nxt;
         TileWindow wnext;
         if (PREFETCH && next < a.ntiles) {
+            __builtin_amdgcn_s_sleep(kPrefetchHold);
             wnext = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, true>(wnext, lane_bytes, nxt);
         }
@@ -416,22 +429,16 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);   // striped view: global loads and stores
     const int run_bytes = (wave - 1) * (kWave * ROWS * 16);   // start of the wave's run inside the tile
     u32x4 *region = stage + (wave - 1) * Stage<ROWS>::SLOTS;
-    // When to request the next tile: for 16-byte elements before the scan (the registers are free
-    // once the tile is unpacked, and their scan is long enough for the read stream to run dry:
-    // arg-max struct 5.25 -> 5.5 TB/s), otherwise after the totals are out (see data_wave_loop;
-    // requested early, float32, uint64 and the affine type measured 1-10 % slower).
-    constexpr bool EARLY = PREFETCH && sizeof(IO) == 16;
-    constexpr bool TOTAL_FIRST = Op::commutative && !EARLY;   // uint64 sum: 5.73 -> 5.94 TB/s
-    // 16-byte elements with an accumulator of the same size (arg-max +1.5 %, quaternions +3.5 %,
-    // 2x2 matrices +5 %); 8-byte ones lose (float64 sum -8 %: the second pass of additions costs
-    // more than the LDS trip it takes off the path after the barrier).
-    constexpr bool BACK_EARLY = sizeof(IO) == 16 && sizeof(A) == sizeof(IO);
+    // The next tile is requested after the totals are out and the pause of kPrefetchHold, as in
+    // data_wave_loop.  (Requested before the scan, which looked best for 16-byte elements while
+    // nothing kept the request from overtaking the look-back's polls, it measures 8-11 % below
+    // the held request: arg-max struct 5.59 against 6.05 TB/s.)
+    constexpr bool TOTAL_FIRST = Op::commutative;   // uint64 sum: 5.73 -> 5.94 TB/s
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
         const TileWindow w = tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE);
         load_raw<ROWS, true>(w, lane_bytes, raw);
-        if (EARLY) settle<ROWS>(raw);
         valid_bytes = w.valid_bytes;
     }
     for (uint32_t loop_tile = blockIdx.x;;) {
@@ -455,6 +462,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
             RawItems<ROWS> blocked;
             fetch_blocked<ROWS>(region, blocked);
             if (PREFETCH && tile + gridDim.x < a.ntiles) {
+                __builtin_amdgcn_s_sleep(kPrefetchHold);
                 const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
                 load_raw<ROWS, true>(w, lane_bytes, raw);
                 valid_bytes = w.valid_bytes;
@@ -464,50 +472,26 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         } else {
             striped_to_blocked<ROWS>(region, raw);
             unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
-            if constexpr (EARLY) {
-                if (tile + gridDim.x < a.ntiles) {
-                    const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
-                    load_raw<ROWS, true>(w, lane_bytes, raw);
-                    valid_bytes = w.valid_bytes;
-                }
-            }
             const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
             if (lane == 0) x.tot[wave] = to_words(wave_total);
             __syncthreads();
-            if (PREFETCH && !EARLY && tile + gridDim.x < a.ntiles) {
+            if (PREFETCH && tile + gridDim.x < a.ntiles) {
+                __builtin_amdgcn_s_sleep(kPrefetchHold);
                 const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
                 load_raw<ROWS, true>(w, lane_bytes, raw);
                 valid_bytes = w.valid_bytes;
             }
         }
         const uint32_t next = tile + gridDim.x;
-        if constexpr (BACK_EARLY) {
-            // Where the accumulator has the element's size, the way back through LDS is taken while the
-            // look-back wave is busy: the wave-local results (lane_before in front of every item) go
-            // back to the striped arrangement now, and after the barrier only the tile's prefix is
-            // put in front of them, as in the striped loop.
-            RawItems<ROWS> local;
-            apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, lane_before, op, local);
-            blocked_to_striped<ROWS>(region, local);
-            ThreadItems<A, ROWS, S::G> striped;
-            unpack_items<IO, ROWS, typename MapOf<Op>::unmapped, true>(local, lane_bytes, 0u, false, striped);
-            __syncthreads();
-            if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-            const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
-            apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE),
-                                                          lane_bytes, striped, prefix, op);
-        } else {
-            __syncthreads();
-            if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-            const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
-            RawItems<ROWS> result;
-            apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
-            blocked_to_striped<ROWS>(region, result);
-            store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
-        }
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
+        RawItems<ROWS> result;
+        apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
+        blocked_to_striped<ROWS>(region, result);
+        store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
         if (next >= a.ntiles) return;
         loop_tile = next;
-        if (EARLY) settle<ROWS>(raw);   // the wait for the early request belongs here, after the stores
         if (!PREFETCH) {
             const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);

@@ -4,6 +4,7 @@
 #pragma once
 
 #include <map>
+#include <type_traits>
 
 #include "ks_host.hpp"
 #include "ks_kernels.hpp"
@@ -46,14 +47,15 @@ constexpr bool variant_fits() {
     return data + parked + other <= budget;
 }
 
-// Default shape per element class: the best measured on MI355X, always 15 data
-// waves + 1 look-back wave, 9 rows, next tile prefetched.
-//   4-byte elements   common loop                            float32 sum 2^28: 6.25 TB/s
-//   everything wider  separate loops, blocked arrangement    uint64 sum 2^27: 5.8 TB/s,
-//                     affine 2^26: 5.1, arg-max struct 2^26: 5.5
-// The 4-byte kernels keep the common loop: with their small register footprint
-// nothing is gained from separating the loops, and the compiler's schedule of
-// the common loop measured 4-5 % faster (6.25 against 6.0 TB/s; blocked 5.8).
+// Default shape per pair: the best measured on MI355X, always 15 data waves + 1
+// look-back wave, 9 rows, next tile prefetched (TB/s at 2 GiB of traffic):
+//   float32 sum        common loop                                     6.25  (separate loops 6.08)
+//   other 4-byte pairs separate loops   int32 sum 6.08 (common 5.94), int32 min 6.09 (5.80),
+//                                       float32 max 6.13 (6.00), uint32 sum 6.05 (5.93)
+//   everything wider   separate loops, blocked arrangement   uint64 / float64 sum 6.15,
+//                      affine 5.8, arg-max struct 6.05, 2x2 matrices 6.0, quaternions 5.9
+// The float32 sum is the one kernel whose common loop the compiler schedules better
+// than its separate loops; why exactly is not known (same algorithm, same bytes).
 //
 // Small inputs (up to kSmallInputBytes) of 4- and 8-byte elements take 4 waves x 8
 // rows instead: 32 KiB tiles spread the input over more compute units, and the run
@@ -64,10 +66,12 @@ constexpr bool variant_fits() {
 // 16-byte elements keep the large blocked shape at every size (arg-max 64 KiB
 // 6.3 / 5.9 us, 4 MiB 10.1 / 7.8: the striped scan of the small shape costs more
 // than the spreading gains).
-template <class T, class A>
+template <class T, class Op>
 struct PairDefaults {
+    using A = typename Op::acc;
+    static constexpr bool kFloat32Sum = std::is_same<typename MapOf<Op>::unmapped, SumOp<float>>::value;
     static constexpr Shape shape() {
-        if (sizeof(A) == 4) return Shape{16, 9, true, kFormCommon};
+        if (sizeof(A) == 4) return Shape{16, 9, true, kFloat32Sum ? kFormCommon : kFormSeparate};
         return Shape{16, 9, true, kFormBlocked};
     }
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
@@ -91,7 +95,7 @@ struct Pair {
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
     static Shape lookback_shape(size_t n) {
-        Shape s = PairDefaults<T, A>::shape_for(n);
+        Shape s = PairDefaults<T, Op>::shape_for(n);
         if (MapOf<Op>::mapped) return s;
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
@@ -222,10 +226,10 @@ struct Pair {
     static int run_lookback(const ScanCall &c) {
         if constexpr (MapOf<Op>::mapped) {
             // mapped pairs are compiled in their element class's two default shapes only
-            constexpr Shape d = PairDefaults<T, A>::shape();
-            constexpr Shape sm = PairDefaults<T, A>::small_shape();
+            constexpr Shape d = PairDefaults<T, Op>::shape();
+            constexpr Shape sm = PairDefaults<T, Op>::small_shape();
             if constexpr (sizeof(T) < 16) {
-                if (c.n * sizeof(T) <= PairDefaults<T, A>::kSmallInputBytes)
+                if (c.n * sizeof(T) <= PairDefaults<T, Op>::kSmallInputBytes)
                     return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
             }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);

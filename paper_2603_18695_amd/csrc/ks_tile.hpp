@@ -100,18 +100,6 @@ __device__ __forceinline__ void load_raw(const TileWindow &w, int lane_bytes, Ra
         raw.v[j] = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, at + j * (kWave * 16), 0, kNonTemporal);
 }
 
-// Wait for a prefetched tile HERE.  The compiler places the wait for a load at the first use of its
-// result; for a tile requested in one loop iteration and first used in the next, that use lies
-// behind the loop's back edge, where the compiler's count of outstanding operations is no longer
-// exact and it falls back to waiting for everything, including requests issued since.  Passing the
-// registers through an empty asm statement is a use at this point (the wait lands here, counted
-// exactly) and a new definition (later uses need no wait).
-template <int ROWS>
-__device__ __forceinline__ void settle(RawItems<ROWS> &raw) {
-#pragma unroll
-    for (int j = 0; j < ROWS; ++j) asm volatile("" : "+v"(raw.v[j]));
-}
-
 // Raw granules -> accumulation type, through the operator's map if it has one
 // (scan(f, op, src), paper Sec. IV-A).  In a partial tile the elements past the
 // end (read as zero by the hardware) become the operator's identity.

@@ -79,7 +79,13 @@ def random_input(dtype: str, op: str, n: int, seed: int) -> np.ndarray:
         info = np.iinfo(npdt)
         return rng.integers(info.min, info.max, size=n, dtype=npdt, endpoint=True)
     if op == "sum":
-        return rng.uniform(-1.0, 1.0, size=n).astype(npdt)
+        # Mixed signs, so that running sums cancel and cross zero.  The amplitude shrinks with n so that
+        # the random walk of the running sum (standard deviation amp * sqrt(n / 3)) stays within a few
+        # hundred: the bar's absolute part (1e-3) is then worth some sixteen float32 roundings at that
+        # magnitude (spacing 6e-5 below 1024).  With amplitude 1 at n = 2.4e7 the walk reaches 4096,
+        # where a handful of roundings already add up to 1e-3 and the bar cannot hold for any scan.
+        amp = min(1.0, float(np.sqrt(2.0 ** 20 / max(n, 1))))
+        return (rng.uniform(-1.0, 1.0, size=n) * amp).astype(npdt)
     return rng.normal(size=n).astype(npdt)
 
 
