@@ -433,7 +433,6 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     // data_wave_loop.  (Requested before the scan, which looked best for 16-byte elements while
     // nothing kept the request from overtaking the look-back's polls, it measures 8-11 % below
     // the held request: arg-max struct 5.59 against 6.05 TB/s.)
-    constexpr bool TOTAL_FIRST = Op::commutative;   // uint64 sum: 5.73 -> 5.94 TB/s
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
@@ -445,42 +444,16 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);   // see data_wave_loop
         ThreadItems<A, ROWS, S::G> cur;
         A lane_before;
-        if constexpr (TOTAL_FIRST) {
-            // Commutative operators: the run's total straight from the striped registers while the
-            // LDS takes the granules, so that the totals are out (and the next tile requested) before
-            // the exchange and the scan (see reduce_wave_run_any_order).
-            const bool partial = tile + 1 == a.ntiles;
-            const uint32_t tile_valid_bytes = valid_bytes;
-            stage_striped<ROWS>(region, raw);
-            {
-                ThreadItems<A, ROWS, S::G> striped;
-                unpack_items<IO, ROWS, Op, true>(raw, lane_bytes, tile_valid_bytes, partial, striped);
-                const A wave_total = reduce_wave_run_any_order<A, ROWS, S::G, Op>(striped, op);
-                if (lane == 0) x.tot[wave] = to_words(wave_total);
-            }
-            __syncthreads();
-            RawItems<ROWS> blocked;
-            fetch_blocked<ROWS>(region, blocked);
-            if (PREFETCH && tile + gridDim.x < a.ntiles) {
-                __builtin_amdgcn_s_sleep(kPrefetchHold);
-                const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
-                load_raw<ROWS, true>(w, lane_bytes, raw);
-                valid_bytes = w.valid_bytes;
-            }
-            unpack_blocked<IO, ROWS, Op>(blocked, run_bytes, tile_valid_bytes, partial, cur);
-            (void)scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
-        } else {
-            striped_to_blocked<ROWS>(region, raw);
-            unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
-            const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
-            if (lane == 0) x.tot[wave] = to_words(wave_total);
-            __syncthreads();
-            if (PREFETCH && tile + gridDim.x < a.ntiles) {
-                __builtin_amdgcn_s_sleep(kPrefetchHold);
-                const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
-                load_raw<ROWS, true>(w, lane_bytes, raw);
-                valid_bytes = w.valid_bytes;
-            }
+        striped_to_blocked<ROWS>(region, raw);
+        unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
+        const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
+        if (lane == 0) x.tot[wave] = to_words(wave_total);
+        __syncthreads();
+        if (PREFETCH && tile + gridDim.x < a.ntiles) {
+            __builtin_amdgcn_s_sleep(kPrefetchHold);
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
+            load_raw<ROWS, true>(w, lane_bytes, raw);
+            valid_bytes = w.valid_bytes;
         }
         const uint32_t next = tile + gridDim.x;
         __syncthreads();
