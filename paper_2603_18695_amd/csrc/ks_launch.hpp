@@ -76,8 +76,14 @@ struct PairDefaults {
     }
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
     static constexpr size_t kSmallInputBytes = (size_t)8 << 20;
+    // 4-byte pairs below this size stay in the common loop: with only a few rounds per workgroup
+    // the separate loops and their pause do not pay yet (int32 sum, common / separate, TB/s:
+    // 32 MiB 5.24 / 5.21, 64 MiB 5.91 / 5.69, 128 MiB 5.57 / 5.53, 256 MiB 5.59 / 5.63, 1 GiB 5.87 / 6.04).
+    static constexpr size_t kSeparateFromBytes = (size_t)256 << 20;
     static constexpr Shape shape_for(size_t n) {
-        return sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes ? small_shape() : shape();
+        if (sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes) return small_shape();
+        if (sizeof(A) == 4 && n * sizeof(T) < kSeparateFromBytes) return Shape{16, 9, true, kFormCommon};
+        return shape();
     }
 };
 
@@ -231,6 +237,10 @@ struct Pair {
             if constexpr (sizeof(T) < 16) {
                 if (c.n * sizeof(T) <= PairDefaults<T, Op>::kSmallInputBytes)
                     return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
+            }
+            if constexpr (sizeof(A) == 4 && d.form != kFormCommon) {
+                if (c.n * sizeof(T) < PairDefaults<T, Op>::kSeparateFromBytes)
+                    return lookback_flags_dispatch<d.waves, d.rows, kFormCommon>(c, d.prefetch);
             }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
         }
