@@ -117,6 +117,17 @@ def test_default_shape_switches_with_the_input_size(ks, dtype, op):
         assert_matches(dtype, op, got, ref, f"({dtype},{op}) n={n}")
 
 
+def test_default_form_switches_with_the_input_size(ks):
+    # 4-byte pairs other than the float32 sum run the common loop below 256 MiB of input and the
+    # separate loops from there on; both sides of the limit, exact compare
+    at = (256 << 20) // 4
+    for n in (at - 1, at):
+        x = ks_inputs.whole("int32_sum", n)
+        say(f"[case] (i32,sum) n={n} at the size where the default form changes")
+        got = run(ks, "i32", "sum", x, api="plain")
+        assert np.array_equal(got, reference("i32", "sum", x, True)), n
+
+
 def test_closed_forms_on_the_gpu(ks):
     n = (1 << 22) + 12345
     say("[case] all-ones int32 / uint64 / f32, iota uint64")
