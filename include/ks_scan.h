@@ -175,8 +175,8 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *                  (0 = what the occupancy query allows; values above it are clamped)
  *   "waves"        wave64s per workgroup of the look-back kernel (one of them does the
  *                  look-back, the others hold the tile): 0 = the default for the type and
- *                  the input size (16 waves x 9 rows; 4 x 8 for up to 8 MiB of 4- or 8-byte
- *                  elements), else 4, 8 or 16
+ *                  the input size (16 waves x 9 rows; for 4- and 8-byte elements 4 x 8 up
+ *                  to 8 MiB and 8 x 8 up to 16 / 32 MiB of input), else 4, 8 or 16
  *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
  *                  default, else 4, 8, 9, 12 or 16.  A (waves, rows, prefetch) combination that
  *                  would not fit the register file for an element type makes the scan

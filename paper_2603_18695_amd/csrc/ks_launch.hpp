@@ -80,8 +80,15 @@ struct PairDefaults {
     // the separate loops and their pause do not pay yet (int32 sum, common / separate, TB/s:
     // 32 MiB 5.24 / 5.21, 64 MiB 5.91 / 5.69, 128 MiB 5.57 / 5.53, 256 MiB 5.59 / 5.63, 1 GiB 5.87 / 6.04).
     static constexpr size_t kSeparateFromBytes = (size_t)256 << 20;
+    // Between the two, 8 waves x 8 rows (64 KiB tiles, no next tile to prefetch): up to 34 MiB the
+    // large tile leaves compute units without work (16 MiB are 124 tiles of 135 KiB).  Against the
+    // large shape, TB/s: int32 sum 16 MiB 3.48 / 3.18, uint64 sum 16 MiB 3.35 / 3.07, 32 MiB 5.11 / 4.75;
+    // from 32 MiB (4-byte) and 64 MiB (8-byte elements) on the large shape is ahead.
+    static constexpr Shape mid_shape() { return Shape{8, 8, false, kFormCommon}; }
+    static constexpr size_t kMidInputBytes = sizeof(T) == 4 ? (size_t)16 << 20 : (size_t)32 << 20;
     static constexpr Shape shape_for(size_t n) {
         if (sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes) return small_shape();
+        if (sizeof(T) < 16 && n * sizeof(T) <= kMidInputBytes) return mid_shape();
         if (sizeof(A) == 4 && n * sizeof(T) < kSeparateFromBytes) return Shape{16, 9, true, kFormCommon};
         return shape();
     }

@@ -39,10 +39,17 @@ SMALL_INPUT_BYTES = 8 << 20   # up to here the default look-back shape of 4- and
 SMALL_SHAPE = (4, 8)
 
 
+MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (4-byte) / 32 MiB (8-byte elements)
+
+
 def default_shape(ks, dtype, n=None):
     """(waves, rows) the library picks for the look-back kernel of this element type and size."""
-    if n is not None and ks.ks_elem_bytes(dtype) < 16 and n * ks.ks_elem_bytes(dtype) <= SMALL_INPUT_BYTES:
-        return SMALL_SHAPE
+    eb = ks.ks_elem_bytes(dtype)
+    if n is not None and eb < 16:
+        if n * eb <= SMALL_INPUT_BYTES:
+            return SMALL_SHAPE
+        if n * eb <= ((16 << 20) if eb == 4 else (32 << 20)):
+            return MID_SHAPE
     return 16, 9
 
 
@@ -106,7 +113,8 @@ def test_library_owned_workspace_back_to_back(ks, dtype, op):
 def test_default_shape_switches_with_the_input_size(ks, dtype, op):
     # at and just above the size where the default look-back shape changes from small to large tiles
     at = SMALL_INPUT_BYTES // ks.ks_elem_bytes(dtype)
-    for n in (at - 1, at, at + 1):
+    mid = ((16 << 20) if ks.ks_elem_bytes(dtype) == 4 else (32 << 20)) // ks.ks_elem_bytes(dtype)
+    for n in (at - 1, at, at + 1, mid, mid + 1):
         x = random_input(dtype, op, n, seed=77)
         ref = reference(dtype, op, x, True)
         say(f"[case] pair=({dtype},{op}) n={n} default shape at the small-input limit")
