@@ -17,6 +17,7 @@ register file or LDS for the element type are refused by the library
 
     python -m paper_2603_18695_amd.tune --dtype f32 --op sum --log2n 28
     python -m paper_2603_18695_amd.tune --dtype u64 --op sum --log2n 27 --exclusive
+    python -m paper_2603_18695_amd.tune --dtype f32 --op sum --n 10000000
 
 Inputs are zero-initialised device buffers of the requested size unless
 --random is given (random bytes are fine for every integer and struct type;
@@ -106,6 +107,7 @@ def main(argv=None) -> int:
     ap.add_argument("--dtype", default="f32", choices=sorted(ks.DTYPES))
     ap.add_argument("--op", default="sum", choices=sorted(ks.OPS))
     ap.add_argument("--log2n", type=int, default=28)
+    ap.add_argument("--n", type=int, default=0, help="element count (overrides --log2n)")
     ap.add_argument("--exclusive", action="store_true")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=4)
@@ -117,7 +119,8 @@ def main(argv=None) -> int:
     if not ks.ks_pair_supported(args.dtype, args.op):
         print(f"({args.dtype}, {args.op}) is not an instantiated pair", file=sys.stderr)
         return 2
-    search(args.dtype, args.op, 1 << args.log2n, not args.exclusive, args.steps, args.warmup, args.random)
+    n = args.n if args.n > 0 else 1 << args.log2n
+    search(args.dtype, args.op, n, not args.exclusive, args.steps, args.warmup, args.random)
     return 0
 
 

@@ -125,6 +125,20 @@ def test_default_shape_switches_with_the_input_size(ks, dtype, op):
         assert_matches(dtype, op, got, ref, f"({dtype},{op}) n={n}")
 
 
+@pytest.mark.parametrize("dtype,op,tiles9,rows", [("i32", "sum", 300, 12), ("f32", "sum", 290, 12),
+                                                  ("u64", "sum", 400, 16), ("affine_f32", "affine_compose", 300, 9)])
+def test_a_little_more_than_one_round_runs_as_one_round(ks, dtype, op, tiles9, rows):
+    # inputs of a little more than 256 default tiles take 12 or 16 rows per thread so that one round
+    # of the 256 compute units covers them (types whose registers do not allow it keep 9 rows)
+    n = tiles9 * tile_elems(ks, dtype, 16, 9) - 5
+    x = random_input(dtype, op, n, seed=91)
+    say(f"[case] pair=({dtype},{op}) n={n}: {tiles9} default tiles, expecting {rows} rows")
+    got = run(ks, dtype, op, x, api="plain")
+    tiles = -(-n // tile_elems(ks, dtype, 16, rows))
+    assert ks.ks_get_option("last_grid") == min(tiles, 256), (tiles, ks.ks_get_option("last_grid"))
+    assert_matches(dtype, op, got, reference(dtype, op, x, True), f"({dtype},{op}) n={n}")
+
+
 def test_default_form_switches_with_the_input_size(ks):
     # 4-byte pairs other than the float32 sum run the common loop below 256 MiB of input and the
     # separate loops from there on; both sides of the limit, exact compare
