@@ -86,7 +86,12 @@ struct PairDefaults {
     // from 32 MiB (4-byte) and 64 MiB (8-byte elements) on the large shape is ahead.
     static constexpr Shape mid_shape() { return Shape{8, 8, false, kFormCommon}; }
     static constexpr size_t kMidInputBytes = sizeof(T) == 4 ? (size_t)16 << 20 : (size_t)32 << 20;
+    // 16-byte elements: only up to 1 MiB a small tile wins, 4 waves x 4 rows (kernel time against
+    // the large blocked shape: quaternions 64 KiB 5.0 / 5.9 us, 1 MiB 6.6 / 7.9; arg-max struct
+    // 1 MiB 6.8 / 7.4; at 4 MiB the blocked shape is ahead, 7.7 / 8.8).
+    static constexpr size_t kSmallInputBytes16 = (size_t)1 << 20;
     static constexpr Shape shape_for(size_t n) {
+        if (sizeof(T) >= 16 && n * sizeof(T) <= kSmallInputBytes16) return Shape{4, 4, true, kFormCommon};
         if (sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes) return small_shape();
         if (sizeof(T) < 16 && n * sizeof(T) <= kMidInputBytes) return mid_shape();
         if (sizeof(A) == 4 && n * sizeof(T) < kSeparateFromBytes) return Shape{16, 9, true, kFormCommon};

@@ -45,6 +45,8 @@ MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (4-byte) / 
 def default_shape(ks, dtype, n=None):
     """(waves, rows) the library picks for the look-back kernel of this element type and size."""
     eb = ks.ks_elem_bytes(dtype)
+    if n is not None and eb >= 16 and n * eb <= (1 << 20):
+        return 4, 4
     if n is not None and eb < 16:
         if n * eb <= SMALL_INPUT_BYTES:
             return SMALL_SHAPE
@@ -114,7 +116,8 @@ def test_default_shape_switches_with_the_input_size(ks, dtype, op):
     # at and just above the size where the default look-back shape changes from small to large tiles
     at = SMALL_INPUT_BYTES // ks.ks_elem_bytes(dtype)
     mid = ((16 << 20) if ks.ks_elem_bytes(dtype) == 4 else (32 << 20)) // ks.ks_elem_bytes(dtype)
-    for n in (at - 1, at, at + 1, mid, mid + 1):
+    tiny16 = (1 << 20) // 16
+    for n in (tiny16, tiny16 + 1, at - 1, at, at + 1, mid, mid + 1):
         x = random_input(dtype, op, n, seed=77)
         ref = reference(dtype, op, x, True)
         say(f"[case] pair=({dtype},{op}) n={n} default shape at the small-input limit")
