@@ -164,6 +164,33 @@ def main() -> int:
                "elements_per_s": done / cpu_s}
         log(f"oracle: {done} elements in {cpu_s:.2f}s -> {cpu_gbs:.2f} GB/s on 1 core; parity ok (worst ratio {worst:.3f})")
 
+    # ---- the other benchmark configurations, for context in the same run (HIP events, 50 launches each;
+    #      their parity is the GPU tests' business).  Only with the default workload and the oracle leg on.
+    others = None
+    if not args.no_cpu and args.workload == "f32_sum" and not args.n and args.algo == "auto" and not args.opt:
+        del d_in, d_out, temp
+        others = {}
+        for name, on in (("int32_sum", None), ("u64_exsum", None), ("affine", None), ("argmax", 1 << 26)):
+            ow = ks_inputs.WORKLOADS[name]
+            on = on or ow.n
+            o_in = torch.cat([to_device(c) for c in ks_inputs.chunks(name, on)])
+            o_out = torch.empty_like(o_in)
+            for _ in range(5):
+                ks.ks_scan(o_in, o_out, dtype=ow.dtype, op=ow.op, inclusive=ow.inclusive)
+            torch.cuda.synchronize()
+            o0, o1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            o0.record()
+            for _ in range(50):
+                ks.ks_scan(o_in, o_out, dtype=ow.dtype, op=ow.op, inclusive=ow.inclusive)
+            o1.record()
+            torch.cuda.synchronize()
+            ks.ks_scan_check()
+            oms = o0.elapsed_time(o1) / 50
+            ogbs = 2 * on * ow.elem_bytes / (oms * 1e-3) / 1e9
+            others[name] = {"n": on, "ms_per_step": oms, "gbs": ogbs, "pct_of_hbm_peak": 100 * ogbs / HBM_PEAK_GBS}
+            log(f"{name}: n={on} {oms * 1e3:.1f} us/step -> {ogbs:.1f} GB/s")
+            del o_in, o_out
+
     result = {
         "metric": "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X" if args.workload == "f32_sum" and n == 1 << 28
                   else f"scan GB/s (read+write), workload {args.workload} n={n}, 1 MI355X",
@@ -190,6 +217,7 @@ def main() -> int:
                      "kernel_ms": event_ms, "algorithmic_bytes": algorithmic_bytes},
         "cpu_baseline": cpu,
         "parity": parity,
+        "other_configs": others,
     }
     print(json.dumps(result), flush=True)
     return 0
