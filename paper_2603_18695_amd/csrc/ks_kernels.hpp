@@ -271,17 +271,28 @@ struct TileExchange {
     uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
 };
 
-// How long the data waves of the separate loops hold the request for the next tile back after the
-// barrier that hands the wave totals over, in units of 64 cycles (s_sleep).  The compute unit's L1
-// returns loads in order, so once the 135 KiB of the next tile are requested every poll of the
-// look-back wave comes back behind them, 6-7 us later; the pause lets the aggregate go out and the
-// first polls return before that.  Measured on MI355X (TB/s, pause 0 / 12 / 24 / 32 / 48 / 96):
-// uint64 sum 5.99 / 6.12 / 6.15 / 6.14 / 6.11 / 5.75, affine 5.14 / 5.82 / 5.84 / 5.82 / 5.81 / 5.53,
-// arg-max struct 5.5 / 5.66 / 5.86 / 6.05 / 6.05 / 5.69, quaternions 5.3 / 5.60 / 5.90 / 5.91 / 5.89 / 5.70.
-// Releasing the request by a flag in LDS as soon as the aggregate is out, or when the look-back is
-// done (bounded), measured 1-5 % below the fixed pause.  The common loop does not need it: its
-// look-back wave publishes while the other waves still fold the totals.
-constexpr int kPrefetchHold = 32;
+// Two pauses after the barrier that hands the wave totals over, in units of 64 cycles (s_sleep).
+// The compute unit's L1 returns loads in order, so once the 135 KiB of the next tile are requested
+// every poll of the look-back wave comes back behind them, 6-7 us later.  Therefore
+//   - the data waves hold the request for the next tile back (kPrefetchHold), so that the aggregate
+//     goes out and the first poll comes back before it, and
+//   - the look-back wave waits a little before its first poll (kPollDelay < kPrefetchHold), so that
+//     this poll, the one that is not caught behind the loads, already finds the aggregates its
+//     neighbours publish at about the same moment.
+// Measured on MI355X, separate loops, TB/s.  Hold alone, 0 / 12 / 24 / 32 / 48 / 96: uint64 sum
+// 5.99 / 6.12 / 6.15 / 6.14 / 6.11 / 5.75, affine 5.14 / 5.82 / 5.84 / 5.82 / 5.81 / 5.53, arg-max struct
+// 5.5 / 5.66 / 5.86 / 6.05 / 6.05 / 5.69, quaternions 5.3 / 5.60 / 5.90 / 5.91 / 5.89 / 5.70.  With the poll
+// delay (delay / hold): uint64 0/32 6.17, 16/32 6.26, 24/40 6.28, 28/32 6.15; affine 0/32 5.82, 20/32
+// 6.01, 24/40 5.99, 28/32 5.65; arg-max 0/32 6.05, 24/40 6.16, 28/44 6.17, 24/32 5.84: the hold has to
+// exceed the delay by 12-16 for the poll to be issued first.  Releasing the request by a flag in LDS
+// as soon as the aggregate is out, or when the look-back is done (bounded), measured 1-5 % below
+// the fixed pauses.  Both apply only while the workgroup has a next tile to request.
+constexpr int kPrefetchHold = 40;
+constexpr int kPollDelay = 24;
+// The same two in the common loop of the 16-wave shape (float32 sum: none 6.22, 24/40 6.29,
+// 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone changes nothing there).
+constexpr int kCommonPrefetchHold = 44;
+constexpr int kCommonPollDelay = 28;
 
 // Arguments of the look-back kernel that its loops pass around.
 struct LookbackArgs {
@@ -328,7 +339,7 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
 // gives the tile's aggregate, the exclusive one every data wave's carry), publish,
 // look back, hand the prefix over, barrier.  The two loops below execute the
 // same number of barriers per tile and leave together.
-template <class A, class Op, int WAVES>
+template <class A, class Op, int WAVES, bool PREFETCH>
 __device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileExchange<A, WAVES> &x) {
     Op op;
     const int lane = threadIdx.x & (kWave - 1);
@@ -343,6 +354,7 @@ __device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileEx
         const A before = wave_shift_up(upto, Op::identity());
         if (lane < WAVES - 1) x.carry[lane + 1] = to_words(before);
         publish_aggregate<A, Op>(a, tile, aggregate);
+        if (PREFETCH && tile + gridDim.x < a.ntiles) __builtin_amdgcn_s_sleep(kPollDelay);   // while the data waves hold
         resolve_prefix<A, Op, WAVES>(a, tile, m, aggregate, x);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
@@ -520,12 +532,14 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
         RawItems<ROWS> nxt;
         TileWindow wnext;
         if (data_wave && PREFETCH && next < ntiles) {
+            if (DEDICATED) __builtin_amdgcn_s_sleep(kCommonPrefetchHold);
             wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
             load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
             A excl = Op::identity();
             bool ok = true;
+            if (DEDICATED && PREFETCH && next < ntiles) __builtin_amdgcn_s_sleep(kCommonPollDelay);
             if (tile != 0) {
                 ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
                 if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
@@ -580,12 +594,12 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
         if constexpr (FORM == kFormBlocked) {
             __shared__ u32x4 stage[(WAVES - 1) * Stage<ROWS>::SLOTS];
             if (threadIdx.x < kWave)
-                lookback_wave_loop<A, Op, WAVES>(a, x);
+                lookback_wave_loop<A, Op, WAVES, PREFETCH>(a, x);
             else
                 blocked_data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, stage);
         } else {
             if (threadIdx.x < kWave)
-                lookback_wave_loop<A, Op, WAVES>(a, x);
+                lookback_wave_loop<A, Op, WAVES, PREFETCH>(a, x);
             else
                 data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
         }
