@@ -186,8 +186,9 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "form"         16-wave shape only: 0 = one common loop for all waves, 1 = the
  *                  look-back wave and the data waves run loops of their own (fewer
  *                  registers, for wide element types), 2 = as 1, and every lane scans
- *                  consecutive elements after an exchange through LDS (rows 8 or 9);
- *                  -1 = the type's default
+ *                  consecutive elements after an exchange through LDS (rows 8 or 9),
+ *                  3 = the common loop with two pauses that pay on long inputs (9 rows
+ *                  with prefetch only); -1 = the default for the pair and the input size
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
  *                  workgroup per tile, which is only deadlock-free if the hardware
  *                  starts workgroups in index order (experimental; waits stay bounded)

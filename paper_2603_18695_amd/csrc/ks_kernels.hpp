@@ -293,6 +293,7 @@ constexpr int kPollDelay = 24;
 // 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone changes nothing there).
 constexpr int kCommonPrefetchHold = 44;
 constexpr int kCommonPollDelay = 28;
+constexpr uint32_t kCommonPacedRounds = 20;   // the host takes the paced common loop from this many rounds on
 
 // Arguments of the look-back kernel that its loops pass around.
 struct LookbackArgs {
@@ -487,7 +488,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
 
 // One loop for all waves: wave 0 looks back, and holds data as well unless the
 // shape has a dedicated look-back wave.
-template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool PACED>
 __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n,
                                                  uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
                                                  uint32_t spin_limit, uint32_t *abort_flag) {
@@ -509,6 +510,10 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
 
     uint32_t tile = blockIdx.x;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
+    // The two pauses pay from some twenty rounds per workgroup on (float32 sum, with / without, TB/s:
+    // 2^24 5.62 / 5.96, 2^26 5.64 / 5.78, 2^27 6.01 / 6.06, 2^28 6.30 / 6.22), and a run-time switch in
+    // this loop costs the unpaced case 4-5 %: two kernels, chosen by the host.
+    constexpr bool paced = DEDICATED && PACED;
     Items cur;
     if (data_wave) {
         const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
@@ -532,14 +537,14 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
         RawItems<ROWS> nxt;
         TileWindow wnext;
         if (data_wave && PREFETCH && next < ntiles) {
-            if (DEDICATED) __builtin_amdgcn_s_sleep(kCommonPrefetchHold);
+            if (paced) __builtin_amdgcn_s_sleep(kCommonPrefetchHold);
             wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
             load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
             A excl = Op::identity();
             bool ok = true;
-            if (DEDICATED && PREFETCH && next < ntiles) __builtin_amdgcn_s_sleep(kCommonPollDelay);
+            if (paced && PREFETCH && next < ntiles) __builtin_amdgcn_s_sleep(kCommonPollDelay);
             if (tile != 0) {
                 ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
                 if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
@@ -575,6 +580,7 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
 constexpr int kFormCommon = 0;     // one loop for all waves
 constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in loops of their own, striped items
 constexpr int kFormBlocked = 2;    // the same with the blocked arrangement (LDS exchange)
+constexpr int kFormCommonPaced = 3;   // the common loop of the 16-wave shape with the two pauses (long inputs)
 
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
 __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out,
@@ -588,7 +594,7 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
     }
     using A = typename Op::acc;
     if (blockIdx.x >= ntiles) return;
-    if constexpr (dedicated_lookback_wave(WAVES) && FORM != kFormCommon) {
+    if constexpr (dedicated_lookback_wave(WAVES) && FORM != kFormCommon && FORM != kFormCommonPaced) {
         __shared__ TileExchange<A, WAVES> x;
         const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
         if constexpr (FORM == kFormBlocked) {
@@ -604,8 +610,8 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
                 data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
         }
     } else {
-        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, n, desc, xdesc, epoch, ntiles, spin_limit,
-                                                                   abort_flag);
+        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM == kFormCommonPaced>(
+            in, out, n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag);
     }
 }
 

@@ -23,7 +23,7 @@ inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 struct Shape {
     int waves, rows;
     bool prefetch;
-    int form;     // kFormCommon / kFormSeparate / kFormBlocked (the last two: 16 waves only)
+    int form;     // kFormCommon / kFormSeparate / kFormBlocked / kFormCommonPaced (the last three: 16 waves only)
 };
 
 // Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
@@ -33,6 +33,8 @@ struct Shape {
 // correct); the defaults below were checked not to.
 template <class T, class A, int WAVES, int ROWS, bool PREFETCH, int FORM>
 constexpr bool variant_fits() {
+    if (FORM == kFormCommonPaced)   // compiled in the default shape only: it exists for long inputs
+        return WAVES == 16 && ROWS == 9 && PREFETCH && variant_fits<T, A, WAVES, ROWS, PREFETCH, kFormCommon>();
     constexpr bool SPLIT = FORM != kFormCommon;
     if (SPLIT && !dedicated_lookback_wave(WAVES)) return false;   // nothing to separate
     if (WAVES == 16 && ROWS == 4) return false;                   // never competitive, not compiled
@@ -127,8 +129,16 @@ struct Pair {
         return s;
     }
 
+    // the common loop of the default shape takes its paced variant for long inputs
+    static Shape paced_shape(size_t n, int cus, Shape s) {
+        if (s.waves == 16 && s.rows == 9 && s.prefetch && s.form == kFormCommon &&
+            ceil_div(n, shape_tile_elems(16, 9)) >= (size_t)kCommonPacedRounds * (size_t)cus)
+            s.form = kFormCommonPaced;
+        return s;
+    }
+
     static Shape lookback_shape(size_t n, int cus) {
-        Shape s = PairDefaults<T, Op>::shape_for(n);
+        Shape s = paced_shape(n, cus, PairDefaults<T, Op>::shape_for(n));
         if (MapOf<Op>::mapped) return s;
         s = one_round_shape(n, cus, s);
         const Options &o = options();
@@ -241,6 +251,7 @@ struct Pair {
         if constexpr (dedicated_lookback_wave(WAVES)) {
             if (s.form == kFormSeparate) return lookback_flags_dispatch<WAVES, ROWS, kFormSeparate>(c, s.prefetch);
             if (s.form == kFormBlocked) return lookback_flags_dispatch<WAVES, ROWS, kFormBlocked>(c, s.prefetch);
+            if (s.form == kFormCommonPaced) return lookback_flags_dispatch<WAVES, ROWS, kFormCommonPaced>(c, s.prefetch);
         }
         return lookback_flags_dispatch<WAVES, ROWS, kFormCommon>(c, s.prefetch);
     }
@@ -269,6 +280,10 @@ struct Pair {
             if constexpr (sizeof(A) == 4 && d.form != kFormCommon) {
                 if (c.n * sizeof(T) < PairDefaults<T, Op>::kSeparateFromBytes)
                     return lookback_flags_dispatch<d.waves, d.rows, kFormCommon>(c, d.prefetch);
+            }
+            if constexpr (d.form == kFormCommon) {
+                if (paced_shape(c.n, c.dev->cus, d).form == kFormCommonPaced)
+                    return lookback_flags_dispatch<d.waves, d.rows, kFormCommonPaced>(c, d.prefetch);
             }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
         }

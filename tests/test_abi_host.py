@@ -150,7 +150,7 @@ def test_options_are_validated(ks):
     assert ks.ks_get_option("form") == 2
     ks.ks_set_option("form", -1)
     with pytest.raises(ks.KsError):
-        ks.ks_set_option("form", 3)
+        ks.ks_set_option("form", 4)
     assert ks.ks_get_option("no_such_option") == -1
 
 

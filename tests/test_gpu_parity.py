@@ -215,7 +215,7 @@ def test_in_place_and_misaligned_pointers(ks):
             assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
 
 
-@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2)])
+@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2), (16, 3)])
 @pytest.mark.parametrize("rows", [4, 8, 9, 12, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
 def test_lookback_variants(ks, waves, form, rows, prefetch):
