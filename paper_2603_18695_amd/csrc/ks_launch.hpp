@@ -51,11 +51,11 @@ constexpr bool variant_fits() {
 
 // Default shape per pair: the best measured on MI355X, always 15 data waves + 1
 // look-back wave, 9 rows, next tile prefetched (TB/s at 2 GiB of traffic):
-//   float32 sum        common loop                                     6.25  (separate loops 6.08)
-//   other 4-byte pairs separate loops   int32 sum 6.08 (common 5.94), int32 min 6.09 (5.80),
+//   float32 sum        common loop, with pauses from 20 rounds on      6.30  (separate loops 6.17)
+//   other 4-byte pairs separate loops   int32 sum 6.16 (common 5.94), int32 min 6.09 (5.80),
 //                                       float32 max 6.13 (6.00), uint32 sum 6.05 (5.93)
-//   everything wider   separate loops, blocked arrangement   uint64 / float64 sum 6.15,
-//                      affine 5.8, arg-max struct 6.05, 2x2 matrices 6.0, quaternions 5.9
+//   everything wider   separate loops, blocked arrangement   uint64 / float64 sum 6.27,
+//                      affine 5.9-6.0, arg-max struct 6.15, 2x2 matrices 6.0, quaternions 5.9
 // The float32 sum is the one kernel whose common loop the compiler schedules better
 // than its separate loops; why exactly is not known (same algorithm, same bytes).
 //
