@@ -54,8 +54,9 @@ constexpr bool variant_fits() {
 //   float32 sum        common loop, with pauses from 20 rounds on      6.30  (separate loops 6.17)
 //   other 4-byte pairs separate loops   int32 sum 6.16 (common 5.94), int32 min 6.09 (5.80),
 //                                       float32 max 6.13 (6.00), uint32 sum 6.05 (5.93)
-//   everything wider   separate loops, blocked arrangement   uint64 / float64 sum 6.27,
-//                      affine 5.9-6.0, arg-max struct 6.15, 2x2 matrices 6.0, quaternions 5.9
+//   8-byte scalars     separate loops, 8 rows                  uint64 / float64 sum 6.32
+//   everything else    separate loops, blocked arrangement   affine 5.9-6.0, arg-max struct 6.15,
+//                      2x2 matrices 6.25, quaternions 6.16
 // The float32 sum is the one kernel whose common loop the compiler schedules better
 // than its separate loops; why exactly is not known (same algorithm, same bytes).
 //
@@ -74,6 +75,9 @@ struct PairDefaults {
     static constexpr bool kFloat32Sum = std::is_same<typename MapOf<Op>::unmapped, SumOp<float>>::value;
     static constexpr Shape shape() {
         if (sizeof(A) == 4) return Shape{16, 9, true, kFloat32Sum ? kFormCommon : kFormSeparate};
+        // 8-byte scalars: 8 rows in striped separate loops measure 1 % above 9 rows blocked
+        // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s)
+        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{16, 8, true, kFormSeparate};
         return Shape{16, 9, true, kFormBlocked};
     }
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
@@ -119,8 +123,8 @@ struct Pair {
     // rows per thread it fits one round (float32 sum, n = 10^7, 290 default tiles on 256 compute
     // units: 5.09 TB/s with 12 rows against 4.61).  Nothing to prefetch then.
     static Shape one_round_shape(size_t n, int cus, Shape s) {
-        if (sizeof(T) >= 16 || s.waves != 16 || s.rows != 9) return s;
-        if (ceil_div(n, shape_tile_elems(16, 9)) <= (size_t)cus) return s;
+        if (sizeof(T) >= 16 || s.waves != 16 || s.rows > 9) return s;
+        if (ceil_div(n, shape_tile_elems(16, s.rows)) <= (size_t)cus) return s;
         constexpr int form = sizeof(A) == 4 ? kFormCommon : kFormSeparate;
         if (variant_fits<T, A, 16, 12, false, form>() && ceil_div(n, shape_tile_elems(16, 12)) <= (size_t)cus)
             return Shape{16, 12, false, form};

@@ -52,7 +52,14 @@ def default_shape(ks, dtype, n=None):
             return SMALL_SHAPE
         if n * eb <= ((16 << 20) if eb == 4 else (32 << 20)):
             return MID_SHAPE
-    return 16, 9
+    waves, rows = (16, 8) if dtype in ("i64", "u64", "f64") else (16, 9)
+    # a little more than one round of 256 tiles: 12 or 16 rows if that makes it one round (the affine
+    # type's registers allow neither)
+    if n is not None and eb < 16 and dtype != "affine_f32" and -(-n // tile_elems(ks, dtype, waves, rows)) > 256:
+        for more in (12, 16):
+            if -(-n // tile_elems(ks, dtype, waves, more)) <= 256:
+                return waves, more
+    return waves, rows
 
 
 RTS_SHAPE = (4, 4)   # tile of the reduce-then-scan kernels
