@@ -289,11 +289,12 @@ struct TileExchange {
 // the fixed pauses.  Both apply only while the workgroup has a next tile to request.
 constexpr int kPrefetchHold = 40;
 constexpr int kPollDelay = 24;
-// The same two in the common loop of the 16-wave shape (float32 sum: none 6.22, 24/40 6.29,
-// 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone changes nothing there).
+// The same two in the common loop of the 16-wave shape (float32 sum 2^28, before the staggered
+// start: none 6.22, 24/40 6.29, 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone
+// changes nothing there).
 constexpr int kCommonPrefetchHold = 44;
 constexpr int kCommonPollDelay = 28;
-constexpr uint32_t kCommonPacedRounds = 20;   // the host takes the paced common loop from this many rounds on
+constexpr uint32_t kCommonPacedRounds = 12;   // the host takes the paced common loop from this many rounds on
 
 // Arguments of the look-back kernel that its loops pass around.
 struct LookbackArgs {
@@ -510,9 +511,10 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
 
     uint32_t tile = blockIdx.x;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
-    // The two pauses pay from some twenty rounds per workgroup on (float32 sum, with / without, TB/s:
-    // 2^24 5.62 / 5.96, 2^26 5.64 / 5.78, 2^27 6.01 / 6.06, 2^28 6.30 / 6.22), and a run-time switch in
-    // this loop costs the unpaced case 4-5 %: two kernels, chosen by the host.
+    // The two pauses pay from a dozen rounds per workgroup on (float32 sum with the staggered start,
+    // with / without, TB/s: 2^24 5.60 / 5.89, 2^25 5.71 / 5.84, 2^26 6.13 / 6.13, 2^27 6.34 / 6.25, 2^28
+    // 6.46 / 6.29), and a run-time switch in this loop costs the unpaced case 4-5 %: two kernels,
+    // chosen by the host.
     constexpr bool paced = DEDICATED && PACED;
     Items cur;
     if (data_wave) {
@@ -576,6 +578,25 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
     }
 }
 
+// Staggered start (16-wave shape, one workgroup per compute unit).  Left alone, all workgroups
+// request their first tile in the same instant and then move in lock-step rounds, so that the whole
+// chip reads at one time and writes at another.  Spreading the starts over about a third of a round
+// (workgroup b waits b / grid of kStartStagger x 64 cycles) lets reads and writes of different compute
+// units overlap and every tile find its predecessors' descriptors already there.  Measured, TB/s,
+// stagger 0 / 75 / 150 / 300: float32 sum 2^28 6.29 / 6.40 / 6.45 / 6.34, 2^26 5.78 / 6.05 / 6.12 / -,
+// uint64 sum 2^27 6.33 / 6.39 / 6.43 / 6.33, 2^25 5.83 / 6.11 / 6.15 / -, arg-max struct 2^26 6.14 / - / 6.25 /
+// 6.18, 2^24 5.60 / 5.84 / 5.91 / -, affine 2^26 5.97 / - / 6.18 (100) / 6.05.  With fewer than about
+// three rounds per workgroup the wait costs more than it gives (float32 2^24, 1.9 rounds: 5.95 / 5.68 /
+// 5.36), so it applies from kStaggerFromRounds rounds on.
+constexpr uint32_t kStartStagger = 150;
+constexpr uint32_t kStaggerFromRounds = 3;
+
+__device__ __forceinline__ void stagger_start(uint32_t ntiles) {
+    if (ntiles < kStaggerFromRounds * gridDim.x) return;
+    const uint32_t pauses = blockIdx.x * kStartStagger / gridDim.x;
+    for (uint32_t i = 0; i < pauses; ++i) __builtin_amdgcn_s_sleep(1);
+}
+
 // FORM: which loop the kernel runs (see above).
 constexpr int kFormCommon = 0;     // one loop for all waves
 constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in loops of their own, striped items
@@ -594,6 +615,7 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
     }
     using A = typename Op::acc;
     if (blockIdx.x >= ntiles) return;
+    if constexpr (dedicated_lookback_wave(WAVES)) stagger_start(ntiles);
     if constexpr (dedicated_lookback_wave(WAVES) && FORM != kFormCommon && FORM != kFormCommonPaced) {
         __shared__ TileExchange<A, WAVES> x;
         const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};

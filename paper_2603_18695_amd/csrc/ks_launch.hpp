@@ -51,12 +51,10 @@ constexpr bool variant_fits() {
 
 // Default shape per pair: the best measured on MI355X, always 15 data waves + 1
 // look-back wave, 9 rows, next tile prefetched (TB/s at 2 GiB of traffic):
-//   float32 sum        common loop, with pauses from 20 rounds on      6.30  (separate loops 6.17)
-//   other 4-byte pairs separate loops   int32 sum 6.16 (common 5.94), int32 min 6.09 (5.80),
-//                                       float32 max 6.13 (6.00), uint32 sum 6.05 (5.93)
-//   8-byte scalars     separate loops, 8 rows                  uint64 / float64 sum 6.32
-//   everything else    separate loops, blocked arrangement   affine 5.9-6.0, arg-max struct 6.15,
-//                      2x2 matrices 6.25, quaternions 6.16
+//   float32 sum        common loop, with pauses from 12 rounds on      6.46  (separate loops 6.32)
+//   other 4-byte pairs separate loops   int32 sum 6.31 (common 5.93)
+//   8-byte scalars     separate loops, 8 rows                  uint64 / float64 sum 6.43
+//   everything else    separate loops, blocked arrangement   affine 6.18, arg-max struct 6.25
 // The float32 sum is the one kernel whose common loop the compiler schedules better
 // than its separate loops; why exactly is not known (same algorithm, same bytes).
 //
@@ -83,9 +81,9 @@ struct PairDefaults {
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
     static constexpr size_t kSmallInputBytes = (size_t)8 << 20;
     // 4-byte pairs below this size stay in the common loop: with only a few rounds per workgroup
-    // the separate loops and their pause do not pay yet (int32 sum, common / separate, TB/s:
-    // 32 MiB 5.24 / 5.21, 64 MiB 5.91 / 5.69, 128 MiB 5.57 / 5.53, 256 MiB 5.59 / 5.63, 1 GiB 5.87 / 6.04).
-    static constexpr size_t kSeparateFromBytes = (size_t)256 << 20;
+    // the separate loops and their pauses do not pay yet (int32 sum, common / separate, TB/s:
+    // 64 MiB 5.89 / 5.91, 128 MiB 5.37 / 5.76, 256 MiB 5.68 / 6.08, 1 GiB 5.93 / 6.31).
+    static constexpr size_t kSeparateFromBytes = (size_t)128 << 20;
     // Between the two, 8 waves x 8 rows (64 KiB tiles, no next tile to prefetch): up to 34 MiB the
     // large tile leaves compute units without work (16 MiB are 124 tiles of 135 KiB).  Against the
     // large shape, TB/s: int32 sum 16 MiB 3.48 / 3.18, uint64 sum 16 MiB 3.35 / 3.07, 32 MiB 5.11 / 4.75;

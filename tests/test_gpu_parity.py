@@ -150,9 +150,9 @@ def test_a_little_more_than_one_round_runs_as_one_round(ks, dtype, op, tiles9, r
 
 
 def test_default_form_switches_with_the_input_size(ks):
-    # 4-byte pairs other than the float32 sum run the common loop below 256 MiB of input and the
+    # 4-byte pairs other than the float32 sum run the common loop below 128 MiB of input and the
     # separate loops from there on; both sides of the limit, exact compare
-    at = (256 << 20) // 4
+    at = (128 << 20) // 4
     for n in (at - 1, at):
         x = ks_inputs.whole("int32_sum", n)
         say(f"[case] (i32,sum) n={n} at the size where the default form changes")
