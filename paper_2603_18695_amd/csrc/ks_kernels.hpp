@@ -292,8 +292,11 @@ constexpr int kPollDelay = 24;
 // The same two in the common loop of the 16-wave shape (float32 sum 2^28, before the staggered
 // start: none 6.22, 24/40 6.29, 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone
 // changes nothing there).
-constexpr int kCommonPrefetchHold = 44;
-constexpr int kCommonPollDelay = 28;
+// With the staggered start (below) longer pauses are a little better for it: 28/44 6.45, 36/52 6.47,
+// 44/60 6.48-6.50, 52/68 6.46, 60/80 6.43; the separate loops stay at 24/40, which is also the better
+// pair for inputs of a few rounds (uint64 sum 64 MiB: 5.15 against 4.91 with 40/56).
+constexpr int kCommonPrefetchHold = 60;
+constexpr int kCommonPollDelay = 44;
 constexpr uint32_t kCommonPacedRounds = 12;   // the host takes the paced common loop from this many rounds on
 
 // Arguments of the look-back kernel that its loops pass around.
