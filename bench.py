@@ -7,7 +7,10 @@ Default workload: BASELINE's headline configuration, inclusive float32 sum scan 
 values uniform in [0, 1) from seed 1.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--stride S] [--no-cpu]
+
+With --stride S > 1 (scalar workloads) the same elements sit S elements apart in both buffers and
+ks_scan_strided runs; GB/s still counts the elements alone (2 * n * element size).
 """
 from __future__ import annotations
 
@@ -53,6 +56,7 @@ def main() -> int:
     ap.add_argument("--workload", default="f32_sum")
     ap.add_argument("--n", type=int, default=0)
     ap.add_argument("--algo", default="auto", choices=["auto", "lookback", "reduce_then_scan"])
+    ap.add_argument("--stride", type=int, default=1, help="element stride of both views (ks_scan_strided)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (cpu_baseline = null)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
     args = ap.parse_args()
@@ -89,8 +93,19 @@ def main() -> int:
                        device="cuda")
     log(f"inputs: workload={args.workload} n={n} ({n * eb / 2**20:.0f} MiB each way) generated in {time.time() - t0:.1f}s")
 
+    if args.stride > 1:
+        if d_in.dim() != 1 or args.algo != "auto":
+            log("bench.py: --stride applies to the scalar workloads with --algo auto")
+            return 2
+        s_in = torch.zeros(n * args.stride, dtype=d_in.dtype, device="cuda")
+        s_in[::args.stride] = d_in
+        s_out = torch.zeros_like(s_in)
+
     def step():
-        if args.algo == "auto":
+        if args.stride > 1:
+            ks.ks_scan_strided(s_in, s_out, dtype=w.dtype, op=w.op, n=n, in_stride=args.stride,
+                               out_stride=args.stride, inclusive=w.inclusive)
+        elif args.algo == "auto":
             ks.ks_scan(d_in, d_out, dtype=w.dtype, op=w.op, inclusive=w.inclusive)
         else:
             ks.ks_scan_with_temp(d_in, d_out, temp, dtype=w.dtype, op=w.op, inclusive=w.inclusive, algo=args.algo)
@@ -142,6 +157,8 @@ def main() -> int:
         import oracle
         step()
         torch.cuda.synchronize()
+        if args.stride > 1:
+            d_out = s_out[::args.stride].contiguous()
         oop, odt, _, _ = KINDS[(w.dtype, w.op)]
         budget_elems = min(n, 1 << 28)
         stream = oracle.ScanStream(oop, odt, w.inclusive)
@@ -167,7 +184,8 @@ def main() -> int:
     # ---- the other benchmark configurations, for context in the same run (HIP events, 50 launches each;
     #      their parity is the GPU tests' business).  Only with the default workload and the oracle leg on.
     others = None
-    if not args.no_cpu and args.workload == "f32_sum" and not args.n and args.algo == "auto" and not args.opt:
+    if (not args.no_cpu and args.workload == "f32_sum" and not args.n and args.algo == "auto" and not args.opt
+            and args.stride == 1):
         del d_in, d_out, temp
         others = {}
         for name, on in (("int32_sum", None), ("u64_exsum", None), ("affine", None), ("argmax", 1 << 26)):
@@ -192,8 +210,10 @@ def main() -> int:
             del o_in, o_out
 
     result = {
-        "metric": "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X" if args.workload == "f32_sum" and n == 1 << 28
-                  else f"scan GB/s (read+write), workload {args.workload} n={n}, 1 MI355X",
+        "metric": "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X"
+                  if args.workload == "f32_sum" and n == 1 << 28 and args.stride == 1
+                  else f"scan GB/s (read+write), workload {args.workload} n={n}"
+                       f"{'' if args.stride == 1 else f' element stride {args.stride}'}, 1 MI355X",
         "value": gbs_wall,
         "unit": "GB/s",
         "n_gpus": 1,
@@ -206,14 +226,15 @@ def main() -> int:
         "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64"}[args.workload],
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
-                               f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb,
+                               f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb, "stride": args.stride,
                    "options": {k: ks.ks_get_option(k) for k in ["waves", "rows", "prefetch", "form", "grid_mode", "wgs_per_cu"]}},
         "elements_per_s": n / (wall_ms * 1e-3),
         "pct_of_hbm_peak": 100 * gbs_wall / HBM_PEAK_GBS,
         "copy_ceiling_gbs": copy_gbs,
         "roofline": {"bound": "hbm", "achieved": gbs_event, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs_event / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(args.workload, n) if args.algo == "auto" and not args.opt else None,
+                     "traffic": measured_traffic(args.workload, n)
+                                if args.algo == "auto" and not args.opt and args.stride == 1 else None,
                      "kernel_ms": event_ms, "algorithmic_bytes": algorithmic_bytes},
         "cpu_baseline": cpu,
         "parity": parity,

@@ -121,9 +121,9 @@ int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void 
  * that is not contiguous): element i of the input is in[i * in_stride], element
  * i of the output out[i * out_stride], strides in elements, >= 1 and <= 2^20
  * (e.g. one column of a row-major matrix).  Elements between the strides are
- * neither read nor written.  Runs the reduce-then-scan strategy (deterministic,
- * three passes over the view) with a library-owned workspace; with both strides
- * 1 it is ks_scan.  In place (in == out and equal strides) is allowed; views
+ * neither read nor written.  Runs the single-pass look-back scan (Sec. V-B) with
+ * one-element accesses and a library-owned workspace; with both strides 1 it is
+ * ks_scan.  In place (in == out and equal strides) is allowed; views
  * whose byte spans overlap otherwise are refused with KS_ERR_OVERLAP, also when
  * their elements interleave without touching.  Other arguments and errors as
  * for ks_scan.

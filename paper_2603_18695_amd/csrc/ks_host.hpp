@@ -43,6 +43,9 @@ struct ScanCall {
     uint32_t epoch;         // tag for this call's descriptors (look-back only)
     bool clear_descriptors; // scratch contents unknown: zero the descriptors first
     const DeviceInfo *dev;
+    // strided views (paper Sec. IV-C): element i at in[i * in_stride] / out[i * out_stride]; always
+    // the look-back algorithm, temp as for it
+    size_t in_stride = 1, out_stride = 1;
 };
 
 // One entry per instantiated (dtype, op) pair.
@@ -52,9 +55,6 @@ struct PairEntry {
     size_t (*temp_bytes)(ks_algo algo, size_t n);
     ks_algo (*pick_algo)(size_t n);
     int (*run)(const ScanCall &call);   // returns ks_status; HIP failures via set_hip_error
-    // strided views: element i at in[i * in_stride] / out[i * out_stride]; temp as for reduce-then-scan
-    int (*run_strided)(int inclusive, const void *in, size_t in_stride, void *out, size_t out_stride, size_t n,
-                       void *temp, size_t temp_bytes, hipStream_t stream);
 };
 
 int set_hip_error(hipError_t e);   // records e, returns KS_ERR_HIP

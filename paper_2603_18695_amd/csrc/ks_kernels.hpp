@@ -3,7 +3,7 @@
 //   scan_lookback_kernel   single pass, decoupled look-back (paper Sec. V-B)
 //   tile_reduce_kernel     reduce-then-scan, first kernel: one aggregate per tile
 //   tile_scan_kernel       reduce-then-scan, last kernel: scan a tile from a seed
-//   tile_*_strided_kernel  the same two for strided views (paper Sec. IV-C)
+//   scan_lookback_strided_kernel  the look-back scan over strided views (paper Sec. IV-C)
 //   fill_zero_kernel       clears caller-provided descriptors
 //   copy_kernel            vectorised copy, the bandwidth ceiling (paper Sec. IV-C)
 //
@@ -685,46 +685,60 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out
                                                op(seed, wave_carry), op);
 }
 
-// The same two kernels for a strided view at the lowest level (element i at
-// base[i * stride]); the aggregates and everything above them are contiguous
-// and go through the kernels above.
-template <class IO, class Op, int ROWS>
-__global__ __launch_bounds__(kBlock) void tile_reduce_strided_kernel(const IO *__restrict__ in, size_t in_stride,
-                                                                     size_t n,
-                                                                     typename Op::acc *__restrict__ aggregates) {
-    using A = typename Op::acc;
-    using S = TileShape<IO, ROWS>;
-    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
-    __shared__ typename WordsOf<A>::type s_tot[kWaves];
-    Op op;
-    const size_t tile = blockIdx.x;
-    ThreadItems<A, ROWS, S::G> cur;
-    load_items_strided<IO, ROWS, Op>(in, in_stride, n, tile * TILE + (threadIdx.x >> 6) * (size_t)S::WAVE_ELEMS, cur);
-    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-    A aggregate;
-    (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
-    if (threadIdx.x == 0) aggregates[tile] = aggregate;
-}
-
+// Single-pass scan of a strided view (element i at base[i * stride], paper Sec. IV-C): the
+// look-back protocol of scan_lookback_kernel (Sec. V-B) with one-element accesses and one-element
+// granules (a tile is 4 waves x ROWS rows x 64 elements).  Four waves, all holding data, no
+// prefetch: a strided access pattern is bound by the sectors it touches, and many small workgroups
+// per compute unit keep more of them in flight than one large one.
 template <class IO, class Op, int ROWS, bool INCLUSIVE>
-__global__ __launch_bounds__(kBlock) void tile_scan_strided_kernel(const IO *in, size_t in_stride, IO *out,
-                                                                   size_t out_stride, size_t n,
-                                                                   const typename Op::acc *__restrict__ seeds) {
+__global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO *in, size_t in_stride, IO *out,
+                                                                       size_t out_stride, size_t n, uint64_t *desc,
+                                                                       uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
+                                                                       uint32_t spin_limit, uint32_t *abort_flag,
+                                                                       uint32_t *residency) {
+    if (residency) {   // residency check of this very kernel: no scan work
+        residency_check(residency, spin_limit);
+        return;
+    }
     using A = typename Op::acc;
-    using S = TileShape<IO, ROWS>;
-    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    constexpr size_t WAVE_ELEMS = (size_t)kWave * ROWS;   // one-element granules
+    constexpr size_t TILE = (size_t)kWaves * WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
+    __shared__ typename WordsOf<A>::type s_prefix;
+    __shared__ uint32_t s_ok;
     Op op;
-    const size_t tile = blockIdx.x;
-    const size_t run_first = tile * TILE + (threadIdx.x >> 6) * (size_t)S::WAVE_ELEMS;
-    ThreadItems<A, ROWS, S::G> cur;
-    load_items_strided<IO, ROWS, Op>(in, in_stride, n, run_first, cur);
-    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-    A aggregate;
-    const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
-    finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
-    const A seed = seeds ? seeds[tile] : Op::identity();
-    apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, n, run_first, cur, op(seed, wave_carry), op);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t run_first = (size_t)tile * TILE + (size_t)wave * WAVE_ELEMS;
+        ThreadItems<A, ROWS, 1> cur;
+        load_items_strided<IO, ROWS, Op>(in, in_stride, n, run_first, cur);
+        const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, 1, Op>(cur, op);
+        A aggregate;
+        const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+        if (wave == 0) {
+            if (lane == 0) {
+                desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+                if (tile == 0) desc_publish<A>(xdesc, 0, epoch, kPrefix, Op::identity());   // nothing before tile 0
+            }
+            A excl = Op::identity();
+            bool ok = true;
+            if (tile != 0) {
+                ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
+                if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
+            }
+            if (lane == 0) {
+                s_prefix = to_words(excl);
+                s_ok = ok ? 1u : 0u;
+            }
+        }
+        __syncthreads();
+        if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
+        const A prefix = op(from_words<A>(s_prefix), wave_carry);
+        finish_wave_run<INCLUSIVE, A, ROWS, 1, Op>(cur, ws, op);
+        apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, n, run_first, cur, prefix, op);
+    }
 }
 
 template <int UNUSED = 0>

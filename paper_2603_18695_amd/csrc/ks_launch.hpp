@@ -178,6 +178,61 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
+    // Resident workgroups per compute unit of one kernel variant on the call's device.  The runtime's
+    // occupancy query is an upper bound only; the kernel is run in its residency-check mode
+    // (launch_check(grid)) and the count stepped down until every workgroup of the grid is seen
+    // running at once.  One-off per variant and device; it synchronises the stream.
+    template <class Kernel, class LaunchCheck>
+    static int verified_residency(const ScanCall &c, std::map<int, int> &cache, Kernel kernel, int threads, int &per_cu,
+                                  LaunchCheck launch_check) {
+        int &known = cache[c.dev->device];
+        if (known == 0) {
+            int nb = 0;
+            hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, threads, 0);
+            if (e != hipSuccess) return set_hip_error(e);
+            int verified = 0;
+            for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
+                uint32_t zero[2] = {0u, 0u};
+                e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
+                if (e != hipSuccess) return set_hip_error(e);
+                launch_check((unsigned)(tryb * c.dev->cus));
+                if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
+                uint32_t seen[2] = {0u, 1u};
+                e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
+                if (e != hipSuccess) return set_hip_error(e);
+                if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
+                if (seen[1] == 0u) verified = tryb;
+            }
+            if (verified < 1) return KS_ERR_WORKSPACE;
+            known = verified;
+        }
+        per_cu = known;
+        return KS_OK;
+    }
+
+    // grid of a persistent look-back launch and the cleared descriptor arrays for `tiles` tiles
+    static size_t persistent_grid(const ScanCall &c, int per_cu, size_t tiles) {
+        long long want = options().wgs_per_cu;
+        int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
+        size_t grid = (size_t)use * (size_t)c.dev->cus;
+        if (options().grid_mode == 1 || grid > tiles) grid = tiles;
+        options().last_grid = (long long)grid;
+        options().last_resident_per_cu = per_cu;
+        return grid;
+    }
+    static void clear_descriptors_if_asked(const ScanCall &c, uint64_t *desc, size_t tiles, size_t xentries) {
+        if (!c.clear_descriptors) return;
+        const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
+        const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
+        hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
+    }
+    static uint32_t spin_limit_option() {
+        long long spin = options().spin_limit;
+        if (spin < 0) spin = 0;
+        if (spin > 0xffffffffll) spin = 0xffffffffll;
+        return (uint32_t)spin;
+    }
+
     template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
     static int launch_lookback(const ScanCall &c) {
         if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH, FORM>()) {
@@ -188,54 +243,24 @@ struct Pair {
             const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
             if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
-            // resident workgroups per compute unit of this variant, per device, as verified below
+            // resident workgroups per compute unit of this variant, per device
             static std::map<int, int> verified_per_cu;
-            int &per_cu = verified_per_cu[c.dev->device];
-            if (per_cu == 0) {
-                int nb = 0;
-                hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kThreads, 0);
-                if (e != hipSuccess) return set_hip_error(e);
-                // The query is an upper bound only; run the kernel in its residency-check mode and
-                // step down until every workgroup of the grid is seen running at once.  One-off per
-                // variant and device; it synchronises the stream.
-                int verified = 0;
-                for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
-                    uint32_t zero[2] = {0u, 0u};
-                    e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
-                    if (e != hipSuccess) return set_hip_error(e);
-                    hipLaunchKernelGGL(kernel, dim3((unsigned)(tryb * c.dev->cus)), dim3(kThreads), 0, c.stream,
-                                       static_cast<const T *>(nullptr), static_cast<T *>(nullptr), (size_t)0,
-                                       static_cast<uint64_t *>(nullptr), static_cast<uint64_t *>(nullptr), 0u, 0u,
-                                       (uint32_t)(1u << 16), c.dev->abort_flag, c.dev->residency);
-                    if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
-                    uint32_t seen[2] = {0u, 1u};
-                    e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
-                    if (e != hipSuccess) return set_hip_error(e);
-                    if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
-                    if (seen[1] == 0u) verified = tryb;
-                }
-                if (verified < 1) return KS_ERR_WORKSPACE;
-                per_cu = verified;
-            }
-            long long want = options().wgs_per_cu;
-            int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
-            size_t grid = (size_t)use * (size_t)c.dev->cus;
-            if (options().grid_mode == 1 || grid > tiles) grid = tiles;
-            options().last_grid = (long long)grid;
-            options().last_resident_per_cu = per_cu;
+            int per_cu = 0;
+            const int vs = verified_residency(c, verified_per_cu, kernel, kThreads, per_cu, [&](unsigned grid) {
+                hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, c.stream, static_cast<const T *>(nullptr),
+                                   static_cast<T *>(nullptr), (size_t)0, static_cast<uint64_t *>(nullptr),
+                                   static_cast<uint64_t *>(nullptr), 0u, 0u, (uint32_t)(1u << 16), c.dev->abort_flag,
+                                   c.dev->residency);
+            });
+            if (vs != KS_OK) return vs;
+            const size_t grid = persistent_grid(c, per_cu, tiles);
             uint64_t *desc = static_cast<uint64_t *>(c.temp);
             uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
-            if (c.clear_descriptors) {
-                const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
-                const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
-                hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
-            }
-            long long spin = options().spin_limit;
-            if (spin < 0) spin = 0;
-            if (spin > 0xffffffffll) spin = 0xffffffffll;
+            clear_descriptors_if_asked(c, desc, tiles, xentries);
+            const uint32_t spin = spin_limit_option();
             hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream,
                                static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch,
-                               (uint32_t)tiles, (uint32_t)spin, c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
+                               (uint32_t)tiles, spin, c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
             hipError_t e = hipGetLastError();
             return e == hipSuccess ? KS_OK : set_hip_error(e);
         }
@@ -329,49 +354,49 @@ struct Pair {
         return launch_tile_scan(inclusive, in, out, n, agg, s);
     }
 
-    // Strided view at the lowest level, contiguous aggregates above it.  temp as for reduce-then-scan.
-    static int run_strided(bool inclusive, const T *in, size_t in_stride, T *out, size_t out_stride, size_t n,
-                           char *temp, size_t temp_bytes, hipStream_t s) {
-        const size_t tile = tile_elems(kRtsRows);
-        const size_t tiles = ceil_div(n, tile);
-        A *agg = nullptr;
-        if (tiles > 1) {
-            const size_t need = align_up(tiles * sizeof(A), 256);
-            if (need > temp_bytes) return KS_ERR_WORKSPACE;
-            agg = reinterpret_cast<A *>(temp);
-            hipLaunchKernelGGL((tile_reduce_strided_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s,
-                               in, in_stride, n, agg);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return set_hip_error(e);
-            using Upper = Pair<A, typename MapOf<Op>::unmapped>;
-            int st = Upper::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
-            if (st != KS_OK) return st;
-        }
-        if (inclusive)
-            hipLaunchKernelGGL((tile_scan_strided_kernel<T, Op, kRtsRows, true>), dim3((unsigned)tiles), dim3(kBlock), 0,
-                               s, in, in_stride, out, out_stride, n, agg);
-        else
-            hipLaunchKernelGGL((tile_scan_strided_kernel<T, Op, kRtsRows, false>), dim3((unsigned)tiles), dim3(kBlock), 0,
-                               s, in, in_stride, out, out_stride, n, agg);
+    // ---- strided views -------------------------------------------------------
+    // The look-back scan with element-wise accesses and one-element granules, 4 waves x kStridedRows
+    // rows x 64 elements per tile; one tile or many.
+    static constexpr int kStridedRows = sizeof(A) >= 16 ? 8 : 16;
+    static constexpr size_t kStridedTile = (size_t)kWaves * kWave * kStridedRows;
+    // temp_bytes(KS_ALGO_LOOKBACK, n) sizes the descriptors for the smallest contiguous tile
+    static_assert(kStridedTile >= (size_t)kMinTileGranules * (16 / sizeof(T)), "strided tile below the smallest tile");
+    template <bool INCLUSIVE>
+    static int launch_lookback_strided(const ScanCall &c) {
+        auto kernel = scan_lookback_strided_kernel<T, Op, kStridedRows, INCLUSIVE>;
+        const size_t tiles = ceil_div(c.n, kStridedTile);
+        const size_t xentries = ceil_div(tiles, kWindow) * kWindow;
+        if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
+        static std::map<int, int> verified_per_cu;
+        int per_cu = 0;
+        const int vs = verified_residency(c, verified_per_cu, kernel, kBlock, per_cu, [&](unsigned grid) {
+            hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(nullptr), (size_t)1,
+                               static_cast<T *>(nullptr), (size_t)1, (size_t)0, static_cast<uint64_t *>(nullptr),
+                               static_cast<uint64_t *>(nullptr), 0u, 0u, (uint32_t)(1u << 16), c.dev->abort_flag,
+                               c.dev->residency);
+        });
+        if (vs != KS_OK) return vs;
+        const size_t grid = persistent_grid(c, per_cu, tiles);
+        uint64_t *desc = static_cast<uint64_t *>(c.temp);
+        uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
+        clear_descriptors_if_asked(c, desc, tiles, xentries);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
+                           c.in_stride, static_cast<T *>(c.out), c.out_stride, c.n, desc, xdesc, c.epoch,
+                           (uint32_t)tiles, spin_limit_option(), c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
     }
 
-    static int run_strided_entry(int inclusive, const void *in, size_t in_stride, void *out, size_t out_stride, size_t n,
-                                 void *temp, size_t temp_bytes, hipStream_t s) {
-        return run_strided(inclusive != 0, static_cast<const T *>(in), in_stride, static_cast<T *>(out), out_stride, n,
-                           static_cast<char *>(temp), temp_bytes, s);
-    }
-
     static int run(const ScanCall &c) {
+        if (c.in_stride != 1 || c.out_stride != 1)
+            return c.inclusive ? launch_lookback_strided<true>(c) : launch_lookback_strided<false>(c);
         if (c.algo == KS_ALGO_LOOKBACK) return run_lookback(c);
         return run_rts(c.inclusive != 0, static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n,
                        static_cast<char *>(c.temp), c.temp_bytes, c.stream);
     }
 
     static const PairEntry *entry() {
-        static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
-                                    &Pair::run_strided_entry};
+        static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run};
         return &e;
     }
 };

@@ -52,10 +52,6 @@ struct Workspace {
     void *ptr = nullptr;
     size_t bytes = 0;
     uint32_t epoch = 0;   // last epoch handed out; descriptors carry (epoch << 2 | state)
-    // Aggregates of the strided path live in a buffer of their own: plain values written over the
-    // tagged descriptors above could be mistaken for a descriptor of a later epoch.
-    void *plain_ptr = nullptr;
-    size_t plain_bytes = 0;
 };
 std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
 
@@ -121,10 +117,12 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
     return e->run(c);
 }
 
-// Common part of ks_scan and ks_scan_map: library-owned, epoch-tagged workspace per (device, stream).
+// Common part of ks_scan, ks_scan_map and ks_scan_strided: library-owned, epoch-tagged workspace per
+// (device, stream).  Strided views always take the look-back algorithm.
 static int scan_with_library_workspace(const PairEntry *e, int inclusive, const void *in, void *out, size_t n,
-                                       void *stream) {
-    const ks_algo algo = e->pick_algo(n);
+                                       void *stream, size_t in_stride = 1, size_t out_stride = 1) {
+    const bool strided = in_stride != 1 || out_stride != 1;
+    const ks_algo algo = strided ? KS_ALGO_LOOKBACK : e->pick_algo(n);
     const size_t need = e->temp_bytes(algo, n);
     std::lock_guard<std::mutex> lock(g_mutex);
     const DeviceInfo *dev = nullptr;
@@ -158,7 +156,8 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
         ws.epoch = 0;
     }
     if (algo == KS_ALGO_LOOKBACK) ++ws.epoch;
-    ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, ws.epoch, false, dev};
+    ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, ws.epoch, false, dev,
+               in_stride, out_stride};
     return e->run(c);
 }
 
@@ -196,26 +195,7 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
     const size_t span_in = ((n - 1) * in_stride + 1) * e->elem_bytes, span_out = ((n - 1) * out_stride + 1) * e->elem_bytes;
     const bool same_view = a == b && in_stride == out_stride;
     if (!same_view && a < b + span_out && b < a + span_in) return KS_ERR_OVERLAP;
-    const size_t need = e->temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, n);
-    std::lock_guard<std::mutex> lock(g_mutex);
-    const DeviceInfo *dev = nullptr;
-    int st;
-    if ((st = device_info(&dev)) != KS_OK) return st;
-    Workspace &ws = g_workspaces[std::make_pair(dev->device, (hipStream_t)stream)];
-    if (ws.plain_bytes < need) {
-        if (ws.plain_ptr) (void)hipFree(ws.plain_ptr);   // waits for the device: nothing in flight uses it
-        ws.plain_ptr = nullptr;
-        ws.plain_bytes = 0;
-        const size_t want = need < ((size_t)1 << 16) ? ((size_t)1 << 16) : need;
-        hipError_t he = hipMalloc(&ws.plain_ptr, want);
-        if (he != hipSuccess) {
-            ws.plain_ptr = nullptr;
-            set_hip_error(he);
-            return KS_ERR_WORKSPACE;
-        }
-        ws.plain_bytes = want;
-    }
-    return e->run_strided(inclusive, in, in_stride, out, out_stride, n, ws.plain_ptr, ws.plain_bytes, (hipStream_t)stream);
+    return scan_with_library_workspace(e, inclusive, in, out, n, stream, in_stride, out_stride);
 }
 
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {

@@ -414,38 +414,32 @@ __device__ __forceinline__ void store_raw(const TileWindow &w, int lane_bytes, c
 // ---------------------------------------------------------------------------
 // Strided views (paper Sec. IV-C: the element-wise fallback for data that is not
 // contiguous keeps the items-per-thread structure).  Element i of the view lives
-// at base[i * stride]; accesses are one element wide, the register arrangement
-// (and therefore every scan routine above) is the striped one.
+// at base[i * stride]; accesses are one element wide and the register arrangement
+// is the striped one with one-element granules (G = 1: lane l of row j holds
+// element j * 64 + l of the wave's run), so that the lanes of one access are
+// neighbours in the view and share cache lines as far as the stride allows.
 // ---------------------------------------------------------------------------
 template <class IO, int ROWS, class Op>
 __device__ __forceinline__ void load_items_strided(const IO *base, size_t stride, size_t n, size_t run_first,
-                                                   ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+                                                   ThreadItems<typename Op::acc, ROWS, 1> &it) {
     using A = typename Op::acc;
-    constexpr int G = TileShape<IO, ROWS>::G;
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const size_t i = run_first + ((size_t)j * kWave + lane) * G + k;
-            it.x[j][k] = i < n ? convert<A>(typename MapOf<Op>::type()(base[i * stride])) : Op::identity();
-        }
+        const size_t i = run_first + (size_t)j * kWave + lane;
+        it.x[j][0] = i < n ? convert<A>(typename MapOf<Op>::type()(base[i * stride])) : Op::identity();
     }
 }
 
 template <class IO, int ROWS, class A, class Op>
 __device__ __forceinline__ void apply_prefix_and_store_strided(IO *base, size_t stride, size_t n, size_t run_first,
-                                                               const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it,
-                                                               const A &prefix, Op op) {
-    constexpr int G = TileShape<IO, ROWS>::G;
+                                                               const ThreadItems<A, ROWS, 1> &it, const A &prefix,
+                                                               Op op) {
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const size_t i = run_first + ((size_t)j * kWave + lane) * G + k;
-            if (i < n) base[i * stride] = convert<IO>(op(prefix, it.x[j][k]));
-        }
+        const size_t i = run_first + (size_t)j * kWave + lane;
+        if (i < n) base[i * stride] = convert<IO>(op(prefix, it.x[j][0]));
     }
 }
 

@@ -355,7 +355,8 @@ def test_strided_views(ks, dtype, op):
     rts = tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)
     sizes = [1, 2, rts - 1, rts, rts + 1, 5 * rts + 3]
     if dtype == "i32":
-        sizes.append(rts * rts + 5)      # two levels of aggregates
+        sizes.append(rts * rts + 5)      # thousands of tiles, several look-back windows
+        sizes.append(40_000_003)         # more tiles than any resident grid: every workgroup loops
     for n in sizes:
         for in_stride, out_stride in [(3, 1), (1, 2), (5, 5)]:
             x = random_input(dtype, op, n, seed=n % 89 + in_stride)
