@@ -195,6 +195,7 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *   "last_grid", "last_resident_per_cu"   read-only: grid of the most recent look-back
  *                  launch and the verified number of resident workgroups per compute
  *                  unit of its kernel variant
+ *   "last_waves", "last_rows", "last_form"   read-only: shape and form that launch ran
  * Returns KS_OK or KS_ERR_INVALID_ARG.  ks_get_option returns the value or -1.
  */
 int ks_set_option(const char *name, long long value);

@@ -21,6 +21,7 @@ struct Options {
     long long grid_mode = 0;      // 0 = persistent resident grid, 1 = one workgroup per tile (experimental)
     long long last_grid = 0;      // read-only: workgroups of the most recent look-back launch
     long long last_resident_per_cu = 0;   // read-only: verified resident workgroups per CU of that kernel variant
+    long long last_waves = 0, last_rows = 0, last_form = 0;   // read-only: shape and form of that launch
 };
 Options &options();
 

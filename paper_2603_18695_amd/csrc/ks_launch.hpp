@@ -116,19 +116,40 @@ struct Pair {
 
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
-    // One round instead of two: an input of a little more than one round of the default tile (one
-    // tile per compute unit) would leave most compute units idle in its second round; with 12 or 16
-    // rows per thread it fits one round (float32 sum, n = 10^7, 290 default tiles on 256 compute
-    // units: 5.09 TB/s with 12 rows against 4.61).  Nothing to prefetch then.
-    static Shape one_round_shape(size_t n, int cus, Shape s) {
+    // Inputs of up to three rounds of the default tile (one tile per compute unit and round): the
+    // workgroups move in lock-step there (the staggered start begins at three rounds), so the run time
+    // goes with rounds x rows per thread, and a last round with a few tiles costs as much as a full
+    // one.  Take the rows that minimise that product; the default stays on a tie.  Measured, us per
+    // call, default rows / chosen rows: float32 sum 40 MiB 17.8 / 15.5 (12 rows, one round), 48 MiB
+    // 20.1 / 18.3 (16 rows, one round), 72 MiB 29.2 / 26.3 (12 rows, two rounds instead of three), 80 MiB
+    // 32.0 / 28.9; uint64 sum 40 MiB 18.0 / 16.1 (12 rows), 64 MiB 26.9 / 23.2 (9 rows, two rounds instead
+    // of three); 16 rows in one round against 8 rows in two is a tie by the product and measures
+    // worse (uint64 48 MiB 22.3 against 18.6), hence the tie rule.  Elements of 16 bytes keep their
+    // blocked shape.
+    static Shape few_rounds_shape(size_t n, int cus, Shape s) {
         if (sizeof(T) >= 16 || s.waves != 16 || s.rows > 9) return s;
-        if (ceil_div(n, shape_tile_elems(16, s.rows)) <= (size_t)cus) return s;
+        auto rounds = [&](int rows) { return ceil_div(ceil_div(n, shape_tile_elems(16, rows)), (size_t)cus); };
+        const size_t r0 = rounds(s.rows);
+        if (r0 <= 1 || r0 > 3) return s;
+        Shape best = s;
+        size_t best_cost = r0 * (size_t)s.rows;
+        auto consider = [&](Shape c) {
+            const size_t cost = rounds(c.rows) * (size_t)c.rows;
+            if (cost < best_cost) {
+                best = c;
+                best_cost = cost;
+            }
+        };
+        if (s.rows == 8 && s.form == kFormSeparate && variant_fits<T, A, 16, 9, true, kFormSeparate>())
+            consider(Shape{16, 9, true, kFormSeparate});
         constexpr int form = sizeof(A) == 4 ? kFormCommon : kFormSeparate;
-        if (variant_fits<T, A, 16, 12, false, form>() && ceil_div(n, shape_tile_elems(16, 12)) <= (size_t)cus)
-            return Shape{16, 12, false, form};
-        if (variant_fits<T, A, 16, 16, false, kFormSeparate>() && ceil_div(n, shape_tile_elems(16, 16)) <= (size_t)cus)
-            return Shape{16, 16, false, kFormSeparate};
-        return s;
+        if (variant_fits<T, A, 16, 12, true, kFormSeparate>())
+            consider(Shape{16, 12, true, kFormSeparate});
+        else if (variant_fits<T, A, 16, 12, false, form>())
+            consider(Shape{16, 12, false, form});
+        if (variant_fits<T, A, 16, 16, false, kFormSeparate>() && rounds(16) == 1)
+            consider(Shape{16, 16, false, kFormSeparate});
+        return best;
     }
 
     // the common loop of the default shape takes its paced variant for long inputs
@@ -142,7 +163,7 @@ struct Pair {
     static Shape lookback_shape(size_t n, int cus) {
         Shape s = paced_shape(n, cus, PairDefaults<T, Op>::shape_for(n));
         if (MapOf<Op>::mapped) return s;
-        s = one_round_shape(n, cus, s);
+        s = few_rounds_shape(n, cus, s);
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
         if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
@@ -254,6 +275,9 @@ struct Pair {
             });
             if (vs != KS_OK) return vs;
             const size_t grid = persistent_grid(c, per_cu, tiles);
+            options().last_waves = WAVES;
+            options().last_rows = ROWS;
+            options().last_form = FORM;
             uint64_t *desc = static_cast<uint64_t *>(c.temp);
             uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
             clear_descriptors_if_asked(c, desc, tiles, xentries);
@@ -377,6 +401,9 @@ struct Pair {
         });
         if (vs != KS_OK) return vs;
         const size_t grid = persistent_grid(c, per_cu, tiles);
+        options().last_waves = kWaves;
+        options().last_rows = kStridedRows;
+        options().last_form = kFormCommon;
         uint64_t *desc = static_cast<uint64_t *>(c.temp);
         uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
         clear_descriptors_if_asked(c, desc, tiles, xentries);

@@ -247,6 +247,9 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
     if (!std::strcmp(name, "last_grid")) return &o.last_grid;
     if (!std::strcmp(name, "last_resident_per_cu")) return &o.last_resident_per_cu;
+    if (!std::strcmp(name, "last_waves")) return &o.last_waves;
+    if (!std::strcmp(name, "last_rows")) return &o.last_rows;
+    if (!std::strcmp(name, "last_form")) return &o.last_form;
     return nullptr;
 }
 
@@ -254,7 +257,9 @@ int ks_set_option(const char *name, long long value) {
     long long *slot = option_slot(name);
     if (!slot) return KS_ERR_INVALID_ARG;
     Options &o = options();
-    if (slot == &o.last_grid || slot == &o.last_resident_per_cu) return KS_ERR_INVALID_ARG;   // read-only
+    if (slot == &o.last_grid || slot == &o.last_resident_per_cu || slot == &o.last_waves || slot == &o.last_rows ||
+        slot == &o.last_form)
+        return KS_ERR_INVALID_ARG;   // read-only
     if (slot == &o.waves && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.rows && !(value == 0 || value == 4 || value == 8 || value == 9 || value == 12 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;

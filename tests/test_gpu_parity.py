@@ -53,12 +53,16 @@ def default_shape(ks, dtype, n=None):
         if n * eb <= ((16 << 20) if eb == 4 else (32 << 20)):
             return MID_SHAPE
     waves, rows = (16, 8) if dtype in ("i64", "u64", "f64") else (16, 9)
-    # a little more than one round of 256 tiles: 12 or 16 rows if that makes it one round (the affine
-    # type's registers allow neither)
-    if n is not None and eb < 16 and dtype != "affine_f32" and -(-n // tile_elems(ks, dtype, waves, rows)) > 256:
-        for more in (12, 16):
-            if -(-n // tile_elems(ks, dtype, waves, more)) <= 256:
-                return waves, more
+    # up to three rounds of 256 default tiles: the rows that minimise rounds x rows, the default on a
+    # tie (16 rows only for one round; the affine type's registers allow neither 12 nor 16 rows)
+    if n is not None and eb < 16 and dtype != "affine_f32":
+        rounds = lambda r: -(-(-(-n // tile_elems(ks, dtype, waves, r))) // 256)
+        if 1 < rounds(rows) <= 3:
+            best, cost = rows, rounds(rows) * rows
+            for cand in ([9] if rows == 8 else []) + [12] + ([16] if rounds(16) == 1 else []):
+                if rounds(cand) * cand < cost:
+                    best, cost = cand, rounds(cand) * cand
+            rows = best
     return waves, rows
 
 
@@ -136,15 +140,22 @@ def test_default_shape_switches_with_the_input_size(ks, dtype, op):
 
 
 @pytest.mark.parametrize("dtype,op,tiles9,rows", [("i32", "sum", 300, 12), ("f32", "sum", 290, 12),
-                                                  ("u64", "sum", 400, 16), ("affine_f32", "affine_compose", 300, 9)])
-def test_a_little_more_than_one_round_runs_as_one_round(ks, dtype, op, tiles9, rows):
-    # inputs of a little more than 256 default tiles take 12 or 16 rows per thread so that one round
-    # of the 256 compute units covers them (types whose registers do not allow it keep 9 rows)
+                                                  ("f32", "sum", 400, 16), ("f32", "sum", 500, 9),
+                                                  ("f32", "sum", 560, 12), ("f32", "sum", 700, 9),
+                                                  ("u64", "sum", 300, 12), ("u64", "sum", 400, 8),
+                                                  ("u64", "sum", 470, 9), ("f64", "sum", 470, 9),
+                                                  ("u64", "sum", 900, 8), ("affine_f32", "affine_compose", 300, 9)])
+def test_inputs_of_a_few_rounds_take_the_rows_that_fill_their_rounds(ks, dtype, op, tiles9, rows):
+    # up to three rounds of 256 default tiles the library takes the rows per thread that minimise
+    # rounds x rows (12 or 16 rows to fit one round, 12 instead of 9 or 9 instead of 8 to save a
+    # round); types whose registers do not allow more rows, and everything longer, keep the default
     n = tiles9 * tile_elems(ks, dtype, 16, 9) - 5
     x = random_input(dtype, op, n, seed=91)
-    say(f"[case] pair=({dtype},{op}) n={n}: {tiles9} default tiles, expecting {rows} rows")
+    say(f"[case] pair=({dtype},{op}) n={n}: {tiles9} tiles of 9 rows, expecting {rows} rows")
+    assert default_shape(ks, dtype, n) == (16, rows)
     got = run(ks, dtype, op, x, api="plain")
     tiles = -(-n // tile_elems(ks, dtype, 16, rows))
+    assert ks.ks_get_option("last_rows") == rows and ks.ks_get_option("last_waves") == 16
     assert ks.ks_get_option("last_grid") == min(tiles, 256), (tiles, ks.ks_get_option("last_grid"))
     assert_matches(dtype, op, got, reference(dtype, op, x, True), f"({dtype},{op}) n={n}")
 
