@@ -87,9 +87,14 @@ struct PairDefaults {
     // Between the two, 8 waves x 8 rows (64 KiB tiles, no next tile to prefetch): up to 34 MiB the
     // large tile leaves compute units without work (16 MiB are 124 tiles of 135 KiB).  Against the
     // large shape, TB/s: int32 sum 16 MiB 3.48 / 3.18, uint64 sum 16 MiB 3.35 / 3.07, 32 MiB 5.11 / 4.75;
-    // from 32 MiB (4-byte) and 64 MiB (8-byte elements) on the large shape is ahead.
+    // from 32 MiB (4-byte) and 64 MiB (8-byte elements) on the large shape is ahead.  That was the
+    // large shape before its pauses; with them 8-byte scalars are ahead in 16 waves x 8 rows from 16 MiB
+    // on (uint64 sum, us per call, 8 x 8 / 16 x 8: 20 MiB 10.8 / 10.0, 24 MiB 12.3 / 10.4, 28 MiB 12.8 / 11.6).
+    // Not for pairs that accumulate wider than they store (the affine type, float32 in, float64
+    // accumulators): its common loop is slow for them (8 x 8 / blocked 16 x 9, us per call: 14 MiB
+    // 11.1 / 10.8, 20 MiB 18.0 / 11.5, 32 MiB 21.1 / 14.5).
     static constexpr Shape mid_shape() { return Shape{8, 8, false, kFormCommon}; }
-    static constexpr size_t kMidInputBytes = sizeof(T) == 4 ? (size_t)16 << 20 : (size_t)32 << 20;
+    static constexpr size_t kMidInputBytes = sizeof(A) == sizeof(T) ? (size_t)16 << 20 : kSmallInputBytes;
     // 16-byte elements: only up to 1 MiB a small tile wins, 4 waves x 4 rows (kernel time against
     // the large blocked shape: quaternions 64 KiB 5.0 / 5.9 us, 1 MiB 6.6 / 7.9; arg-max struct
     // 1 MiB 6.8 / 7.4; at 4 MiB the blocked shape is ahead, 7.7 / 8.8).
@@ -124,13 +129,14 @@ struct Pair {
     // 20.1 / 18.3 (16 rows, one round), 72 MiB 29.2 / 26.3 (12 rows, two rounds instead of three), 80 MiB
     // 32.0 / 28.9; uint64 sum 40 MiB 18.0 / 16.1 (12 rows), 64 MiB 26.9 / 23.2 (9 rows, two rounds instead
     // of three); 16 rows in one round against 8 rows in two is a tie by the product and measures
-    // worse (uint64 48 MiB 22.3 against 18.6), hence the tie rule.  Elements of 16 bytes keep their
-    // blocked shape.
+    // worse (uint64 48 MiB 22.3 against 18.6), hence the tie rule.  The same product sends 4-byte
+    // inputs of less than one round of 8-row tiles to 8 rows (float32 sum 24 MiB 11.3 / 10.6, 28 MiB
+    // 12.2 / 11.4).  Elements of 16 bytes keep their blocked shape.
     static Shape few_rounds_shape(size_t n, int cus, Shape s) {
         if (sizeof(T) >= 16 || s.waves != 16 || s.rows > 9) return s;
         auto rounds = [&](int rows) { return ceil_div(ceil_div(n, shape_tile_elems(16, rows)), (size_t)cus); };
         const size_t r0 = rounds(s.rows);
-        if (r0 <= 1 || r0 > 3) return s;
+        if (r0 > 3) return s;
         Shape best = s;
         size_t best_cost = r0 * (size_t)s.rows;
         auto consider = [&](Shape c) {
@@ -149,6 +155,9 @@ struct Pair {
             consider(Shape{16, 12, false, form});
         if (variant_fits<T, A, 16, 16, false, kFormSeparate>() && rounds(16) == 1)
             consider(Shape{16, 16, false, kFormSeparate});
+        // less than one round: smaller tiles keep more compute units busy
+        if (s.rows == 9 && sizeof(A) == 4 && variant_fits<T, A, 16, 8, true, kFormSeparate>())
+            consider(Shape{16, 8, true, kFormSeparate});
         return best;
     }
 

@@ -39,7 +39,7 @@ SMALL_INPUT_BYTES = 8 << 20   # up to here the default look-back shape of 4- and
 SMALL_SHAPE = (4, 8)
 
 
-MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (4-byte) / 32 MiB (8-byte elements)
+MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (not for the affine type)
 
 
 def default_shape(ks, dtype, n=None):
@@ -50,16 +50,16 @@ def default_shape(ks, dtype, n=None):
     if n is not None and eb < 16:
         if n * eb <= SMALL_INPUT_BYTES:
             return SMALL_SHAPE
-        if n * eb <= ((16 << 20) if eb == 4 else (32 << 20)):
+        if n * eb <= (16 << 20) and dtype != "affine_f32":
             return MID_SHAPE
     waves, rows = (16, 8) if dtype in ("i64", "u64", "f64") else (16, 9)
     # up to three rounds of 256 default tiles: the rows that minimise rounds x rows, the default on a
     # tie (16 rows only for one round; the affine type's registers allow neither 12 nor 16 rows)
     if n is not None and eb < 16 and dtype != "affine_f32":
         rounds = lambda r: -(-(-(-n // tile_elems(ks, dtype, waves, r))) // 256)
-        if 1 < rounds(rows) <= 3:
+        if rounds(rows) <= 3:
             best, cost = rows, rounds(rows) * rows
-            for cand in ([9] if rows == 8 else []) + [12] + ([16] if rounds(16) == 1 else []):
+            for cand in ([9] if rows == 8 else []) + [12] + ([16] if rounds(16) == 1 else []) + ([8] if eb == 4 else []):
                 if rounds(cand) * cand < cost:
                     best, cost = cand, rounds(cand) * cand
             rows = best
@@ -126,7 +126,7 @@ def test_library_owned_workspace_back_to_back(ks, dtype, op):
 def test_default_shape_switches_with_the_input_size(ks, dtype, op):
     # at and just above the size where the default look-back shape changes from small to large tiles
     at = SMALL_INPUT_BYTES // ks.ks_elem_bytes(dtype)
-    mid = ((16 << 20) if ks.ks_elem_bytes(dtype) == 4 else (32 << 20)) // ks.ks_elem_bytes(dtype)
+    mid = (16 << 20) // ks.ks_elem_bytes(dtype)
     tiny16 = (1 << 20) // 16
     for n in (tiny16, tiny16 + 1, at - 1, at, at + 1, mid, mid + 1):
         x = random_input(dtype, op, n, seed=77)
@@ -140,6 +140,7 @@ def test_default_shape_switches_with_the_input_size(ks, dtype, op):
 
 
 @pytest.mark.parametrize("dtype,op,tiles9,rows", [("i32", "sum", 300, 12), ("f32", "sum", 290, 12),
+                                                  ("f32", "sum", 200, 8), ("f32", "sum", 250, 9),
                                                   ("f32", "sum", 400, 16), ("f32", "sum", 500, 9),
                                                   ("f32", "sum", 560, 12), ("f32", "sum", 700, 9),
                                                   ("u64", "sum", 300, 12), ("u64", "sum", 400, 8),
