@@ -140,8 +140,10 @@ def test_options_are_validated(ks):
     ks.ks_set_option("waves", 0)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("waves", 2)
-    with pytest.raises(ks.KsError):
-        ks.ks_set_option("last_grid", 1)
+    for read_only in ("last_grid", "last_resident_per_cu", "last_waves", "last_rows", "last_form"):
+        assert ks.ks_get_option(read_only) >= 0
+        with pytest.raises(ks.KsError):
+            ks.ks_set_option(read_only, 1)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("no_such_option", 1)
     with pytest.raises(ks.KsError):
