@@ -134,6 +134,22 @@ def main() -> int:
     log(f"scan: {wall_ms:.4f} ms/step wall, {event_ms:.4f} ms/step by HIP events -> {gbs_event:.1f} GB/s "
         f"({100 * gbs_event / HBM_PEAK_GBS:.1f}% of {HBM_PEAK_GBS:.0f} GB/s)")
 
+    # ---- the paper's protocol (Sec. VII: one launch per event pair, mean +- std; launch overhead
+    #      included), outside the timed region
+    singles = []
+    for _ in range(50):
+        s0 = torch.cuda.Event(enable_timing=True)
+        s1 = torch.cuda.Event(enable_timing=True)
+        s0.record()
+        step()
+        s1.record()
+        torch.cuda.synchronize()
+        singles.append(s0.elapsed_time(s1) * 1e3)
+    ks.ks_scan_check()
+    launch_stats = {"launches": len(singles), "mean_us": float(np.mean(singles)), "std_us": float(np.std(singles)),
+                    "min_us": float(np.min(singles)), "max_us": float(np.max(singles))}
+    log(f"single launches: {launch_stats['mean_us']:.1f} +- {launch_stats['std_us']:.1f} us (min {launch_stats['min_us']:.1f})")
+
     # ---- copy kernel on the same bytes: the practical ceiling (context, not the metric)
     for _ in range(5):
         ks.ks_copy(d_in, d_out)
@@ -231,6 +247,7 @@ def main() -> int:
         "elements_per_s": n / (wall_ms * 1e-3),
         "pct_of_hbm_peak": 100 * gbs_wall / HBM_PEAK_GBS,
         "copy_ceiling_gbs": copy_gbs,
+        "single_launch_us": launch_stats,
         "roofline": {"bound": "hbm", "achieved": gbs_event, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs_event / HBM_PEAK_GBS,
                      "traffic": measured_traffic(args.workload, n)
