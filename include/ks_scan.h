@@ -188,7 +188,10 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *                  registers, for wide element types), 2 = as 1, and every lane scans
  *                  consecutive elements after an exchange through LDS (rows 8 or 9),
  *                  3 = the common loop with two pauses that pay on long inputs (9 rows
- *                  with prefetch only); -1 = the default for the pair and the input size
+ *                  with prefetch only), 4 and 5 = forms 0 and 3 with tiles that start on
+ *                  128-byte lines of the output, which the library takes by itself for
+ *                  output pointers that are not so aligned (forms 1 and 2 always do
+ *                  this); -1 = the default for the pair, the input size and the pointers
  *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
  *                  workgroup per tile, which is only deadlock-free if the hardware
  *                  starts workgroups in index order (experimental; waits stay bounded)

@@ -17,7 +17,8 @@ struct Options {
     long long rows = 0;           // 0 = default for the type, else 4, 8, 9, 12 or 16
     long long prefetch = -1;      // -1 = default, 0 / 1 forced
     long long form = -1;          // -1 = default, else 0 common loop, 1 separate loops, 2 separate + blocked,
-                                  // 3 common loop with pauses (1-3: 16 waves only; 3: 9 rows with prefetch only)
+                                  // 3 common loop with pauses, 4 / 5 = 0 / 3 with tiles on the output's
+                                  // 128-byte lines (1-5: 16 waves only; 3-5: 9 rows with prefetch only)
     long long grid_mode = 0;      // 0 = persistent resident grid, 1 = one workgroup per tile (experimental)
     long long last_grid = 0;      // read-only: workgroups of the most recent look-back launch
     long long last_resident_per_cu = 0;   // read-only: verified resident workgroups per CU of that kernel variant

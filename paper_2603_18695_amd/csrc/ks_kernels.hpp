@@ -299,6 +299,31 @@ constexpr int kCommonPrefetchHold = 60;
 constexpr int kCommonPollDelay = 44;
 constexpr uint32_t kCommonPacedRounds = 12;   // the host takes the paced common loop from this many rounds on
 
+// Output pointers that are not aligned to a 128-byte line (element-aligned views, paper
+// Sec. IV-D).  The buffer accesses work at any alignment, but with tiles that start in the middle
+// of a line every 1 KiB row of a wave straddles nine lines instead of covering eight, and the
+// lines at the seams are written in two parts (float32 sum 2^28, both pointers moved by 4 bytes:
+// 6.08 TB/s against 6.41).  So all tiles move down by `shift` elements: tile 0 keeps only the
+// `lead` elements in front of the output's first line boundary and every other tile starts on a
+// boundary (6.41 again; with different offsets of input and output the loads stay unaligned,
+// 6.26).  Host and kernel derive lead and shift from the output pointer alone.
+template <class IO>
+__host__ __device__ __forceinline__ uint32_t lead_elements(const IO *out) {
+    return (uint32_t)((128u - (uint32_t)((uintptr_t)out & 127u)) & 127u) / (uint32_t)sizeof(IO);
+}
+template <class IO>
+__host__ __device__ __forceinline__ size_t tile_shift(const IO *out, size_t tile_elems) {
+    const uint32_t lead = lead_elements(out);
+    return lead ? tile_elems - lead : 0;
+}
+// first element and element count of tile t under a shift
+__device__ __forceinline__ size_t shifted_first(uint32_t t, size_t shift, size_t tile_elems) {
+    return t ? (size_t)t * tile_elems - shift : 0;
+}
+__device__ __forceinline__ size_t shifted_elems(uint32_t t, size_t shift, size_t tile_elems) {
+    return t ? tile_elems : tile_elems - shift;
+}
+
 // Arguments of the look-back kernel that its loops pass around.
 struct LookbackArgs {
     size_t n;
@@ -380,12 +405,13 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
     Op op;
+    const size_t shift = tile_shift(out, TILE);   // tiles start on 128-byte lines of the output
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE), lane_bytes,
-                             blockIdx.x + 1 == a.ntiles, cur);
+    load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE)), lane_bytes,
+                             blockIdx.x + 1 == a.ntiles || (blockIdx.x == 0 && shift != 0), cur);
     for (uint32_t loop_tile = blockIdx.x;;) {
         // The tile index is the same in every lane; saying so keeps it, and the buffer resources
         // derived from it, in scalar registers.
@@ -409,21 +435,21 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
         TileWindow wnext;
         if (PREFETCH && next < a.ntiles) {
             __builtin_amdgcn_s_sleep(kPrefetchHold);
-            wnext = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
+            wnext = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
             load_raw<ROWS, true>(wnext, lane_bytes, nxt);
         }
         if constexpr (Op::commutative) (void)scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
         const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
-        apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, cur,
+        apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, cur,
                                                 prefix, op);
         if (next >= a.ntiles) return;
         loop_tile = next;
         if (PREFETCH) {
             unpack_items<IO, ROWS, Op, true>(nxt, lane_bytes, wnext.valid_bytes, next + 1 == a.ntiles, cur);
         } else {
-            load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)next * TILE, TILE), lane_bytes,
+            load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE), lane_bytes,
                                      next + 1 == a.ntiles, cur);
         }
     }
@@ -441,6 +467,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
     Op op;
+    const size_t shift = tile_shift(out, TILE);   // see data_wave_loop
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);   // striped view: global loads and stores
@@ -453,7 +480,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
-        const TileWindow w = tile_window<IO>(in, a.n, (size_t)blockIdx.x * TILE, TILE);
+        const TileWindow w = tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE));
         load_raw<ROWS, true>(w, lane_bytes, raw);
         valid_bytes = w.valid_bytes;
     }
@@ -462,13 +489,13 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         ThreadItems<A, ROWS, S::G> cur;
         A lane_before;
         striped_to_blocked<ROWS>(region, raw);
-        unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles, cur);
+        unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles || (tile == 0 && shift != 0), cur);
         const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
         if (PREFETCH && tile + gridDim.x < a.ntiles) {
             __builtin_amdgcn_s_sleep(kPrefetchHold);
-            const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE, TILE);
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE - shift, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
             valid_bytes = w.valid_bytes;
         }
@@ -479,11 +506,11 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         RawItems<ROWS> result;
         apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
         blocked_to_striped<ROWS>(region, result);
-        store_raw<ROWS, true>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, result);
+        store_raw<ROWS, true>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, result);
         if (next >= a.ntiles) return;
         loop_tile = next;
         if (!PREFETCH) {
-            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
             valid_bytes = w.valid_bytes;
         }
@@ -492,7 +519,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
 
 // One loop for all waves: wave 0 looks back, and holds data as well unless the
 // shape has a dedicated look-back wave.
-template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool PACED>
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool PACED, bool ALIGN_OUT>
 __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n,
                                                  uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
                                                  uint32_t spin_limit, uint32_t *abort_flag) {
@@ -506,6 +533,17 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
     __shared__ typename WordsOf<A>::type s_prefix;
     __shared__ uint32_t s_ok;
     Op op;
+    // ALIGN_OUT: tiles start on 128-byte lines of the output (see tile_shift).  A variant of its own:
+    // the shift in this loop costs the float32 kernel 1 % also when it is zero.
+    const size_t shift = ALIGN_OUT ? tile_shift(out, TILE) : 0;
+    auto first_of = [&](uint32_t t) -> size_t {
+        if constexpr (ALIGN_OUT) return shifted_first(t, shift, TILE);
+        else return (size_t)t * TILE;
+    };
+    auto elems_of = [&](uint32_t t) -> size_t {
+        if constexpr (ALIGN_OUT) return shifted_elems(t, shift, TILE);
+        else return TILE;
+    };
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const bool data_wave = !DEDICATED || wave != 0;
@@ -521,8 +559,8 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
     constexpr bool paced = DEDICATED && PACED;
     Items cur;
     if (data_wave) {
-        const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
-        load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles, cur);
+        const TileWindow w = tile_window<IO>(in, n, first_of(tile), elems_of(tile));
+        load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles || (ALIGN_OUT && tile == 0 && shift != 0), cur);
     }
     for (;;) {
         WaveScan<A, ROWS> ws;
@@ -543,7 +581,7 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
         TileWindow wnext;
         if (data_wave && PREFETCH && next < ntiles) {
             if (paced) __builtin_amdgcn_s_sleep(kCommonPrefetchHold);
-            wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
+            wnext = tile_window<IO>(in, n, first_of(next), TILE);
             load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
@@ -565,7 +603,7 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
         if (data_wave) {
             const A prefix = op(from_words<A>(s_prefix), wave_carry);
             finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
-            apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE),
+            apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, first_of(tile), elems_of(tile)),
                                                            lane_bytes, cur, prefix, op);
         }
         if (next >= ntiles) break;
@@ -574,7 +612,7 @@ __device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n
             if (PREFETCH) {
                 unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
             } else {
-                const TileWindow w = tile_window<IO>(in, n, (size_t)tile * TILE, TILE);
+                const TileWindow w = tile_window<IO>(in, n, first_of(tile), elems_of(tile));
                 load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles, cur);
             }
         }
@@ -605,6 +643,17 @@ constexpr int kFormCommon = 0;     // one loop for all waves
 constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in loops of their own, striped items
 constexpr int kFormBlocked = 2;    // the same with the blocked arrangement (LDS exchange)
 constexpr int kFormCommonPaced = 3;   // the common loop of the 16-wave shape with the two pauses (long inputs)
+constexpr int kFormCommonAligned = 4;        // forms 0 and 3 with tiles aligned to the output's 128-byte lines:
+constexpr int kFormCommonPacedAligned = 5;   // taken by the host for output pointers that are not (16 x 9 only)
+constexpr int kFormCount = 6;
+constexpr bool common_form(int form) {
+    return form == kFormCommon || form == kFormCommonPaced || form == kFormCommonAligned || form == kFormCommonPacedAligned;
+}
+// whether the kernel of this shape and form moves its tiles to the output's line boundaries
+constexpr bool aligns_output(int waves, int form) {
+    return dedicated_lookback_wave(waves) &&
+           (form == kFormSeparate || form == kFormBlocked || form == kFormCommonAligned || form == kFormCommonPacedAligned);
+}
 
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
 __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out,
@@ -619,7 +668,7 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
     using A = typename Op::acc;
     if (blockIdx.x >= ntiles) return;
     if constexpr (dedicated_lookback_wave(WAVES)) stagger_start(ntiles);
-    if constexpr (dedicated_lookback_wave(WAVES) && FORM != kFormCommon && FORM != kFormCommonPaced) {
+    if constexpr (dedicated_lookback_wave(WAVES) && !common_form(FORM)) {
         __shared__ TileExchange<A, WAVES> x;
         const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
         if constexpr (FORM == kFormBlocked) {
@@ -635,7 +684,8 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
                 data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
         }
     } else {
-        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM == kFormCommonPaced>(
+        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH,
+                         FORM == kFormCommonPaced || FORM == kFormCommonPacedAligned, aligns_output(WAVES, FORM)>(
             in, out, n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag);
     }
 }

@@ -23,7 +23,7 @@ inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 struct Shape {
     int waves, rows;
     bool prefetch;
-    int form;     // kFormCommon / kFormSeparate / kFormBlocked / kFormCommonPaced (the last three: 16 waves only)
+    int form;     // kFormCommon ... kFormCommonPacedAligned (all but kFormCommon: 16 waves only)
 };
 
 // Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
@@ -33,7 +33,9 @@ struct Shape {
 // correct); the defaults below were checked not to.
 template <class T, class A, int WAVES, int ROWS, bool PREFETCH, int FORM>
 constexpr bool variant_fits() {
-    if (FORM == kFormCommonPaced)   // compiled in the default shape only: it exists for long inputs
+    // the paced common loop (long inputs) and the common loops with output-aligned tiles are compiled
+    // in the default shape only
+    if (FORM == kFormCommonPaced || FORM == kFormCommonAligned || FORM == kFormCommonPacedAligned)
         return WAVES == 16 && ROWS == 9 && PREFETCH && variant_fits<T, A, WAVES, ROWS, PREFETCH, kFormCommon>();
     constexpr bool SPLIT = FORM != kFormCommon;
     if (SPLIT && !dedicated_lookback_wave(WAVES)) return false;   // nothing to separate
@@ -169,7 +171,17 @@ struct Pair {
         return s;
     }
 
-    static Shape lookback_shape(size_t n, int cus) {
+    // The common loop of the default shape has variants of its own for output pointers that are not
+    // aligned to a 128-byte line (the separate loops handle them in place).
+    static Shape output_aligned_shape(const void *out, Shape s) {
+        if (s.waves == 16 && s.rows == 9 && s.prefetch && lead_elements(static_cast<const T *>(out)) != 0) {
+            if (s.form == kFormCommon) s.form = kFormCommonAligned;
+            if (s.form == kFormCommonPaced) s.form = kFormCommonPacedAligned;
+        }
+        return s;
+    }
+
+    static Shape lookback_shape(size_t n, int cus, const void *out) {
         Shape s = paced_shape(n, cus, PairDefaults<T, Op>::shape_for(n));
         if (MapOf<Op>::mapped) return s;
         s = few_rounds_shape(n, cus, s);
@@ -177,7 +189,10 @@ struct Pair {
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
         if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
         if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
-        if (o.form >= 0) s.form = (int)o.form;
+        if (o.form >= 0)
+            s.form = (int)o.form;
+        else
+            s = output_aligned_shape(out, s);
         if (!dedicated_lookback_wave(s.waves)) s.form = kFormCommon;
         return s;
     }
@@ -270,7 +285,11 @@ struct Pair {
         } else {
             auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM>;
             constexpr int kThreads = WAVES * kWave;
-            const size_t tiles = ceil_div(c.n, shape_tile_elems(WAVES, ROWS));
+            // kernels that move their tiles to the output's line boundaries have tile 0 cut short
+            const size_t shift = aligns_output(WAVES, FORM)
+                                     ? tile_shift(static_cast<const T *>(c.out), shape_tile_elems(WAVES, ROWS))
+                                     : 0;
+            const size_t tiles = ceil_div(c.n + shift, shape_tile_elems(WAVES, ROWS));
             const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
             if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
             // resident workgroups per compute unit of this variant, per device
@@ -312,6 +331,9 @@ struct Pair {
             if (s.form == kFormSeparate) return lookback_flags_dispatch<WAVES, ROWS, kFormSeparate>(c, s.prefetch);
             if (s.form == kFormBlocked) return lookback_flags_dispatch<WAVES, ROWS, kFormBlocked>(c, s.prefetch);
             if (s.form == kFormCommonPaced) return lookback_flags_dispatch<WAVES, ROWS, kFormCommonPaced>(c, s.prefetch);
+            if (s.form == kFormCommonAligned) return lookback_flags_dispatch<WAVES, ROWS, kFormCommonAligned>(c, s.prefetch);
+            if (s.form == kFormCommonPacedAligned)
+                return lookback_flags_dispatch<WAVES, ROWS, kFormCommonPacedAligned>(c, s.prefetch);
         }
         return lookback_flags_dispatch<WAVES, ROWS, kFormCommon>(c, s.prefetch);
     }
@@ -347,7 +369,7 @@ struct Pair {
             }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
         }
-        const Shape s = lookback_shape(c.n, c.dev->cus);
+        const Shape s = lookback_shape(c.n, c.dev->cus, c.out);
         switch (s.waves) {
             case 4: return lookback_rows_dispatch<4>(c, s);
             case 8: return lookback_rows_dispatch<8>(c, s);

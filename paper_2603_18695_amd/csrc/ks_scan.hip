@@ -266,7 +266,7 @@ int ks_set_option(const char *name, long long value) {
     if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
     if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;
     if (slot == &o.prefetch && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
-    if (slot == &o.form && !(value >= -1 && value <= 3)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.form && !(value >= -1 && value < kFormCount)) return KS_ERR_INVALID_ARG;
     *slot = value;
     return KS_OK;
 }

@@ -152,7 +152,7 @@ def test_options_are_validated(ks):
     assert ks.ks_get_option("form") == 2
     ks.ks_set_option("form", -1)
     with pytest.raises(ks.KsError):
-        ks.ks_set_option("form", 4)
+        ks.ks_set_option("form", 6)
     assert ks.ks_get_option("no_such_option") == -1
 
 

@@ -234,7 +234,41 @@ def test_in_place_and_misaligned_pointers(ks):
             assert_matches(dtype, op, to_host(d_out, x.dtype), reference(dtype, op, x[1:], True), f"misaligned {algo}")
 
 
-@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2), (16, 3)])
+@pytest.mark.parametrize("dtype,op", [("f32", "sum"), ("i32", "max"), ("u64", "sum"), ("affine_f32", "affine_compose"),
+                                      ("argmax_i32_cnt64", "argmax_count")])
+def test_output_pointers_off_the_128_byte_lines(ks, dtype, op):
+    # the 16-wave kernels move their tiles to the output's line boundaries (tile 0 is cut short);
+    # sizes of a few rounds (12 rows), several rounds, and enough rounds for the paced common loop
+    tile9 = tile_elems(ks, dtype, 16, 9)
+    for tiles, offsets in ((290, [(1, 1)]), (700, [(1, 1), (0, 3), (5, 2)]), (3300, [(7, 7), (2, 0)])):
+        n = tiles * tile9 + 11
+        x = random_input(dtype, op, n + 8, seed=tiles)
+        d_all = to_device(x)
+        d_out_all = torch.zeros_like(d_all)
+        for off_in, off_out in offsets:
+            for inclusive in (True, False):
+                say(f"[case] off-line pointers ({dtype},{op}) n={n} in+{off_in} out+{off_out} elements incl={inclusive}")
+                d_in, d_out = d_all[off_in:off_in + n], d_out_all[off_out:off_out + n]
+                d_out_all.fill_(0x3C)
+                ks.ks_scan(d_in, d_out, dtype=dtype, op=op, inclusive=inclusive)
+                ks.ks_scan_check()
+                if off_out % (128 // ks.ks_elem_bytes(dtype)) and dtype == "f32":
+                    assert ks.ks_get_option("last_form") in ((1, 4) if tiles < 3072 else (5,))
+                got = to_host(d_out, x.dtype)
+                assert_matches(dtype, op, got, reference(dtype, op, x[off_in:off_in + n], inclusive),
+                               f"off-line ({dtype},{op}) n={n} +{off_in}/+{off_out}")
+                # nothing outside the output view is written
+                assert bool((d_out_all[:off_out] == 0x3C).all()) and bool((d_out_all[off_out + n:] == 0x3C).all())
+    # in place, off the line
+    n = 700 * tile9 + 5
+    x = random_input(dtype, op, n + 3, seed=5)
+    d_all = to_device(x)
+    ks.ks_scan(d_all[3:], d_all[3:], dtype=dtype, op=op)
+    ks.ks_scan_check()
+    assert_matches(dtype, op, to_host(d_all[3:], x.dtype), reference(dtype, op, x[3:], True), "in place, off the line")
+
+
+@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2), (16, 3), (16, 4), (16, 5)])
 @pytest.mark.parametrize("rows", [4, 8, 9, 12, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
 def test_lookback_variants(ks, waves, form, rows, prefetch):
