@@ -303,10 +303,10 @@ constexpr uint32_t kCommonPacedRounds = 12;   // the host takes the paced common
 // Sec. IV-D).  The buffer accesses work at any alignment, but with tiles that start in the middle
 // of a line every 1 KiB row of a wave straddles nine lines instead of covering eight, and the
 // lines at the seams are written in two parts (float32 sum 2^28, both pointers moved by 4 bytes:
-// 6.08 TB/s against 6.41).  So all tiles move down by `shift` elements: tile 0 keeps only the
+// 6.07 TB/s against 6.41).  So all tiles move down by `shift` elements: tile 0 keeps only the
 // `lead` elements in front of the output's first line boundary and every other tile starts on a
-// boundary (6.41 again; with different offsets of input and output the loads stay unaligned,
-// 6.26).  Host and kernel derive lead and shift from the output pointer alone.
+// boundary (6.42 against 6.39 aligned in that run; with different offsets of input and output the
+// loads stay off the lines, 6.29).  Host and kernel derive lead and shift from the output pointer alone.
 template <class IO>
 __host__ __device__ __forceinline__ uint32_t lead_elements(const IO *out) {
     return (uint32_t)((128u - (uint32_t)((uintptr_t)out & 127u)) & 127u) / (uint32_t)sizeof(IO);
