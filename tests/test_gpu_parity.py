@@ -434,6 +434,31 @@ def test_strided_views(ks, dtype, op):
                 assert bool((d_in[:, 1:, :] == 0x5A5A5A5A).all())
 
 
+def test_random_pairs_sizes_offsets(ks):
+    # seeded sweep over every pair: sizes log-uniform up to 2.5e8 bytes (a third of them above 2e6
+    # elements), pointers moved by up to 39 elements, inclusive / exclusive, some in place
+    rng = np.random.default_rng(20261127)
+    for case in range(240):
+        dtype, op = ALL_PAIRS[int(rng.integers(len(ALL_PAIRS)))]
+        eb = ks.ks_elem_bytes(dtype)
+        lo = np.log(2e6) if case % 3 == 0 else 0.0
+        n = int(np.exp(rng.uniform(lo, np.log(2.5e8 / eb))))
+        off_in, off_out = (int(rng.integers(0, 40)), int(rng.integers(0, 40))) if rng.random() < 0.6 else (0, 0)
+        inclusive = bool(rng.integers(2))
+        in_place = rng.random() < 0.2
+        if in_place:
+            off_out = off_in
+        x = random_input(dtype, op, n + 40, seed=int(rng.integers(1 << 30)))
+        d_all = to_device(x)
+        d_out_all = d_all if in_place else torch.zeros_like(d_all)
+        say(f"[case {case}] ({dtype},{op}) n={n} in+{off_in} out+{off_out} incl={inclusive} in_place={in_place}")
+        ks.ks_scan(d_all[off_in:off_in + n], d_out_all[off_out:off_out + n], dtype=dtype, op=op, inclusive=inclusive)
+        ks.ks_scan_check()
+        got = to_host(d_out_all[off_out:off_out + n], x.dtype)
+        assert_matches(dtype, op, got, reference(dtype, op, x[off_in:off_in + n], inclusive), f"case {case}")
+        del d_all, d_out_all
+
+
 def test_two_streams_at_once(ks):
     # calls on different streams use different workspaces and may overlap on the device; each stream's
     # results must be those of its own inputs
