@@ -287,8 +287,18 @@ struct TileExchange {
 // exceed the delay by 12-16 for the poll to be issued first.  Releasing the request by a flag in LDS
 // as soon as the aggregate is out, or when the look-back is done (bounded), measured 1-5 % below
 // the fixed pauses.  Both apply only while the workgroup has a next tile to request.
+// With the staggered start (below) accumulators of 16 bytes gain from longer pauses, 8-byte ones
+// do not (delay / hold 24/40, 32/48, 40/56, 48/64 at 2 GiB of traffic: arg-max struct 6.25 / 6.30 / 6.32 /
+// 6.33, quaternions 6.25 / 6.29 / 6.32 / 6.33, 2x2 matrices 6.35 / 6.38 / 6.40 / 6.40, affine 6.20 / 6.22 / 6.22 /
+// 6.24, uint64 sum 6.43 / 6.43 / 6.43 / -; at 256 MiB of traffic 48/64 starts to lose).
 constexpr int kPrefetchHold = 40;
 constexpr int kPollDelay = 24;
+constexpr int kPrefetchHoldWide = 56;   // accumulators of 16 bytes and more
+constexpr int kPollDelayWide = 40;
+template <class A>
+constexpr int prefetch_hold() { return sizeof(A) >= 16 ? kPrefetchHoldWide : kPrefetchHold; }
+template <class A>
+constexpr int poll_delay() { return sizeof(A) >= 16 ? kPollDelayWide : kPollDelay; }
 // The same two in the common loop of the 16-wave shape (float32 sum 2^28, before the staggered
 // start: none 6.22, 24/40 6.29, 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone
 // changes nothing there).
@@ -384,7 +394,7 @@ __device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileEx
         const A before = wave_shift_up(upto, Op::identity());
         if (lane < WAVES - 1) x.carry[lane + 1] = to_words(before);
         publish_aggregate<A, Op>(a, tile, aggregate);
-        if (PREFETCH && tile + gridDim.x < a.ntiles) __builtin_amdgcn_s_sleep(kPollDelay);   // while the data waves hold
+        if (PREFETCH && tile + gridDim.x < a.ntiles) __builtin_amdgcn_s_sleep(poll_delay<A>());   // while the data waves hold
         resolve_prefix<A, Op, WAVES>(a, tile, m, aggregate, x);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
@@ -434,7 +444,7 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
         RawItems<ROWS> nxt;
         TileWindow wnext;
         if (PREFETCH && next < a.ntiles) {
-            __builtin_amdgcn_s_sleep(kPrefetchHold);
+            __builtin_amdgcn_s_sleep(prefetch_hold<A>());
             wnext = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
             load_raw<ROWS, true>(wnext, lane_bytes, nxt);
         }
@@ -494,7 +504,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
         if (PREFETCH && tile + gridDim.x < a.ntiles) {
-            __builtin_amdgcn_s_sleep(kPrefetchHold);
+            __builtin_amdgcn_s_sleep(prefetch_hold<A>());
             const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE - shift, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
             valid_bytes = w.valid_bytes;
