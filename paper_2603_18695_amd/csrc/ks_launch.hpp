@@ -73,11 +73,14 @@ template <class T, class Op>
 struct PairDefaults {
     using A = typename Op::acc;
     static constexpr bool kFloat32Sum = std::is_same<typename MapOf<Op>::unmapped, SumOp<float>>::value;
+    static constexpr bool kSum = std::is_same<typename MapOf<Op>::unmapped, SumOp<T>>::value;
     static constexpr Shape shape() {
         if (sizeof(A) == 4) return Shape{16, 9, true, kFloat32Sum ? kFormCommon : kFormSeparate};
-        // 8-byte scalars: 8 rows in striped separate loops measure 1 % above 9 rows blocked
-        // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s)
-        if (sizeof(A) == 8 && sizeof(T) == 8) return Shape{16, 8, true, kFormSeparate};
+        // 8-byte scalars, sums: 8 rows in striped separate loops measure 1 % above 9 rows blocked
+        // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s).  Minimum and maximum of 8-byte values
+        // take several instructions per combination, and the striped arrangement pays them in one
+        // wave scan per row: blocked 9 rows is 5 % ahead (uint64 max 6.41 / 6.11, float64 min 6.40 / 6.07).
+        if (sizeof(A) == 8 && sizeof(T) == 8 && kSum) return Shape{16, 8, true, kFormSeparate};
         return Shape{16, 9, true, kFormBlocked};
     }
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }

@@ -42,7 +42,7 @@ SMALL_SHAPE = (4, 8)
 MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (not for the affine type)
 
 
-def default_shape(ks, dtype, n=None):
+def default_shape(ks, dtype, n=None, op="sum"):
     """(waves, rows) the library picks for the look-back kernel of this element type and size."""
     eb = ks.ks_elem_bytes(dtype)
     if n is not None and eb >= 16 and n * eb <= (1 << 20):
@@ -52,7 +52,7 @@ def default_shape(ks, dtype, n=None):
             return SMALL_SHAPE
         if n * eb <= (16 << 20) and dtype != "affine_f32":
             return MID_SHAPE
-    waves, rows = (16, 8) if dtype in ("i64", "u64", "f64") else (16, 9)
+    waves, rows = (16, 8) if dtype in ("i64", "u64", "f64") and op == "sum" else (16, 9)
     # up to three rounds of 256 default tiles: the rows that minimise rounds x rows, the default on a
     # tie (16 rows only for one round; the affine type's registers allow neither 12 nor 16 rows)
     if n is not None and eb < 16 and dtype != "affine_f32":
@@ -97,7 +97,7 @@ ALL_PAIRS = sorted(KINDS)
 
 @pytest.mark.parametrize("dtype,op", ALL_PAIRS)
 def test_every_pair_edge_sizes_both_strategies(ks, dtype, op):
-    for n in edge_sizes(tile_elems(ks, dtype, *default_shape(ks, dtype)), tile_elems(ks, dtype, *SMALL_SHAPE),
+    for n in edge_sizes(tile_elems(ks, dtype, *default_shape(ks, dtype, op=op)), tile_elems(ks, dtype, *SMALL_SHAPE),
                         tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)):
         x = random_input(dtype, op, n, seed=1000 + n % 97)
         for inclusive in (True, False):
