@@ -55,7 +55,8 @@ constexpr bool variant_fits() {
 // look-back wave, 9 rows, next tile prefetched (TB/s at 2 GiB of traffic):
 //   float32 sum        common loop, with pauses from 12 rounds on      6.46  (separate loops 6.32)
 //   other 4-byte pairs separate loops   int32 sum 6.31 (common 5.93)
-//   8-byte scalars     separate loops, 8 rows                  uint64 / float64 sum 6.43
+//   8-byte sums        separate loops, 8 rows                  uint64 / float64 sum 6.43
+//   8-byte min / max   separate loops, blocked arrangement   uint64 max 6.41 (striped 8 rows 6.11)
 //   everything else    separate loops, blocked arrangement   affine 6.18, arg-max struct 6.25
 // The float32 sum is the one kernel whose common loop the compiler schedules better
 // than its separate loops; why exactly is not known (same algorithm, same bytes).
