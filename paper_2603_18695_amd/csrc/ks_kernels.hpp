@@ -178,21 +178,26 @@ __device__ __forceinline__ bool lookback(const uint64_t *desc, uint64_t *xdesc, 
 
 // Cross-wave exchange through LDS (paper Sec. V-B: shared-memory exchange that
 // yields the tile aggregate).  Returns the combination of the waves before
-// this one; `aggregate` receives the whole tile's.
-template <class T, class Op, int WAVES>
-__device__ __forceinline__ T exchange_wave_totals(typename WordsOf<T>::type *s_tot, const T &wave_total,
-                                                  T &aggregate, Op op) {
+// this one; `aggregate` receives the whole tile's.  Wave totals are of the
+// accumulation type; from here upwards everything is of the operator's chain type.
+template <class Op, int WAVES>
+__device__ __forceinline__ typename ChainOf<Op>::type exchange_wave_totals(
+    typename WordsOf<typename Op::acc>::type *s_tot, const typename Op::acc &wave_total,
+    typename ChainOf<Op>::type &aggregate) {
+    using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    typename ChainOf<Op>::op cop;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     if (lane == 0) s_tot[wave] = to_words(wave_total);
     __syncthreads();
-    T carry = Op::identity();
-    T all = Op::identity();
+    C carry = ChainOf<Op>::op::identity();
+    C all = ChainOf<Op>::op::identity();
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-        const T t = from_words<T>(s_tot[w]);
-        if (w < wave) carry = op(carry, t);
-        all = op(all, t);
+        const C t = convert<C>(from_words<A>(s_tot[w]));
+        if (w < wave) carry = cop(carry, t);
+        all = cop(all, t);
     }
     aggregate = all;
     return carry;
@@ -241,7 +246,8 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 // atomic per tile: one device-scope atomic on a single address costs 12 ns here,
 // more than a tile's share of the run time).  Every wait is bounded by spin_limit.
 //
-// IO = element type in memory, Op::acc = type of registers and descriptors.
+// IO = element type in memory, Op::acc = type of the registers, ChainOf<Op>::type = type of
+// wave totals once they leave the wave, of aggregates and of descriptors.
 // A workgroup has WAVES wave64s.  Wave 0 talks to the descriptors (publish,
 // look-back).  In the 16-wave shape it does nothing else and waves 1..15 each
 // own a run of 64*ROWS granules of the tile: vector memory instructions of a
@@ -254,20 +260,23 @@ __device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t sp
 // wait and parked unconverted.
 //
 // The tile loop exists in three forms (template parameter FORM, below): one
-// common loop for all waves; for the 16-wave shape, loops of their own for the
-// look-back wave and the data waves, which keeps the look-back's registers
-// apart from the tile's; and the latter with the blocked arrangement of
-// ks_tile.hpp.  Which one a type uses by default was measured (ks_launch.hpp).
+// common loop for all waves in the 4- and 8-wave shapes; in the 16-wave shape
+// loops of their own for the look-back wave and the data waves, which keeps the
+// look-back's registers apart from the tile's (one register allocation serves
+// the whole kernel: in a common loop the two add up, and a reload of a spilled
+// register in the loop waits for every outstanding load, which cancels the
+// prefetch); and the latter with the blocked arrangement of ks_tile.hpp.  Which
+// one a type uses by default was measured (ks_launch.hpp).
 // ---------------------------------------------------------------------------
 constexpr bool dedicated_lookback_wave(int waves) { return waves >= 16; }
 constexpr int data_waves(int waves) { return dedicated_lookback_wave(waves) ? waves - 1 : waves; }
 
-// What the waves of a workgroup share.
-template <class A, int WAVES>
+// What the waves of a workgroup share: A = accumulation type, C = chain type.
+template <class A, class C, int WAVES>
 struct TileExchange {
     typename WordsOf<A>::type tot[WAVES];     // per wave: combination of its run
-    typename WordsOf<A>::type carry[WAVES];   // per wave: combination of the runs before it (separate loops)
-    typename WordsOf<A>::type prefix;         // exclusive prefix of the tile, from the look-back
+    typename WordsOf<C>::type carry[WAVES];   // per wave: combination of the runs before it (separate loops)
+    typename WordsOf<C>::type prefix;         // exclusive prefix of the tile, from the look-back
     uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
 };
 
@@ -299,15 +308,8 @@ template <class A>
 constexpr int prefetch_hold() { return sizeof(A) >= 16 ? kPrefetchHoldWide : kPrefetchHold; }
 template <class A>
 constexpr int poll_delay() { return sizeof(A) >= 16 ? kPollDelayWide : kPollDelay; }
-// The same two in the common loop of the 16-wave shape (float32 sum 2^28, before the staggered
-// start: none 6.22, 24/40 6.29, 28/44 6.30, 32/48 6.30, 20/40 6.25, 32/56 6.27; the hold alone
-// changes nothing there).
-// With the staggered start (below) longer pauses are a little better for it: 28/44 6.45, 36/52 6.47,
-// 44/60 6.48-6.50, 52/68 6.46, 60/80 6.43; the separate loops stay at 24/40, which is also the better
-// pair for inputs of a few rounds (uint64 sum 64 MiB: 5.15 against 4.91 with 40/56).
-constexpr int kCommonPrefetchHold = 60;
-constexpr int kCommonPollDelay = 44;
-constexpr uint32_t kCommonPacedRounds = 12;   // the host takes the paced common loop from this many rounds on
+// Float32 sum, separate loops, delay / hold, TB/s at n = 2^28 / 2^26 / 2^24: 16/32 6.42 / 6.15 / 6.09, 24/40
+// 6.42 / 6.13 / 6.07, 32/48 6.41 / 6.09 / 5.99, 40/56 6.39 / 6.04 / 5.90, 56/72 6.34 / 5.96 / 5.77.
 
 // Output pointers that are not aligned to a 128-byte line (element-aligned views, paper
 // Sec. IV-D).  The buffer accesses work at any alignment, but with tiles that start in the middle
@@ -357,9 +359,9 @@ __device__ __forceinline__ void publish_aggregate(const LookbackArgs &a, uint32_
 
 // Find the tile's exclusive prefix, publish its inclusive prefix, and hand the
 // exclusive prefix to the other waves through x.  Called by wave 0 only.
-template <class A, class Op, int WAVES>
+template <class A, class Op, class X>
 __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t tile, uint32_t m, const A &aggregate,
-                                               TileExchange<A, WAVES> &x) {
+                                               X &x) {
     const int lane = threadIdx.x & (kWave - 1);
     Op op;
     A excl = Op::identity();
@@ -379,23 +381,27 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
 // gives the tile's aggregate, the exclusive one every data wave's carry), publish,
 // look back, hand the prefix over, barrier.  The two loops below execute the
 // same number of barriers per tile and leave together.
-template <class A, class Op, int WAVES, bool PREFETCH>
-__device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileExchange<A, WAVES> &x) {
-    Op op;
+template <class Op, int WAVES, bool PREFETCH>
+__device__ __forceinline__ void lookback_wave_loop(
+    const LookbackArgs &a, TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
+    using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    using COp = typename ChainOf<Op>::op;
+    COp op;
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t m = (a.ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
     for (uint32_t loop_tile = blockIdx.x;;) {
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
         __syncthreads();
-        A mine = Op::identity();
-        if (lane < WAVES - 1) mine = from_words<A>(x.tot[lane + 1]);
-        const A upto = wave_inclusive_scan(mine, op);
-        const A aggregate = read_lane(upto, WAVES - 2);
-        const A before = wave_shift_up(upto, Op::identity());
+        C mine = COp::identity();
+        if (lane < WAVES - 1) mine = convert<C>(from_words<A>(x.tot[lane + 1]));
+        const C upto = wave_inclusive_scan(mine, op);
+        const C aggregate = read_lane(upto, WAVES - 2);
+        const C before = wave_shift_up(upto, COp::identity());
         if (lane < WAVES - 1) x.carry[lane + 1] = to_words(before);
-        publish_aggregate<A, Op>(a, tile, aggregate);
+        publish_aggregate<C, COp>(a, tile, aggregate);
         if (PREFETCH && tile + gridDim.x < a.ntiles) __builtin_amdgcn_s_sleep(poll_delay<A>());   // while the data waves hold
-        resolve_prefix<A, Op, WAVES>(a, tile, m, aggregate, x);
+        resolve_prefix<C, COp>(a, tile, m, aggregate, x);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
         const uint32_t next = tile + gridDim.x;
@@ -409,18 +415,24 @@ __device__ __forceinline__ void lookback_wave_loop(const LookbackArgs &a, TileEx
 // coexist with the look-back's temporaries (one register allocation serves the
 // whole kernel; in one common loop the two add up and wide element types spill).
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const LookbackArgs &a,
-                                               TileExchange<typename Op::acc, WAVES> &x) {
+__device__ __forceinline__ void data_wave_loop(
+    const IO *in, IO *out, const LookbackArgs &a,
+    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    typename ChainOf<Op>::op cop;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
+    // see pinned(): 4-byte elements measure 1 % faster without it (float32 sum 2^28 6.43 against 6.37 TB/s,
+    // int32 sum 6.38 / 6.32), 8-byte ones 0.3-0.8 % slower (uint64 sum 6.42 / 6.43, 2^25 6.11 / 6.16)
+    constexpr bool PIN = sizeof(IO) != 4;
     Op op;
     const size_t shift = tile_shift(out, TILE);   // tiles start on 128-byte lines of the output
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE)), lane_bytes,
+    load_items<IO, ROWS, Op, PIN>(tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE)), lane_bytes,
                              blockIdx.x + 1 == a.ntiles || (blockIdx.x == 0 && shift != 0), cur);
     for (uint32_t loop_tile = blockIdx.x;;) {
         // The tile index is the same in every lane; saying so keeps it, and the buffer resources
@@ -446,20 +458,20 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
         if (PREFETCH && next < a.ntiles) {
             __builtin_amdgcn_s_sleep(prefetch_hold<A>());
             wnext = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
-            load_raw<ROWS, true>(wnext, lane_bytes, nxt);
+            load_raw<ROWS, PIN>(wnext, lane_bytes, nxt);
         }
         if constexpr (Op::commutative) (void)scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-        const A prefix = op(from_words<A>(x.prefix), from_words<A>(x.carry[wave]));
-        apply_prefix_and_store<IO, ROWS, A, Op, true>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, cur,
+        const A prefix = convert<A>(cop(from_words<C>(x.prefix), from_words<C>(x.carry[wave])));
+        apply_prefix_and_store<IO, ROWS, A, Op, PIN>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, cur,
                                                 prefix, op);
         if (next >= a.ntiles) return;
         loop_tile = next;
         if (PREFETCH) {
-            unpack_items<IO, ROWS, Op, true>(nxt, lane_bytes, wnext.valid_bytes, next + 1 == a.ntiles, cur);
+            unpack_items<IO, ROWS, Op, PIN>(nxt, lane_bytes, wnext.valid_bytes, next + 1 == a.ntiles, cur);
         } else {
-            load_items<IO, ROWS, Op, true>(tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE), lane_bytes,
+            load_items<IO, ROWS, Op, PIN>(tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE), lane_bytes,
                                      next + 1 == a.ntiles, cur);
         }
     }
@@ -470,10 +482,12 @@ __device__ __forceinline__ void data_wave_loop(const IO *in, IO *out, const Look
 // granules through its LDS region `stage + (wave - 1) * Stage<ROWS>::SLOTS` on
 // the way in and on the way out, and scans ROWS consecutive granules per lane.
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
-__device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
-                                                       const LookbackArgs &a, TileExchange<typename Op::acc, WAVES> &x,
-                                                       u32x4 *stage) {
+__device__ __forceinline__ void blocked_data_wave_loop(
+    const IO *in, IO *out, const LookbackArgs &a,
+    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, u32x4 *stage) {
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    typename ChainOf<Op>::op cop;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
     Op op;
@@ -512,7 +526,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
         const uint32_t next = tile + gridDim.x;
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-        const A before = op(op(from_words<A>(x.prefix), from_words<A>(x.carry[wave])), lane_before);
+        const A before = op(convert<A>(cop(from_words<C>(x.prefix), from_words<C>(x.carry[wave]))), lane_before);
         RawItems<ROWS> result;
         apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
         blocked_to_striped<ROWS>(region, result);
@@ -527,105 +541,80 @@ __device__ __forceinline__ void blocked_data_wave_loop(const IO *in, IO *out,
     }
 }
 
-// One loop for all waves: wave 0 looks back, and holds data as well unless the
-// shape has a dedicated look-back wave.
-template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, bool PACED, bool ALIGN_OUT>
-__device__ __forceinline__ void common_wave_loop(const IO *in, IO *out, size_t n,
-                                                 uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
-                                                 uint32_t spin_limit, uint32_t *abort_flag) {
+// What the waves share in the common loop.
+template <class A, class C, int WAVES>
+struct CommonExchange {
+    typename WordsOf<A>::type tot[WAVES];
+    typename WordsOf<C>::type prefix;
+    uint32_t ok;
+};
+
+// One loop for all waves (the 4- and 8-wave shapes): every wave holds data and
+// wave 0 looks back as well.
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
+__device__ __forceinline__ void common_wave_loop(
+    const IO *in, IO *out, size_t n, uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
+    uint32_t spin_limit, uint32_t *abort_flag,
+    CommonExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    using COp = typename ChainOf<Op>::op;
     using S = TileShape<IO, ROWS>;
     using Items = ThreadItems<A, ROWS, S::G>;
-    constexpr bool DEDICATED = dedicated_lookback_wave(WAVES);
-    constexpr int DATA_WAVES = data_waves(WAVES);
-    constexpr size_t TILE = (size_t)DATA_WAVES * S::WAVE_ELEMS;
-    __shared__ typename WordsOf<A>::type s_tot[WAVES];
-    __shared__ typename WordsOf<A>::type s_prefix;
-    __shared__ uint32_t s_ok;
+    constexpr size_t TILE = (size_t)WAVES * S::WAVE_ELEMS;
     Op op;
-    // ALIGN_OUT: tiles start on 128-byte lines of the output (see tile_shift).  A variant of its own:
-    // the shift in this loop costs the float32 kernel 1 % also when it is zero.
-    const size_t shift = ALIGN_OUT ? tile_shift(out, TILE) : 0;
-    auto first_of = [&](uint32_t t) -> size_t {
-        if constexpr (ALIGN_OUT) return shifted_first(t, shift, TILE);
-        else return (size_t)t * TILE;
-    };
-    auto elems_of = [&](uint32_t t) -> size_t {
-        if constexpr (ALIGN_OUT) return shifted_elems(t, shift, TILE);
-        else return TILE;
-    };
+    COp cop;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const bool data_wave = !DEDICATED || wave != 0;
     const bool lookback_wave = wave == 0;
-    const int lane_bytes = lane_tile_bytes<ROWS>(DEDICATED ? (wave != 0 ? wave - 1 : 0) : wave);
+    const int lane_bytes = lane_tile_bytes<ROWS>(wave);
 
     uint32_t tile = blockIdx.x;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
-    // The two pauses pay from a dozen rounds per workgroup on (float32 sum with the staggered start,
-    // with / without, TB/s: 2^24 5.60 / 5.89, 2^25 5.71 / 5.84, 2^26 6.13 / 6.13, 2^27 6.34 / 6.25, 2^28
-    // 6.46 / 6.29), and a run-time switch in this loop costs the unpaced case 4-5 %: two kernels,
-    // chosen by the host.
-    constexpr bool paced = DEDICATED && PACED;
     Items cur;
-    if (data_wave) {
-        const TileWindow w = tile_window<IO>(in, n, first_of(tile), elems_of(tile));
-        load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles || (ALIGN_OUT && tile == 0 && shift != 0), cur);
-    }
+    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == ntiles, cur);
     for (;;) {
-        WaveScan<A, ROWS> ws;
-        if (data_wave)
-            ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-        else
-            ws.wave_total = Op::identity();
-        A aggregate;
-        const A wave_carry = exchange_wave_totals<A, Op, WAVES>(s_tot, ws.wave_total, aggregate, op);
+        WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+        C aggregate;
+        const C wave_carry = exchange_wave_totals<Op, WAVES>(x.tot, ws.wave_total, aggregate);
 
         // publish as early as possible: successors only need the aggregate
         if (lookback_wave && lane == 0) {
-            desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
-            if (tile == 0) desc_publish<A>(xdesc, 0, epoch, kPrefix, Op::identity());   // nothing before tile 0
+            desc_publish<C>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+            if (tile == 0) desc_publish<C>(xdesc, 0, epoch, kPrefix, COp::identity());   // nothing before tile 0
         }
         const uint32_t next = tile + gridDim.x;
         RawItems<ROWS> nxt;
         TileWindow wnext;
-        if (data_wave && PREFETCH && next < ntiles) {
-            if (paced) __builtin_amdgcn_s_sleep(kCommonPrefetchHold);
-            wnext = tile_window<IO>(in, n, first_of(next), TILE);
+        if (PREFETCH && next < ntiles) {
+            wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
             load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
-            A excl = Op::identity();
+            C excl = COp::identity();
             bool ok = true;
-            if (paced && PREFETCH && next < ntiles) __builtin_amdgcn_s_sleep(kCommonPollDelay);
             if (tile != 0) {
-                ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
-                if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
+                ok = lookback<C, COp>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
+                if (ok && lane == 0) desc_publish<C>(desc, tile, epoch, kPrefix, cop(excl, aggregate));
             }
             if (lane == 0) {
-                s_prefix = to_words(excl);
-                s_ok = ok ? 1u : 0u;
+                x.prefix = to_words(excl);
+                x.ok = ok ? 1u : 0u;
             }
         }
         __syncthreads();
-        if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
+        if (x.ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
 
-        if (data_wave) {
-            const A prefix = op(from_words<A>(s_prefix), wave_carry);
-            finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
-            apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, first_of(tile), elems_of(tile)),
-                                                           lane_bytes, cur, prefix, op);
-        }
+        const A prefix = convert<A>(cop(from_words<C>(x.prefix), wave_carry));
+        finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
+        apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE), lane_bytes, cur,
+                                                       prefix, op);
         if (next >= ntiles) break;
         tile = next;
-        if (data_wave) {
-            if (PREFETCH) {
-                unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
-            } else {
-                const TileWindow w = tile_window<IO>(in, n, first_of(tile), elems_of(tile));
-                load_items<IO, ROWS, Op, false>(w, lane_bytes, tile + 1 == ntiles, cur);
-            }
-        }
+        if (PREFETCH)
+            unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
+        else
+            load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == ntiles, cur);
     }
 }
 
@@ -649,21 +638,12 @@ __device__ __forceinline__ void stagger_start(uint32_t ntiles) {
 }
 
 // FORM: which loop the kernel runs (see above).
-constexpr int kFormCommon = 0;     // one loop for all waves
+constexpr int kFormCommon = 0;     // one loop for all waves (4- and 8-wave shapes)
 constexpr int kFormSeparate = 1;   // 16 waves: look-back wave and data waves in loops of their own, striped items
 constexpr int kFormBlocked = 2;    // the same with the blocked arrangement (LDS exchange)
-constexpr int kFormCommonPaced = 3;   // the common loop of the 16-wave shape with the two pauses (long inputs)
-constexpr int kFormCommonAligned = 4;        // forms 0 and 3 with tiles aligned to the output's 128-byte lines:
-constexpr int kFormCommonPacedAligned = 5;   // taken by the host for output pointers that are not (16 x 9 only)
-constexpr int kFormCount = 6;
-constexpr bool common_form(int form) {
-    return form == kFormCommon || form == kFormCommonPaced || form == kFormCommonAligned || form == kFormCommonPacedAligned;
-}
-// whether the kernel of this shape and form moves its tiles to the output's line boundaries
-constexpr bool aligns_output(int waves, int form) {
-    return dedicated_lookback_wave(waves) &&
-           (form == kFormSeparate || form == kFormBlocked || form == kFormCommonAligned || form == kFormCommonPacedAligned);
-}
+constexpr int kFormCount = 3;
+// whether the kernel of this shape moves its tiles to the output's line boundaries
+constexpr bool aligns_output(int waves) { return dedicated_lookback_wave(waves); }
 
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
 __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out,
@@ -676,38 +656,41 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
         return;
     }
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    static_assert(dedicated_lookback_wave(WAVES) == (FORM != kFormCommon), "16 waves run separate loops, 4 and 8 the common one");
     if (blockIdx.x >= ntiles) return;
-    if constexpr (dedicated_lookback_wave(WAVES)) stagger_start(ntiles);
-    if constexpr (dedicated_lookback_wave(WAVES) && !common_form(FORM)) {
-        __shared__ TileExchange<A, WAVES> x;
+    if constexpr (dedicated_lookback_wave(WAVES)) {
+        stagger_start(ntiles);
+        __shared__ TileExchange<A, C, WAVES> x;
         const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
         if constexpr (FORM == kFormBlocked) {
             __shared__ u32x4 stage[(WAVES - 1) * Stage<ROWS>::SLOTS];
             if (threadIdx.x < kWave)
-                lookback_wave_loop<A, Op, WAVES, PREFETCH>(a, x);
+                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x);
             else
                 blocked_data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, stage);
         } else {
             if (threadIdx.x < kWave)
-                lookback_wave_loop<A, Op, WAVES, PREFETCH>(a, x);
+                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x);
             else
                 data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
         }
     } else {
-        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH,
-                         FORM == kFormCommonPaced || FORM == kFormCommonPacedAligned, aligns_output(WAVES, FORM)>(
-            in, out, n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag);
+        __shared__ CommonExchange<A, C, WAVES> x;
+        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, n, desc, xdesc, epoch, ntiles, spin_limit,
+                                                                   abort_flag, x);
     }
 }
 
 // ---------------------------------------------------------------------------
 // Reduce-then-scan (no waiting between workgroups; one workgroup per tile).
-// Aggregates and seeds are arrays of Op::acc.
+// Aggregates and seeds are arrays of the operator's chain type.
 // ---------------------------------------------------------------------------
 template <class IO, class Op, int ROWS>
 __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restrict__ in, size_t n,
-                                                             typename Op::acc *__restrict__ aggregates) {
+                                                             typename ChainOf<Op>::type *__restrict__ aggregates) {
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
@@ -717,8 +700,8 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
     ThreadItems<A, ROWS, S::G> cur;
     load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
     const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-    A aggregate;
-    (void)exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+    C aggregate;
+    (void)exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
     if (threadIdx.x == 0) aggregates[tile] = aggregate;
 }
 
@@ -726,8 +709,11 @@ __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restric
 // covers the whole input).  Otherwise seeds[tile] = combination of all earlier tiles.
 template <class IO, class Op, int ROWS, bool INCLUSIVE>
 __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out, size_t n,
-                                                           const typename Op::acc *__restrict__ seeds) {
+                                                           const typename ChainOf<Op>::type *__restrict__ seeds) {
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    using COp = typename ChainOf<Op>::op;
+    COp cop;
     using S = TileShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
@@ -737,12 +723,12 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out
     ThreadItems<A, ROWS, S::G> cur;
     load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
     const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-    A aggregate;
-    const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+    C aggregate;
+    const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
     finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
-    const A seed = seeds ? seeds[tile] : Op::identity();
+    const C seed = seeds ? seeds[tile] : COp::identity();
     apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, tile * TILE, TILE), lane_bytes, cur,
-                                               op(seed, wave_carry), op);
+                                               convert<A>(cop(seed, wave_carry)), op);
 }
 
 // Single-pass scan of a strided view (element i at base[i * stride], paper Sec. IV-C): the
@@ -761,12 +747,15 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO 
         return;
     }
     using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    using COp = typename ChainOf<Op>::op;
     constexpr size_t WAVE_ELEMS = (size_t)kWave * ROWS;   // one-element granules
     constexpr size_t TILE = (size_t)kWaves * WAVE_ELEMS;
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
-    __shared__ typename WordsOf<A>::type s_prefix;
+    __shared__ typename WordsOf<C>::type s_prefix;
     __shared__ uint32_t s_ok;
     Op op;
+    COp cop;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
@@ -775,18 +764,18 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO 
         ThreadItems<A, ROWS, 1> cur;
         load_items_strided<IO, ROWS, Op>(in, in_stride, n, run_first, cur);
         const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, 1, Op>(cur, op);
-        A aggregate;
-        const A wave_carry = exchange_wave_totals<A, Op, kWaves>(s_tot, ws.wave_total, aggregate, op);
+        C aggregate;
+        const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
         if (wave == 0) {
             if (lane == 0) {
-                desc_publish<A>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
-                if (tile == 0) desc_publish<A>(xdesc, 0, epoch, kPrefix, Op::identity());   // nothing before tile 0
+                desc_publish<C>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+                if (tile == 0) desc_publish<C>(xdesc, 0, epoch, kPrefix, COp::identity());   // nothing before tile 0
             }
-            A excl = Op::identity();
+            C excl = COp::identity();
             bool ok = true;
             if (tile != 0) {
-                ok = lookback<A, Op>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
-                if (ok && lane == 0) desc_publish<A>(desc, tile, epoch, kPrefix, op(excl, aggregate));
+                ok = lookback<C, COp>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
+                if (ok && lane == 0) desc_publish<C>(desc, tile, epoch, kPrefix, cop(excl, aggregate));
             }
             if (lane == 0) {
                 s_prefix = to_words(excl);
@@ -795,7 +784,7 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO 
         }
         __syncthreads();
         if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
-        const A prefix = op(from_words<A>(s_prefix), wave_carry);
+        const A prefix = convert<A>(cop(from_words<C>(s_prefix), wave_carry));
         finish_wave_run<INCLUSIVE, A, ROWS, 1, Op>(cur, ws, op);
         apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, n, run_first, cur, prefix, op);
     }

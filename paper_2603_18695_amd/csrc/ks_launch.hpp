@@ -23,22 +23,18 @@ inline size_t ceil_div(size_t x, size_t y) { return (x + y - 1) / y; }
 struct Shape {
     int waves, rows;
     bool prefetch;
-    int form;     // kFormCommon ... kFormCommonPacedAligned (all but kFormCommon: 16 waves only)
+    int form;     // kFormCommon (4 and 8 waves), kFormSeparate or kFormBlocked (16 waves)
 };
 
 // Which variants are offered at all.  A wave may use 512 / (waves per SIMD)
 // registers; the tile needs 4 * ROWS * (acc size / element size) of them, the
 // parked next tile 4 * ROWS, the rest goes to addresses and wave-scan temporaries.
 // The bound is loose: variants close to it may spill a few registers (they stay
-// correct); the defaults below were checked not to.
+// correct); no default shape of any pair does (the compiler's resource report of
+// every default kernel shows no scratch).
 template <class T, class A, int WAVES, int ROWS, bool PREFETCH, int FORM>
 constexpr bool variant_fits() {
-    // the paced common loop (long inputs) and the common loops with output-aligned tiles are compiled
-    // in the default shape only
-    if (FORM == kFormCommonPaced || FORM == kFormCommonAligned || FORM == kFormCommonPacedAligned)
-        return WAVES == 16 && ROWS == 9 && PREFETCH && variant_fits<T, A, WAVES, ROWS, PREFETCH, kFormCommon>();
-    constexpr bool SPLIT = FORM != kFormCommon;
-    if (SPLIT && !dedicated_lookback_wave(WAVES)) return false;   // nothing to separate
+    if (dedicated_lookback_wave(WAVES) != (FORM != kFormCommon)) return false;   // see scan_lookback_kernel
     if (WAVES == 16 && ROWS == 4) return false;                   // never competitive, not compiled
     if (FORM == kFormBlocked)   // bounded by LDS; every element type compiles without spills at 8 and 9 rows
         return (size_t)(WAVES - 1) * Stage<ROWS>::SLOTS * 16 <= 150 * 1024;
@@ -47,19 +43,16 @@ constexpr bool variant_fits() {
     constexpr int data = 4 * ROWS * (int)(sizeof(A) / sizeof(T));
     constexpr int parked = PREFETCH ? 4 * ROWS : 0;
     // in the common loop the look-back's temporaries live next to the data, in separate loops they do not
-    constexpr int other = SPLIT ? 24 + 6 * (int)(sizeof(A) / 4) : 40 + 12 * (int)(sizeof(A) / 4);
+    constexpr int other = FORM != kFormCommon ? 24 + 6 * (int)(sizeof(A) / 4) : 40 + 12 * (int)(sizeof(A) / 4);
     return data + parked + other <= budget;
 }
 
 // Default shape per pair: the best measured on MI355X, always 15 data waves + 1
-// look-back wave, 9 rows, next tile prefetched (TB/s at 2 GiB of traffic):
-//   float32 sum        common loop, with pauses from 12 rounds on      6.46  (separate loops 6.32)
-//   other 4-byte pairs separate loops   int32 sum 6.31 (common 5.93)
+// look-back wave, next tile prefetched (TB/s at 2 GiB of traffic):
+//   4-byte pairs       separate loops, 9 rows                  float32 sum 6.42, int32 sum 6.38
 //   8-byte sums        separate loops, 8 rows                  uint64 / float64 sum 6.43
 //   8-byte min / max   separate loops, blocked arrangement   uint64 max 6.41 (striped 8 rows 6.11)
 //   everything else    separate loops, blocked arrangement   affine 6.18, arg-max struct 6.25
-// The float32 sum is the one kernel whose common loop the compiler schedules better
-// than its separate loops; why exactly is not known (same algorithm, same bytes).
 //
 // Small inputs (up to kSmallInputBytes) of 4- and 8-byte elements take 4 waves x 8
 // rows instead: 32 KiB tiles spread the input over more compute units, and the run
@@ -73,10 +66,9 @@ constexpr bool variant_fits() {
 template <class T, class Op>
 struct PairDefaults {
     using A = typename Op::acc;
-    static constexpr bool kFloat32Sum = std::is_same<typename MapOf<Op>::unmapped, SumOp<float>>::value;
     static constexpr bool kSum = std::is_same<typename MapOf<Op>::unmapped, SumOp<T>>::value;
     static constexpr Shape shape() {
-        if (sizeof(A) == 4) return Shape{16, 9, true, kFloat32Sum ? kFormCommon : kFormSeparate};
+        if (sizeof(A) == 4) return Shape{16, 9, true, kFormSeparate};
         // 8-byte scalars, sums: 8 rows in striped separate loops measure 1 % above 9 rows blocked
         // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s).  Minimum and maximum of 8-byte values
         // take several instructions per combination, and the striped arrangement pays them in one
@@ -86,10 +78,6 @@ struct PairDefaults {
     }
     static constexpr Shape small_shape() { return Shape{4, 8, true, kFormCommon}; }
     static constexpr size_t kSmallInputBytes = (size_t)8 << 20;
-    // 4-byte pairs below this size stay in the common loop: with only a few rounds per workgroup
-    // the separate loops and their pauses do not pay yet (int32 sum, common / separate, TB/s:
-    // 64 MiB 5.89 / 5.91, 128 MiB 5.37 / 5.76, 256 MiB 5.68 / 6.08, 1 GiB 5.93 / 6.31).
-    static constexpr size_t kSeparateFromBytes = (size_t)128 << 20;
     // Between the two, 8 waves x 8 rows (64 KiB tiles, no next tile to prefetch): up to 34 MiB the
     // large tile leaves compute units without work (16 MiB are 124 tiles of 135 KiB).  Against the
     // large shape, TB/s: int32 sum 16 MiB 3.48 / 3.18, uint64 sum 16 MiB 3.35 / 3.07, 32 MiB 5.11 / 4.75;
@@ -109,16 +97,17 @@ struct PairDefaults {
         if (sizeof(T) >= 16 && n * sizeof(T) <= kSmallInputBytes16) return Shape{4, 4, true, kFormCommon};
         if (sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes) return small_shape();
         if (sizeof(T) < 16 && n * sizeof(T) <= kMidInputBytes) return mid_shape();
-        if (sizeof(A) == 4 && n * sizeof(T) < kSeparateFromBytes) return Shape{16, 9, true, kFormCommon};
         return shape();
     }
 };
 
-// T = element type in memory; A = Op::acc = type of aggregates, seeds and descriptors.
+// T = element type in memory; A = Op::acc = type held in registers; C = the operator's chain type =
+// type of aggregates, seeds and descriptors.
 template <class T, class Op>
 struct Pair {
     using A = typename Op::acc;
-    static constexpr int W = WordsOf<A>::W;
+    using C = typename ChainOf<Op>::type;
+    static constexpr int W = WordsOf<C>::W;
     static constexpr int kRtsRows = 4;
     static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
 
@@ -154,11 +143,10 @@ struct Pair {
         };
         if (s.rows == 8 && s.form == kFormSeparate && variant_fits<T, A, 16, 9, true, kFormSeparate>())
             consider(Shape{16, 9, true, kFormSeparate});
-        constexpr int form = sizeof(A) == 4 ? kFormCommon : kFormSeparate;
         if (variant_fits<T, A, 16, 12, true, kFormSeparate>())
             consider(Shape{16, 12, true, kFormSeparate});
-        else if (variant_fits<T, A, 16, 12, false, form>())
-            consider(Shape{16, 12, false, form});
+        else if (variant_fits<T, A, 16, 12, false, kFormSeparate>())
+            consider(Shape{16, 12, false, kFormSeparate});
         if (variant_fits<T, A, 16, 16, false, kFormSeparate>() && rounds(16) == 1)
             consider(Shape{16, 16, false, kFormSeparate});
         // less than one round: smaller tiles keep more compute units busy
@@ -167,37 +155,19 @@ struct Pair {
         return best;
     }
 
-    // the common loop of the default shape takes its paced variant for long inputs
-    static Shape paced_shape(size_t n, int cus, Shape s) {
-        if (s.waves == 16 && s.rows == 9 && s.prefetch && s.form == kFormCommon &&
-            ceil_div(n, shape_tile_elems(16, 9)) >= (size_t)kCommonPacedRounds * (size_t)cus)
-            s.form = kFormCommonPaced;
-        return s;
-    }
-
-    // The common loop of the default shape has variants of its own for output pointers that are not
-    // aligned to a 128-byte line (the separate loops handle them in place).
-    static Shape output_aligned_shape(const void *out, Shape s) {
-        if (s.waves == 16 && s.rows == 9 && s.prefetch && lead_elements(static_cast<const T *>(out)) != 0) {
-            if (s.form == kFormCommon) s.form = kFormCommonAligned;
-            if (s.form == kFormCommonPaced) s.form = kFormCommonPacedAligned;
-        }
-        return s;
-    }
-
-    static Shape lookback_shape(size_t n, int cus, const void *out) {
-        Shape s = paced_shape(n, cus, PairDefaults<T, Op>::shape_for(n));
+    static Shape lookback_shape(size_t n, int cus) {
+        Shape s = PairDefaults<T, Op>::shape_for(n);
         if (MapOf<Op>::mapped) return s;
         s = few_rounds_shape(n, cus, s);
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
         if (o.rows == 4 || o.rows == 8 || o.rows == 9 || o.rows == 12 || o.rows == 16) s.rows = (int)o.rows;
         if (o.prefetch >= 0) s.prefetch = o.prefetch != 0;
-        if (o.form >= 0)
-            s.form = (int)o.form;
-        else
-            s = output_aligned_shape(out, s);
+        // an explicit wave count takes the form that goes with it; an explicit form that does not go
+        // with the wave count is refused by the dispatch below
         if (!dedicated_lookback_wave(s.waves)) s.form = kFormCommon;
+        else if (s.form == kFormCommon) s.form = PairDefaults<T, Op>::shape().form;
+        if (o.form >= 0) s.form = (int)o.form;
         return s;
     }
 
@@ -219,8 +189,8 @@ struct Pair {
         const size_t tile = tile_elems(kRtsRows);
         if (m > tile) {
             m = ceil_div(m, tile);
-            total = align_up(m * sizeof(A), 256);
-            using Upper = Pair<A, typename MapOf<Op>::unmapped>;
+            total = align_up(m * sizeof(C), 256);
+            using Upper = Pair<C, typename ChainOf<Op>::op>;
             if (m > Upper::tile_elems(kRtsRows)) total += Upper::temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, m);
         }
         return total > 0 ? total : 256;
@@ -290,7 +260,7 @@ struct Pair {
             auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM>;
             constexpr int kThreads = WAVES * kWave;
             // kernels that move their tiles to the output's line boundaries have tile 0 cut short
-            const size_t shift = aligns_output(WAVES, FORM)
+            const size_t shift = aligns_output(WAVES)
                                      ? tile_shift(static_cast<const T *>(c.out), shape_tile_elems(WAVES, ROWS))
                                      : 0;
             const size_t tiles = ceil_div(c.n + shift, shape_tile_elems(WAVES, ROWS));
@@ -332,14 +302,12 @@ struct Pair {
     template <int WAVES, int ROWS>
     static int lookback_pf_dispatch(const ScanCall &c, const Shape &s) {
         if constexpr (dedicated_lookback_wave(WAVES)) {
-            if (s.form == kFormSeparate) return lookback_flags_dispatch<WAVES, ROWS, kFormSeparate>(c, s.prefetch);
             if (s.form == kFormBlocked) return lookback_flags_dispatch<WAVES, ROWS, kFormBlocked>(c, s.prefetch);
-            if (s.form == kFormCommonPaced) return lookback_flags_dispatch<WAVES, ROWS, kFormCommonPaced>(c, s.prefetch);
-            if (s.form == kFormCommonAligned) return lookback_flags_dispatch<WAVES, ROWS, kFormCommonAligned>(c, s.prefetch);
-            if (s.form == kFormCommonPacedAligned)
-                return lookback_flags_dispatch<WAVES, ROWS, kFormCommonPacedAligned>(c, s.prefetch);
+            if (s.form == kFormSeparate) return lookback_flags_dispatch<WAVES, ROWS, kFormSeparate>(c, s.prefetch);
+        } else {
+            if (s.form == kFormCommon) return lookback_flags_dispatch<WAVES, ROWS, kFormCommon>(c, s.prefetch);
         }
-        return lookback_flags_dispatch<WAVES, ROWS, kFormCommon>(c, s.prefetch);
+        return KS_ERR_UNSUPPORTED;   // the 16-wave shape has no common loop, the others nothing to separate
     }
 
     template <int WAVES>
@@ -363,17 +331,9 @@ struct Pair {
                 if (c.n * sizeof(T) <= PairDefaults<T, Op>::kSmallInputBytes)
                     return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
             }
-            if constexpr (sizeof(A) == 4 && d.form != kFormCommon) {
-                if (c.n * sizeof(T) < PairDefaults<T, Op>::kSeparateFromBytes)
-                    return lookback_flags_dispatch<d.waves, d.rows, kFormCommon>(c, d.prefetch);
-            }
-            if constexpr (d.form == kFormCommon) {
-                if (paced_shape(c.n, c.dev->cus, d).form == kFormCommonPaced)
-                    return lookback_flags_dispatch<d.waves, d.rows, kFormCommonPaced>(c, d.prefetch);
-            }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
         }
-        const Shape s = lookback_shape(c.n, c.dev->cus, c.out);
+        const Shape s = lookback_shape(c.n, c.dev->cus);
         switch (s.waves) {
             case 4: return lookback_rows_dispatch<4>(c, s);
             case 8: return lookback_rows_dispatch<8>(c, s);
@@ -383,7 +343,7 @@ struct Pair {
     }
 
     // ---- reduce-then-scan ----------------------------------------------------
-    static int launch_tile_scan(bool inclusive, const T *in, T *out, size_t n, const A *seeds, hipStream_t s) {
+    static int launch_tile_scan(bool inclusive, const T *in, T *out, size_t n, const C *seeds, hipStream_t s) {
         const size_t tiles = ceil_div(n, tile_elems(kRtsRows));
         if (inclusive)
             hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, true>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in,
@@ -399,15 +359,15 @@ struct Pair {
         const size_t tile = tile_elems(kRtsRows);
         const size_t tiles = ceil_div(n, tile);
         if (tiles <= 1) return launch_tile_scan(inclusive, in, out, n, nullptr, s);
-        const size_t need = align_up(tiles * sizeof(A), 256);
+        const size_t need = align_up(tiles * sizeof(C), 256);
         if (need > temp_bytes) return KS_ERR_WORKSPACE;
-        A *agg = reinterpret_cast<A *>(temp);
+        C *agg = reinterpret_cast<C *>(temp);
         hipLaunchKernelGGL((tile_reduce_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in, n, agg);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return set_hip_error(e);
         // aggregates -> exclusive prefixes of the tiles, in place (scratch is 256-byte aligned)
         // (the map has been applied by the reduction; the levels above combine plain accumulators)
-        using Upper = Pair<A, typename MapOf<Op>::unmapped>;
+        using Upper = Pair<C, typename ChainOf<Op>::op>;
         int st = Upper::run_rts(false, agg, agg, tiles, temp + need, temp_bytes - need, s);
         if (st != KS_OK) return st;
         return launch_tile_scan(inclusive, in, out, n, agg, s);

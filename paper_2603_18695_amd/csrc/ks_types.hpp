@@ -5,6 +5,7 @@
 //     using acc = ...;                    // type the scan is carried out in
 //     static acc identity();              // op(identity, x) == x bit for bit
 //     acc operator()(acc l, acc r) const; // l = accumulated (earlier), r = later
+//     using chain = ...;                  // optional: a wider operator for everything above one wave's run
 // The element type in memory ("io" type) is converted to acc on load and back
 // on store (convert<>); for most pairs the two are the same type.  io types are
 // trivially copyable, 4, 8 or 16 bytes; acc types are a multiple of 4 bytes and
@@ -76,6 +77,21 @@ struct SumOp {
     using acc = T;
     __device__ static T identity() { return T(0); }
     __device__ __forceinline__ T operator()(T l, T r) const { return l + r; }
+};
+// Float32 sums: inside one wave's run (a few thousand neighbouring elements) the additions are
+// float32; wave totals, tile aggregates, descriptors and the look-back's running value are double.
+// The prefix of a long input is a chain of one addition per tile, and every float32 rounding in
+// that chain stays in all later outputs at the magnitude the running sum had when it was made:
+// for mixed-sign data the sum comes back to zero with the error of its excursions still in it.
+// Carried in double the chain adds nothing; what is left are the roundings inside the runs
+// (paper Sec. VII-B validates against a Float64 reference; Sec. V-B leaves the accumulation type open).
+template <>
+struct SumOp<float> {
+    static constexpr bool commutative = true;
+    using acc = float;
+    using chain = SumOp<double>;
+    __device__ static float identity() { return 0.0f; }
+    __device__ __forceinline__ float operator()(float l, float r) const { return l + r; }
 };
 // signed integer sums wrap: add in the unsigned type
 template <>
@@ -206,7 +222,22 @@ struct MapOf<Op, decltype((void)sizeof(typename Op::map))> {
     static constexpr bool mapped = true;
 };
 
-// ---- conversions between memory type and accumulation type ---------------------
+// ---- chain type: what is carried above one wave's run ----------------------------
+// ChainOf<Op>::op is the operator that combines wave totals, tile aggregates and descriptor values,
+// ChainOf<Op>::type its value type; for most operators they are the operator itself (without its
+// map) and its acc.  convert<> moves values between acc and the chain type.
+template <class Op, class = void>
+struct ChainOf {
+    using op = typename MapOf<Op>::unmapped;
+    using type = typename Op::acc;
+};
+template <class Op>
+struct ChainOf<Op, decltype((void)sizeof(typename Op::chain))> {
+    using op = typename Op::chain;
+    using type = typename op::acc;
+};
+
+// ---- conversions between memory type, accumulation type and chain type ------------
 
 template <class To, class From>
 struct Convert {
@@ -215,6 +246,14 @@ struct Convert {
 template <class T>
 struct Convert<T, T> {
     __device__ __forceinline__ static T apply(const T &x) { return x; }
+};
+template <>
+struct Convert<double, float> {
+    __device__ __forceinline__ static double apply(const float &x) { return (double)x; }
+};
+template <>
+struct Convert<float, double> {
+    __device__ __forceinline__ static float apply(const double &x) { return (float)x; }
 };
 template <>
 struct Convert<AffineF64, AffineF32> {

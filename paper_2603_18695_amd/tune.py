@@ -8,9 +8,8 @@ combination of
     waves     4, 8, 16 wave64s per workgroup
     rows      4, 8, 9, 12, 16  16-byte vectors per thread
     prefetch  next tile requested before the look-back wait, or not
-    form      0 common loop, 1 separate loops, 2 separate loops + blocked arrangement,
-              3 common loop with pauses (9 rows with prefetch only),
-              4 / 5 forms 0 / 3 with tiles on the output's 128-byte lines (the same only)
+    form      0 common loop (4 and 8 waves), 1 separate loops, 2 separate loops + blocked
+              arrangement (16 waves)
 
 through the library's own options (ks_set_option) and prints them best first,
 next to the library's built-in default.  Combinations that do not fit the
@@ -38,7 +37,7 @@ import paper_2603_18695_amd as ks
 
 WAVES = (4, 8, 16)
 ROWS = (4, 8, 9, 12, 16)
-FORMS = {4: (0,), 8: (0,), 16: (0, 1, 2, 3, 4, 5)}
+FORMS = {4: (0,), 8: (0,), 16: (1, 2)}
 
 
 def _buffers(dtype: str, n: int, random: bool):

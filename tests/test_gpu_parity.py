@@ -1,6 +1,6 @@
 """GPU parity: the HIP library, called through its C ABI, against the sequential CPU oracle on the
-same seeded inputs.  Bars are in tests/parity.py (bit-exact integers / structs, 1e-4 relative +
-1e-3 absolute for floating point against the fp64 oracle)."""
+same seeded inputs.  Bars are in tests/parity.py (bit-exact integers / structs; relative 1e-4,
+absolute 1e-3 near zero, for floating point against the fp64 oracle)."""
 import sys
 
 import numpy as np
@@ -161,17 +161,6 @@ def test_inputs_of_a_few_rounds_take_the_rows_that_fill_their_rounds(ks, dtype, 
     assert_matches(dtype, op, got, reference(dtype, op, x, True), f"({dtype},{op}) n={n}")
 
 
-def test_default_form_switches_with_the_input_size(ks):
-    # 4-byte pairs other than the float32 sum run the common loop below 128 MiB of input and the
-    # separate loops from there on; both sides of the limit, exact compare
-    at = (128 << 20) // 4
-    for n in (at - 1, at):
-        x = ks_inputs.whole("int32_sum", n)
-        say(f"[case] (i32,sum) n={n} at the size where the default form changes")
-        got = run(ks, "i32", "sum", x, api="plain")
-        assert np.array_equal(got, reference("i32", "sum", x, True)), n
-
-
 def test_closed_forms_on_the_gpu(ks):
     n = (1 << 22) + 12345
     say("[case] all-ones int32 / uint64 / f32, iota uint64")
@@ -238,7 +227,7 @@ def test_in_place_and_misaligned_pointers(ks):
                                       ("argmax_i32_cnt64", "argmax_count")])
 def test_output_pointers_off_the_128_byte_lines(ks, dtype, op):
     # the 16-wave kernels move their tiles to the output's line boundaries (tile 0 is cut short);
-    # sizes of a few rounds (12 rows), several rounds, and enough rounds for the paced common loop
+    # sizes of a few rounds (12 rows), several rounds and a dozen rounds
     tile9 = tile_elems(ks, dtype, 16, 9)
     for tiles, offsets in ((290, [(1, 1)]), (700, [(1, 1), (0, 3), (5, 2)]), (3300, [(7, 7), (2, 0)])):
         n = tiles * tile9 + 11
@@ -252,8 +241,6 @@ def test_output_pointers_off_the_128_byte_lines(ks, dtype, op):
                 d_out_all.fill_(0x3C)
                 ks.ks_scan(d_in, d_out, dtype=dtype, op=op, inclusive=inclusive)
                 ks.ks_scan_check()
-                if off_out % (128 // ks.ks_elem_bytes(dtype)) and dtype == "f32":
-                    assert ks.ks_get_option("last_form") in ((1, 4) if tiles < 3072 else (5,))
                 got = to_host(d_out, x.dtype)
                 assert_matches(dtype, op, got, reference(dtype, op, x[off_in:off_in + n], inclusive),
                                f"off-line ({dtype},{op}) n={n} +{off_in}/+{off_out}")
@@ -268,7 +255,7 @@ def test_output_pointers_off_the_128_byte_lines(ks, dtype, op):
     assert_matches(dtype, op, to_host(d_all[3:], x.dtype), reference(dtype, op, x[3:], True), "in place, off the line")
 
 
-@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 0), (16, 1), (16, 2), (16, 3), (16, 4), (16, 5)])
+@pytest.mark.parametrize("waves,form", [(4, 0), (8, 0), (16, 1), (16, 2)])
 @pytest.mark.parametrize("rows", [4, 8, 9, 12, 16])
 @pytest.mark.parametrize("prefetch", [0, 1])
 def test_lookback_variants(ks, waves, form, rows, prefetch):
@@ -585,6 +572,42 @@ def test_config_int32_sum_2_20(ks):
 def test_config_f32_sum_2_28(ks):
     assert _full_config(ks, "f32_sum") <= 1.0
     assert _full_config(ks, "f32_sum", api="with_temp", algo="reduce_then_scan") <= 1.0
+
+
+def test_f32_sum_2_28_is_exact_on_small_integers(ks):
+    # The float bar at the end of config 2 is 1e-4 x 1.3e8: a dropped or doubled element would pass it.
+    # Inputs in {0, 1} with a total below 2^24 make every partial sum an integer that float32 holds
+    # exactly, whatever the order of the additions, so the default kernel of the headline size (and the
+    # fallback) must reproduce the oracle bit for bit at all 2^28 positions.
+    n = 1 << 28
+    rng = np.random.default_rng(28)
+    d_in = torch.empty(n, dtype=torch.float32, device="cuda")
+    d_ref = torch.empty(n, dtype=torch.float32, device="cuda")
+    stream = oracle.ScanStream("sum", "f32", True)
+    total = 0.0
+    for at in range(0, n, ks_inputs.CHUNK):
+        x = (rng.random(ks_inputs.CHUNK, dtype=np.float32) < 0.05).astype(np.float32)
+        ref = stream.feed(x)
+        total = float(ref[-1])
+        d_in[at:at + len(x)] = torch.from_numpy(x).cuda()
+        d_ref[at:at + len(x)] = torch.from_numpy(ref.astype(np.float32)).cuda()
+    assert total < float(1 << 24), total
+    d_out = torch.empty_like(d_in)
+    for inclusive in (True, False):
+        say(f"[case] f32 sum n=2^28, inputs in {{0,1}}, total {total:.0f}, inclusive={inclusive}: exact compare")
+        ks.ks_scan(d_in, d_out, dtype="f32", op="sum", inclusive=inclusive)
+        ks.ks_scan_check()
+        assert ks.ks_get_option("last_waves") == 16 and ks.ks_get_option("last_rows") == 9
+        if inclusive:
+            assert torch.equal(d_out, d_ref)
+        else:
+            assert float(d_out[0]) == 0.0 and torch.equal(d_out[1:], d_ref[:-1])
+    temp = torch.empty(ks.ks_scan_temp_bytes(dtype="f32", op="sum", n=n, algo="reduce_then_scan"), dtype=torch.uint8,
+                       device="cuda")
+    say("[case] f32 sum n=2^28, inputs in {0,1}, reduce-then-scan: exact compare")
+    ks.ks_scan_with_temp(d_in, d_out, temp, dtype="f32", op="sum", inclusive=True, algo="reduce_then_scan")
+    ks.ks_scan_check()
+    assert torch.equal(d_out, d_ref)
 
 
 def test_config_u64_exclusive_sum_2_27(ks):
