@@ -254,7 +254,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
                                f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb, "stride": args.stride,
-                   "options": {k: ks.ks_get_option(k) for k in ["waves", "rows", "prefetch", "form", "grid_mode", "wgs_per_cu"]}},
+                   "options": {k: ks.ks_get_option(k) for k in ["waves", "rows", "prefetch", "form", "tickets", "wgs_per_cu"]}},
         "elements_per_s": n / (wall_ms * 1e-3),
         "pct_of_hbm_peak": 100 * gbs_wall / HBM_PEAK_GBS,
         "copy_ceiling_gbs": copy_gbs,

@@ -92,15 +92,16 @@ typedef enum {
 
 /*
  * Scan n elements of `in` into `out` on `stream` (paper Sec. V-B).
- * Uses a library-owned workspace cached per (device, stream); the first call on
- * a stream, or a call needing a larger workspace, allocates device memory (and
- * must therefore not be made under stream capture: use ks_scan_with_temp there).
- * The first look-back launch of each kernel variant (dtype, op, inclusive and
- * tuning options) also runs a short residency check that synchronises the
- * stream; this holds for ks_scan_with_temp too, so warm a variant up once
- * before capturing it into a graph.
+ * Uses a library-owned scratch buffer cached per (device, stream); the first
+ * call on a stream, or a call that needs a larger one, allocates device memory.
  * Back-to-back calls on one stream are safe; calls on different streams use
- * different workspaces.  inclusive: non-zero = inclusive, 0 = exclusive.
+ * different buffers.  inclusive: non-zero = inclusive, 0 = exclusive.
+ * Under stream capture the call is recorded if the stream's scratch is already
+ * large enough (make an eager call with at least the same n on that stream
+ * first); otherwise it returns KS_ERR_WORKSPACE and records nothing.  A recorded
+ * call clears its scratch with a kernel of its own on every replay, and a
+ * scratch buffer that a graph has recorded is never freed.  Callers that must
+ * not depend on any of this use ks_scan_with_temp.
  */
 int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n,
             void *stream);
@@ -146,19 +147,24 @@ size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n);
  * 256-byte aligned, of at least ks_scan_temp_bytes(...) bytes, whose previous
  * contents do not matter.  Allocates nothing.  The scratch may be reused by a
  * later call on the same stream; two calls in flight at once need two buffers.
- * The call only launches kernels (the descriptors are cleared by one, not by a
- * memset), so it may be recorded into a HIP graph and replayed; make one
- * ordinary call with the same dtype, op and shape options first: the first use
- * of a kernel variant on a device runs a one-off check that synchronises the
- * stream and cannot be captured.
+ * The call only launches kernels (the scratch is cleared by one, not by a
+ * memset) and never synchronises, so it may be recorded into a HIP graph and
+ * replayed.
  */
 int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, const void *in,
                       void *out, size_t n, void *temp, size_t temp_bytes, void *stream);
 
 /*
- * Synchronise `stream` and report whether any look-back kernel since the last
- * check gave up waiting for a predecessor tile (KS_ERR_TIMEOUT; its output is
- * then invalid), or a HIP error surfaced (KS_ERR_HIP).  The flag is cleared.
+ * Synchronise `stream` and report whether any scan issued on this stream (of
+ * the current device) since the last check gave up waiting for a predecessor
+ * tile (KS_ERR_TIMEOUT; that call's output is invalid), or a HIP error surfaced
+ * (KS_ERR_HIP).  The stream's flag is cleared; scans on other streams have flags
+ * of their own and are neither blamed nor disturbed.  Waits are bounded
+ * ("spin_limit") so that a scan can never hang the device: a workgroup waits
+ * for tiles of workgroups that may not have started yet when other work holds
+ * the compute units, and gives up if that lasts longer than the limit allows
+ * (about half a second at the default).  With the option "tickets" = 1 no
+ * workgroup ever waits for one that has not started.
  */
 int ks_scan_check(void *stream);
 
@@ -169,37 +175,41 @@ int ks_pair_supported(ks_dtype dtype, ks_op op);
 size_t ks_elem_bytes(ks_dtype dtype);
 
 /*
- * Tuning / test knobs (process-wide, not thread-safe against concurrent calls):
+ * Tuning / test knobs.  Process-wide; setting one is serialised with the calls
+ * that launch, so a change never lands in the middle of a launch.
  *   "spin_limit"   polls a look-back wave makes before giving up (default 1<<20)
- *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid
- *                  (0 = what the occupancy query allows; values above it are clamped)
- *   "waves"        wave64s per workgroup of the look-back kernel (one of them does the
- *                  look-back, the others hold the tile): 0 = the default for the type and
- *                  the input size (16 waves x 9 rows; for 4- and 8-byte elements 4 x 8 up
- *                  to 8 MiB and 8 x 8 up to 16 / 32 MiB of input), else 4, 8 or 16
+ *   "wgs_per_cu"   workgroups per compute unit of the persistent look-back grid:
+ *                  0 = what the runtime's occupancy query reports, else 1 .. 64.
+ *                  More than can be resident is safe (such grids take their tiles
+ *                  by ticket), only slower
+ *   "tickets"      how tiles get to workgroups: -1 = by index (workgroup b takes
+ *                  tiles b, b + grid, ...) for grids of up to one workgroup per
+ *                  compute unit, which is every default shape, and by ticket (a
+ *                  counter in the scratch) for larger grids; 1 = always by ticket:
+ *                  0-3 % slower on long inputs, more on short ones, but correct
+ *                  without a timeout however long other kernels hold the device
+ *   "waves"        wave64s per workgroup of the look-back kernel: 0 = the default for
+ *                  the type and the input size (16 waves, one of which only looks
+ *                  back, x 9 rows; for 4- and 8-byte elements 4 x 8 up to 8 MiB and
+ *                  8 x 8 up to 16 MiB of input), else 4, 8 or 16
  *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
- *                  default, else 4, 8, 9, 12 or 16.  A (waves, rows, prefetch) combination that
- *                  would not fit the register file for an element type makes the scan
- *                  call return KS_ERR_UNSUPPORTED
+ *                  default, else 4, 8, 9, 12 or 16.  A (waves, rows, prefetch, form)
+ *                  combination that is not compiled for an element type (it would not
+ *                  fit the register file or LDS) makes the scan call return
+ *                  KS_ERR_UNSUPPORTED
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
- *   "form"         16-wave shape only: 0 = one common loop for all waves, 1 = the
- *                  look-back wave and the data waves run loops of their own (fewer
- *                  registers, for wide element types), 2 = as 1, and every lane scans
- *                  consecutive elements after an exchange through LDS (rows 8 or 9),
- *                  3 = the common loop with two pauses that pay on long inputs (9 rows
- *                  with prefetch only), 4 and 5 = forms 0 and 3 with tiles that start on
- *                  128-byte lines of the output, which the library takes by itself for
- *                  output pointers that are not so aligned (forms 1 and 2 always do
- *                  this); -1 = the default for the pair, the input size and the pointers
- *   "grid_mode"    0 = persistent grid of resident workgroups (default); 1 = one
- *                  workgroup per tile, which is only deadlock-free if the hardware
- *                  starts workgroups in index order (experimental; waits stay bounded)
- *   "last_grid", "last_resident_per_cu"   read-only: grid of the most recent look-back
- *                  launch and the verified number of resident workgroups per compute
- *                  unit of its kernel variant
- *   "last_waves", "last_rows", "last_form"   read-only: shape and form that launch ran
- * Returns KS_OK or KS_ERR_INVALID_ARG.  ks_get_option returns the value or -1.
+ *   "form"         0 = one common loop for all waves (the 4- and 8-wave shapes), 1 = the
+ *                  look-back wave and the data waves run loops of their own, 2 = as 1,
+ *                  and every lane scans consecutive elements after an exchange through
+ *                  LDS, rows 8 or 9 (1 and 2: the 16-wave shape); -1 = the default for
+ *                  the pair and the input size.  A form that does not go with the
+ *                  wave count gives KS_ERR_UNSUPPORTED
+ * Read-only, per calling thread, what its most recent look-back launch ran:
+ *   "last_grid", "last_wgs_per_cu" (the occupancy figure behind the grid),
+ *   "last_waves", "last_rows", "last_form", "last_tickets"
+ * ks_set_option returns KS_OK or KS_ERR_INVALID_ARG; ks_get_option the value, or -1
+ * for an unknown name.
  */
 int ks_set_option(const char *name, long long value);
 long long ks_get_option(const char *name);

@@ -10,27 +10,31 @@
 
 namespace ks {
 
+// Process-wide tuning options.  Read and written under the library's mutex (every entry point that
+// launches holds it), so a change never lands in the middle of a launch.
 struct Options {
     long long spin_limit = 1ll << 20;
-    long long wgs_per_cu = 0;     // 0 = occupancy query
+    long long wgs_per_cu = 0;     // 0 = what the occupancy query gives, else 1 .. 64
     long long waves = 0;          // 0 = default for the type, else 4, 8 or 16 waves per workgroup
     long long rows = 0;           // 0 = default for the type, else 4, 8, 9, 12 or 16
     long long prefetch = -1;      // -1 = default, 0 / 1 forced
-    long long form = -1;          // -1 = default, else 0 common loop, 1 separate loops, 2 separate + blocked,
-                                  // 3 common loop with pauses, 4 / 5 = 0 / 3 with tiles on the output's
-                                  // 128-byte lines (1-5: 16 waves only; 3-5: 9 rows with prefetch only)
-    long long grid_mode = 0;      // 0 = persistent resident grid, 1 = one workgroup per tile (experimental)
-    long long last_grid = 0;      // read-only: workgroups of the most recent look-back launch
-    long long last_resident_per_cu = 0;   // read-only: verified resident workgroups per CU of that kernel variant
-    long long last_waves = 0, last_rows = 0, last_form = 0;   // read-only: shape and form of that launch
+    long long form = -1;          // -1 = default, else 0 common loop (4 and 8 waves), 1 separate loops,
+                                  // 2 separate loops + blocked arrangement (16 waves)
+    long long tickets = -1;       // tile assignment: -1 = by index for grids of up to one workgroup per compute
+                                  // unit, by ticket for larger ones; 1 = always by ticket
 };
 Options &options();
+
+// What the calling thread's most recent look-back launch ran (read-only "last_*" options).
+struct LastLaunch {
+    long long grid = 0, wgs_per_cu = 0, waves = 0, rows = 0, form = 0, tickets = 0;
+};
+LastLaunch &last_launch();
 
 struct DeviceInfo {
     int device = -1;
     int cus = 0;
-    uint32_t *abort_flag = nullptr;   // device address of the library's abort word on this device
-    uint32_t *residency = nullptr;    // two words used by the one-off residency check of a kernel variant
+    uint32_t *abort_table = nullptr;   // device address of the library's table of abort words on this device
 };
 
 struct ScanCall {
@@ -43,8 +47,10 @@ struct ScanCall {
     size_t temp_bytes;
     hipStream_t stream;
     uint32_t epoch;         // tag for this call's descriptors (look-back only)
-    bool clear_descriptors; // scratch contents unknown: zero the descriptors first
+    bool clear_descriptors; // scratch contents unknown: zero control block and descriptors first
     const DeviceInfo *dev;
+    uint32_t *abort_flag;   // abort word of the call's (device, stream)
+    uint32_t call_seq;      // sequence number of the call on its stream, never zero
     // strided views (paper Sec. IV-C): element i at in[i * in_stride] / out[i * out_stride]; always
     // the look-back algorithm, temp as for it
     size_t in_stride = 1, out_stride = 1;

@@ -90,24 +90,27 @@ __device__ __forceinline__ size_t xdesc_index(uint32_t tile, uint32_t m) {
 }
 
 // Bookkeeping of the bounded wait: every failed poll of a look-back wave counts
-// against `limit`; the abort word lets all workgroups stop once one has given up.
+// against `limit`.  A wave that gives up writes the call's sequence number (never
+// zero) into the abort word of the call's stream; the other workgroups of the same
+// call see it and stop as well, calls with another sequence number are not affected,
+// and the host's status call reports and clears whatever it finds there.
 struct SpinState {
     uint32_t spins;
     uint32_t limit;
     uint32_t *abort_flag;
-    uint32_t who;   // tile doing the waiting; the abort word receives who + 1
+    uint32_t call_seq;
 };
 
 __device__ __forceinline__ bool spin_once(SpinState &sp) {
     const int lane = threadIdx.x & (kWave - 1);
     ++sp.spins;
     if (sp.spins > sp.limit) {
-        if (lane == 0) __hip_atomic_store(sp.abort_flag, sp.who + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) __hip_atomic_store(sp.abort_flag, sp.call_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return false;
     }
-    if ((sp.spins & 63u) == 0) {   // has another workgroup given up?  (decided wave-uniformly)
+    if ((sp.spins & 63u) == 0) {   // has another workgroup of this call given up?  (decided wave-uniformly)
         const uint32_t f = __hip_atomic_load(sp.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (__ballot(f != 0) != 0) return false;
+        if (__ballot(f == sp.call_seq) != 0) return false;
     }
     __builtin_amdgcn_s_sleep(1);
     return true;
@@ -149,11 +152,11 @@ __device__ __forceinline__ bool poll_window(const uint64_t *desc, size_t base, l
 // tiles before `tile`, and X(tile) has been published in state PREFIX.
 template <class A, class Op>
 __device__ __forceinline__ bool lookback(const uint64_t *desc, uint64_t *xdesc, uint32_t m, uint32_t tile,
-                                         uint32_t epoch, uint32_t spin_limit, uint32_t *abort_flag,
+                                         uint32_t epoch, uint32_t spin_limit, uint32_t *abort_flag, uint32_t call_seq,
                                          A &exclusive_prefix) {
     const int lane = threadIdx.x & (kWave - 1);
     Op op;
-    SpinState sp{0u, spin_limit, abort_flag, tile};
+    SpinState sp{0u, spin_limit, abort_flag, call_seq};
     const size_t my_x = xdesc_index(tile, m);
     A running;
     bool done;
@@ -211,40 +214,100 @@ __device__ __forceinline__ int lane_tile_bytes(int dwave) {
     return (dwave * (kWave * ROWS) + lane) * 16;
 }
 
-// Do all workgroups of this launch run at the same time?  Each one counts itself
-// in residency[0] and waits, bounded, for the count to reach the grid size; a
-// workgroup that gives up sets residency[1].  Every wave of the workgroup stays
-// alive at the closing barrier until its thread 0 is done, so the workgroup
-// holds all of its registers and wave slots while it is counted.  The host uses
-// this once per kernel variant to size the persistent grid: the occupancy the
-// runtime reports can be higher than what the hardware grants (observed here: 8
-// workgroups per compute unit reported, 7 granted, for kernels with more than
-// 80 scalar registers), and a persistent grid larger than the resident set
-// would never finish its second round.
-__device__ __forceinline__ void residency_check(uint32_t *residency, uint32_t spin_limit) {
+// ---------------------------------------------------------------------------
+// Tile assignment.  The paper does not say how tiles get to workgroups (Sec. V-B);
+// what the look-back needs is that the tile a workgroup waits for is owned by a
+// workgroup that is running or will run without anybody's help.  Two ways:
+//
+//   by index    workgroup b takes tiles b, b + G, b + 2G, ... (G = grid size).  Safe as long as
+//               every workgroup of the grid gets to run while the others wait, which holds
+//               for G <= number of compute units: any compute unit can host one workgroup of
+//               any kernel, and whatever else occupies the device finishes without our help.
+//               The host uses it for exactly those grids, which covers every default shape
+//               (one 1024-thread workgroup per compute unit; small inputs have few tiles).
+//   by ticket   every tile, the first one included, comes from a counter in the call's
+//               scratch.  Tickets go up and a workgroup handles its tiles in increasing
+//               order, so the lowest unfinished tile always belongs to a running workgroup
+//               that waits for nobody, whatever the grid size and however few workgroups are
+//               resident.  Used for grids of more than one workgroup per compute unit (how
+//               many of those the hardware really grants is not known: the runtime's
+//               occupancy figure has been seen to say 8 where 7 ran), and on request.
+//
+// Tickets cost a little: all workgroups move in near lock-step, so their draws arrive in
+// bursts on one address (12 ns each: the last of 256 waits 3 us), and the order of the tiles
+// among neighbouring workgroups gets shuffled in every round, so a tile's predecessor is no
+// longer always a little ahead of it.  Float32 sum, by index / by ticket, TB/s: 2^28 6.44 / 6.45,
+// 2^26 6.14 / 6.04; arg-max struct 2^26 6.33 / 6.15.  Who draws matters more: a wave's vector memory
+// operations return in order, and when the look-back wave drew, its first poll of every round
+// waited behind the draw (float32 sum 2^28: 5.92).  So the first data wave draws, right before it
+// requests the next tile: the ticket comes back ahead of 135 KiB of loads that the wave waits
+// for anyway, and nobody ever waits for a ticket alone (except for the very first ones, at the
+// start of the kernel).
+//
+// Control block: the first 256 bytes of the scratch.  word 0: tickets drawn; word 1:
+// workgroups that have left.  Both are zero before a launch; the last workgroup to
+// leave puts them back to zero, so a library-owned scratch needs no clearing
+// between calls.
+// ---------------------------------------------------------------------------
+constexpr size_t kControlBytes = 256;
+constexpr uint32_t kNoTile = 0xffffffffu;
+
+// Issue a draw (one lane).
+__device__ __forceinline__ uint32_t draw_ticket(uint32_t *control) {
+    return __hip_atomic_fetch_add(&control[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Called by one lane of every workgroup of a launch by ticket, after its last draw has come back.
+__device__ __forceinline__ void leave_grid(uint32_t *control) {
+    const uint32_t before = __hip_atomic_fetch_add(&control[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (before + 1u == gridDim.x) {
+        __hip_atomic_store(&control[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&control[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Arguments of the look-back kernels that their loops pass around.
+struct LookbackArgs {
+    size_t n;
+    uint32_t *control;       // control block (above)
+    uint64_t *desc, *xdesc;
+    uint32_t epoch, ntiles, spin_limit;
+    uint32_t *abort_flag;    // abort word of the call's stream
+    uint32_t call_seq;       // what a wave that gives up writes there; never zero
+    uint32_t tickets;        // 0: tiles by index (grid <= tiles), 1: by ticket
+};
+
+// First tile of the calling workgroup (all threads call; kNoTile: nothing left, leave).
+__device__ __forceinline__ uint32_t first_tile(const LookbackArgs &a, uint32_t *s_first) {
+    if (!a.tickets) return blockIdx.x;
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(&residency[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (uint32_t spins = 0;; ++spins) {
-            if (__hip_atomic_load(&residency[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x) break;
-            if (spins >= spin_limit ||
-                __hip_atomic_load(&residency[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                __hip_atomic_store(&residency[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(8);
-        }
+        const uint32_t t = draw_ticket(a.control);
+        *s_first = t < a.ntiles ? t : kNoTile;
+        if (t >= a.ntiles) leave_grid(a.control);
     }
     __syncthreads();
+    return __builtin_amdgcn_readfirstlane(*s_first);
+}
+
+// By ticket, round r of a workgroup handles tile t_r between two barriers A(r) and B(r).  The
+// drawing wave (wave 1, lane 0) issues the draw of t_(r+1) in round r - 1, just before its loads
+// of t_r, has the value when those loads are back at the top of round r, and writes it to
+// next_tile before A(r); every wave reads it between A(r) and B(r).  The write for the round
+// after comes after B(r).
+struct TileQueue {
+    uint32_t next_tile;
+};
+constexpr int kDrawingWave = 1;
+
+// The tile after `tile`, read between the two barriers of a round (>= ntiles: none).
+__device__ __forceinline__ uint32_t next_tile_of(const LookbackArgs &a, const TileQueue &q, uint32_t tile) {
+    return a.tickets ? __builtin_amdgcn_readfirstlane(q.next_tile) : tile + gridDim.x;
 }
 
 // ---------------------------------------------------------------------------
-// Single-pass scan.  The grid is persistent: workgroup b handles tiles b,
-// b + gridDim.x, ... in increasing order, and the host launches no more
-// workgroups than can be resident at once, so the tile a workgroup waits for is
-// always owned by a workgroup that is running (the paper does not say how tiles
-// are assigned; this removes any reliance on dispatch order without a ticket
-// atomic per tile: one device-scope atomic on a single address costs 12 ns here,
-// more than a tile's share of the run time).  Every wait is bounded by spin_limit.
+// Single-pass scan.  The grid is persistent, about as many workgroups as fit the
+// device, each taking tiles until none are left (tile assignment: above).  Every
+// wait is bounded by spin_limit.
 //
 // IO = element type in memory, Op::acc = type of the registers, ChainOf<Op>::type = type of
 // wave totals once they leave the wave, of aggregates and of descriptors.
@@ -278,6 +341,8 @@ struct TileExchange {
     typename WordsOf<C>::type carry[WAVES];   // per wave: combination of the runs before it (separate loops)
     typename WordsOf<C>::type prefix;         // exclusive prefix of the tile, from the look-back
     uint32_t ok;                              // 0: a wait was abandoned, everybody leaves
+    TileQueue q;
+    uint32_t first;
 };
 
 // Two pauses after the barrier that hands the wave totals over, in units of 64 cycles (s_sleep).
@@ -336,14 +401,6 @@ __device__ __forceinline__ size_t shifted_elems(uint32_t t, size_t shift, size_t
     return t ? tile_elems : tile_elems - shift;
 }
 
-// Arguments of the look-back kernel that its loops pass around.
-struct LookbackArgs {
-    size_t n;
-    uint64_t *desc, *xdesc;
-    uint32_t epoch, ntiles, spin_limit;
-    uint32_t *abort_flag;
-};
-
 // First thing wave 0 does once the tile's aggregate is known: successors only
 // need the aggregate, so it goes out before anything else is queued.
 template <class A, class Op>
@@ -367,7 +424,7 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
     A excl = Op::identity();
     bool ok = true;
     if (tile != 0) {
-        ok = lookback<A, Op>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, excl);
+        ok = lookback<A, Op>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
         if (ok && lane == 0) desc_publish<A>(a.desc, tile, a.epoch, kPrefix, op(excl, aggregate));
     }
     if (lane == 0) {
@@ -383,16 +440,17 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
 // same number of barriers per tile and leave together.
 template <class Op, int WAVES, bool PREFETCH>
 __device__ __forceinline__ void lookback_wave_loop(
-    const LookbackArgs &a, TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
+    const LookbackArgs &a, TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, uint32_t first) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
     COp op;
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t m = (a.ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
-    for (uint32_t loop_tile = blockIdx.x;;) {
-        const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
+    uint32_t tile = first;
+    for (;;) {
         __syncthreads();
+        const uint32_t next = next_tile_of(a, x.q, tile);
         C mine = COp::identity();
         if (lane < WAVES - 1) mine = convert<C>(from_words<A>(x.tot[lane + 1]));
         const C upto = wave_inclusive_scan(mine, op);
@@ -400,13 +458,12 @@ __device__ __forceinline__ void lookback_wave_loop(
         const C before = wave_shift_up(upto, COp::identity());
         if (lane < WAVES - 1) x.carry[lane + 1] = to_words(before);
         publish_aggregate<C, COp>(a, tile, aggregate);
-        if (PREFETCH && tile + gridDim.x < a.ntiles) __builtin_amdgcn_s_sleep(poll_delay<A>());   // while the data waves hold
+        if (PREFETCH && next < a.ntiles) __builtin_amdgcn_s_sleep(poll_delay<A>());   // while the data waves hold
         resolve_prefix<C, COp>(a, tile, m, aggregate, x);
         __syncthreads();
         if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
-        const uint32_t next = tile + gridDim.x;
         if (next >= a.ntiles) return;
-        loop_tile = next;
+        tile = next;
     }
 }
 
@@ -417,7 +474,7 @@ __device__ __forceinline__ void lookback_wave_loop(
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
 __device__ __forceinline__ void data_wave_loop(
     const IO *in, IO *out, const LookbackArgs &a,
-    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
+    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, uint32_t first) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     typename ChainOf<Op>::op cop;
@@ -431,13 +488,18 @@ __device__ __forceinline__ void data_wave_loop(
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;   // 1 .. WAVES-1
     const int lane_bytes = lane_tile_bytes<ROWS>(wave - 1);
+    const bool drawing = a.tickets && wave == kDrawingWave && lane == 0;
+    uint32_t drawn = 0;   // drawing lane: the ticket of the tile after the one in `cur`
+    if (drawing) drawn = draw_ticket(a.control);
     ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op, PIN>(tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE)), lane_bytes,
-                             blockIdx.x + 1 == a.ntiles || (blockIdx.x == 0 && shift != 0), cur);
-    for (uint32_t loop_tile = blockIdx.x;;) {
+    load_items<IO, ROWS, Op, PIN>(tile_window<IO>(in, a.n, shifted_first(first, shift, TILE), shifted_elems(first, shift, TILE)), lane_bytes,
+                             first + 1 == a.ntiles || (first == 0 && shift != 0), cur);
+    uint32_t loop_tile = first;
+    for (;;) {
         // The tile index is the same in every lane; saying so keeps it, and the buffer resources
         // derived from it, in scalar registers.
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);
+        if (drawing) x.q.next_tile = drawn;
         // Commutative operators: the run's total first, by the shortest route, and the scan itself
         // after the barrier (see reduce_wave_run_any_order).  From the scan on `cur` holds the scan
         // of the wave's run alone.
@@ -452,7 +514,8 @@ __device__ __forceinline__ void data_wave_loop(
         // The next tile is requested only now, after the totals are out: requested before the scan
         // (the registers would be free) it measured 5-12 % slower, the descriptor traffic of the
         // look-back wave then queues behind 135 KiB of loads in this compute unit's memory pipeline.
-        const uint32_t next = tile + gridDim.x;
+        const uint32_t next = next_tile_of(a, x.q, tile);
+        if (drawing && next < a.ntiles) drawn = draw_ticket(a.control);   // no draw once one has failed
         RawItems<ROWS> nxt;
         TileWindow wnext;
         if (PREFETCH && next < a.ntiles) {
@@ -462,11 +525,11 @@ __device__ __forceinline__ void data_wave_loop(
         }
         if constexpr (Op::commutative) (void)scan_wave_run_in_place<INCLUSIVE, A, ROWS, S::G, Op>(cur, op);
         __syncthreads();
-        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) break;
         const A prefix = convert<A>(cop(from_words<C>(x.prefix), from_words<C>(x.carry[wave])));
         apply_prefix_and_store<IO, ROWS, A, Op, PIN>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, cur,
                                                 prefix, op);
-        if (next >= a.ntiles) return;
+        if (next >= a.ntiles) break;
         loop_tile = next;
         if (PREFETCH) {
             unpack_items<IO, ROWS, Op, PIN>(nxt, lane_bytes, wnext.valid_bytes, next + 1 == a.ntiles, cur);
@@ -475,6 +538,7 @@ __device__ __forceinline__ void data_wave_loop(
                                      next + 1 == a.ntiles, cur);
         }
     }
+    if (drawing) leave_grid(a.control);   // `drawn` has been used: the last draw is back
 }
 
 // The data waves of the 16-wave shape in the blocked arrangement (ks_tile.hpp):
@@ -484,7 +548,7 @@ __device__ __forceinline__ void data_wave_loop(
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
 __device__ __forceinline__ void blocked_data_wave_loop(
     const IO *in, IO *out, const LookbackArgs &a,
-    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, u32x4 *stage) {
+    TileExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, u32x4 *stage, uint32_t first) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     typename ChainOf<Op>::op cop;
@@ -501,15 +565,20 @@ __device__ __forceinline__ void blocked_data_wave_loop(
     // data_wave_loop.  (Requested before the scan, which looked best for 16-byte elements while
     // nothing kept the request from overtaking the look-back's polls, it measures 8-11 % below
     // the held request: arg-max struct 5.59 against 6.05 TB/s.)
+    const bool drawing = a.tickets && wave == kDrawingWave && lane == 0;   // see data_wave_loop
+    uint32_t drawn = 0;
+    if (drawing) drawn = draw_ticket(a.control);
     RawItems<ROWS> raw;
     uint32_t valid_bytes;
     {
-        const TileWindow w = tile_window<IO>(in, a.n, shifted_first(blockIdx.x, shift, TILE), shifted_elems(blockIdx.x, shift, TILE));
+        const TileWindow w = tile_window<IO>(in, a.n, shifted_first(first, shift, TILE), shifted_elems(first, shift, TILE));
         load_raw<ROWS, true>(w, lane_bytes, raw);
         valid_bytes = w.valid_bytes;
     }
-    for (uint32_t loop_tile = blockIdx.x;;) {
+    uint32_t loop_tile = first;
+    for (;;) {
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);   // see data_wave_loop
+        if (drawing) x.q.next_tile = drawn;
         ThreadItems<A, ROWS, S::G> cur;
         A lane_before;
         striped_to_blocked<ROWS>(region, raw);
@@ -517,21 +586,22 @@ __device__ __forceinline__ void blocked_data_wave_loop(
         const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
-        if (PREFETCH && tile + gridDim.x < a.ntiles) {
+        const uint32_t next = next_tile_of(a, x.q, tile);
+        if (drawing && next < a.ntiles) drawn = draw_ticket(a.control);
+        if (PREFETCH && next < a.ntiles) {
             __builtin_amdgcn_s_sleep(prefetch_hold<A>());
-            const TileWindow w = tile_window<IO>(in, a.n, (size_t)(tile + gridDim.x) * TILE - shift, TILE);
+            const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
             load_raw<ROWS, true>(w, lane_bytes, raw);
             valid_bytes = w.valid_bytes;
         }
-        const uint32_t next = tile + gridDim.x;
         __syncthreads();
-        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) return;
+        if (__builtin_amdgcn_readfirstlane(x.ok) == 0u) break;
         const A before = op(convert<A>(cop(from_words<C>(x.prefix), from_words<C>(x.carry[wave]))), lane_before);
         RawItems<ROWS> result;
         apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
         blocked_to_striped<ROWS>(region, result);
         store_raw<ROWS, true>(tile_window<IO>(out, a.n, shifted_first(tile, shift, TILE), shifted_elems(tile, shift, TILE)), lane_bytes, result);
-        if (next >= a.ntiles) return;
+        if (next >= a.ntiles) break;
         loop_tile = next;
         if (!PREFETCH) {
             const TileWindow w = tile_window<IO>(in, a.n, (size_t)next * TILE - shift, TILE);
@@ -539,6 +609,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(
             valid_bytes = w.valid_bytes;
         }
     }
+    if (drawing) leave_grid(a.control);
 }
 
 // What the waves share in the common loop.
@@ -547,15 +618,16 @@ struct CommonExchange {
     typename WordsOf<A>::type tot[WAVES];
     typename WordsOf<C>::type prefix;
     uint32_t ok;
+    TileQueue q;
+    uint32_t first;
 };
 
 // One loop for all waves (the 4- and 8-wave shapes): every wave holds data and
-// wave 0 looks back as well.
+// wave 0 looks back as well; wave 1 draws the tickets.
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH>
 __device__ __forceinline__ void common_wave_loop(
-    const IO *in, IO *out, size_t n, uint64_t *desc, uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
-    uint32_t spin_limit, uint32_t *abort_flag,
-    CommonExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x) {
+    const IO *in, IO *out, const LookbackArgs &a,
+    CommonExchange<typename Op::acc, typename ChainOf<Op>::type, WAVES> &x, uint32_t first) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
@@ -568,34 +640,40 @@ __device__ __forceinline__ void common_wave_loop(
     const int wave = threadIdx.x >> 6;
     const bool lookback_wave = wave == 0;
     const int lane_bytes = lane_tile_bytes<ROWS>(wave);
+    const uint32_t m = (a.ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
 
-    uint32_t tile = blockIdx.x;
-    const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
+    uint32_t tile = first;
+    const bool drawing = a.tickets && wave == kDrawingWave && lane == 0;   // see data_wave_loop
+    uint32_t drawn = 0;
+    if (drawing) drawn = draw_ticket(a.control);
     Items cur;
-    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == ntiles, cur);
+    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, a.n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == a.ntiles, cur);
     for (;;) {
+        if (drawing) x.q.next_tile = drawn;
         WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
         C aggregate;
         const C wave_carry = exchange_wave_totals<Op, WAVES>(x.tot, ws.wave_total, aggregate);
 
         // publish as early as possible: successors only need the aggregate
         if (lookback_wave && lane == 0) {
-            desc_publish<C>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
-            if (tile == 0) desc_publish<C>(xdesc, 0, epoch, kPrefix, COp::identity());   // nothing before tile 0
+            desc_publish<C>(a.desc, tile, a.epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+            if (tile == 0) desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, COp::identity());   // nothing before tile 0
         }
-        const uint32_t next = tile + gridDim.x;
+        const uint32_t next = next_tile_of(a, x.q, tile);
+        const bool more = next < a.ntiles;
+        if (drawing && more) drawn = draw_ticket(a.control);   // no draw once one has failed
         RawItems<ROWS> nxt;
         TileWindow wnext;
-        if (PREFETCH && next < ntiles) {
-            wnext = tile_window<IO>(in, n, (size_t)next * TILE, TILE);
+        if (PREFETCH && more) {
+            wnext = tile_window<IO>(in, a.n, (size_t)next * TILE, TILE);
             load_raw<ROWS, false>(wnext, lane_bytes, nxt);
         }
         if (lookback_wave) {
             C excl = COp::identity();
             bool ok = true;
             if (tile != 0) {
-                ok = lookback<C, COp>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
-                if (ok && lane == 0) desc_publish<C>(desc, tile, epoch, kPrefix, cop(excl, aggregate));
+                ok = lookback<C, COp>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
+                if (ok && lane == 0) desc_publish<C>(a.desc, tile, a.epoch, kPrefix, cop(excl, aggregate));
             }
             if (lane == 0) {
                 x.prefix = to_words(excl);
@@ -603,19 +681,20 @@ __device__ __forceinline__ void common_wave_loop(
             }
         }
         __syncthreads();
-        if (x.ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
+        if (x.ok == 0u) break;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
 
         const A prefix = convert<A>(cop(from_words<C>(x.prefix), wave_carry));
         finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
-        apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, (size_t)tile * TILE, TILE), lane_bytes, cur,
+        apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, a.n, (size_t)tile * TILE, TILE), lane_bytes, cur,
                                                        prefix, op);
-        if (next >= ntiles) break;
+        if (!more) break;
         tile = next;
         if (PREFETCH)
-            unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == ntiles, cur);
+            unpack_items<IO, ROWS, Op, false>(nxt, lane_bytes, wnext.valid_bytes, tile + 1 == a.ntiles, cur);
         else
-            load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == ntiles, cur);
+            load_items<IO, ROWS, Op, false>(tile_window<IO>(in, a.n, (size_t)tile * TILE, TILE), lane_bytes, tile + 1 == a.ntiles, cur);
     }
+    if (drawing) leave_grid(a.control);
 }
 
 // Staggered start (16-wave shape, one workgroup per compute unit).  Left alone, all workgroups
@@ -631,9 +710,9 @@ __device__ __forceinline__ void common_wave_loop(
 constexpr uint32_t kStartStagger = 150;
 constexpr uint32_t kStaggerFromRounds = 3;
 
-__device__ __forceinline__ void stagger_start(uint32_t ntiles) {
+__device__ __forceinline__ void stagger_start(uint32_t ntiles, uint32_t first) {
     if (ntiles < kStaggerFromRounds * gridDim.x) return;
-    const uint32_t pauses = blockIdx.x * kStartStagger / gridDim.x;
+    const uint32_t pauses = (first % gridDim.x) * kStartStagger / gridDim.x;   // first: the workgroup's first tile
     for (uint32_t i = 0; i < pauses; ++i) __builtin_amdgcn_s_sleep(1);
 }
 
@@ -646,39 +725,32 @@ constexpr int kFormCount = 3;
 constexpr bool aligns_output(int waves) { return dedicated_lookback_wave(waves); }
 
 template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
-__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out,
-                                                                     size_t n, uint64_t *desc, uint64_t *xdesc,
-                                                                     uint32_t epoch, uint32_t ntiles,
-                                                                     uint32_t spin_limit, uint32_t *abort_flag,
-                                                                     uint32_t *residency) {
-    if (residency) {   // residency check of this very kernel (same registers, same LDS): no scan work
-        residency_check(residency, spin_limit);
-        return;
-    }
+__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *in, IO *out, LookbackArgs a) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     static_assert(dedicated_lookback_wave(WAVES) == (FORM != kFormCommon), "16 waves run separate loops, 4 and 8 the common one");
-    if (blockIdx.x >= ntiles) return;
     if constexpr (dedicated_lookback_wave(WAVES)) {
-        stagger_start(ntiles);
         __shared__ TileExchange<A, C, WAVES> x;
-        const LookbackArgs a{n, desc, xdesc, epoch, ntiles, spin_limit, abort_flag};
+        const uint32_t first = first_tile(a, &x.first);
+        if (first == kNoTile) return;
+        stagger_start(a.ntiles, first);
         if constexpr (FORM == kFormBlocked) {
             __shared__ u32x4 stage[(WAVES - 1) * Stage<ROWS>::SLOTS];
             if (threadIdx.x < kWave)
-                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x);
+                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x, first);
             else
-                blocked_data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, stage);
+                blocked_data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, stage, first);
         } else {
             if (threadIdx.x < kWave)
-                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x);
+                lookback_wave_loop<Op, WAVES, PREFETCH>(a, x, first);
             else
-                data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x);
+                data_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, first);
         }
     } else {
         __shared__ CommonExchange<A, C, WAVES> x;
-        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, n, desc, xdesc, epoch, ntiles, spin_limit,
-                                                                   abort_flag, x);
+        const uint32_t first = first_tile(a, &x.first);
+        if (first == kNoTile) return;
+        common_wave_loop<IO, Op, WAVES, ROWS, INCLUSIVE, PREFETCH>(in, out, a, x, first);
     }
 }
 
@@ -738,56 +810,57 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out
 // per compute unit keep more of them in flight than one large one.
 template <class IO, class Op, int ROWS, bool INCLUSIVE>
 __global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO *in, size_t in_stride, IO *out,
-                                                                       size_t out_stride, size_t n, uint64_t *desc,
-                                                                       uint64_t *xdesc, uint32_t epoch, uint32_t ntiles,
-                                                                       uint32_t spin_limit, uint32_t *abort_flag,
-                                                                       uint32_t *residency) {
-    if (residency) {   // residency check of this very kernel: no scan work
-        residency_check(residency, spin_limit);
-        return;
-    }
+                                                                       size_t out_stride, LookbackArgs a) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
     constexpr size_t WAVE_ELEMS = (size_t)kWave * ROWS;   // one-element granules
     constexpr size_t TILE = (size_t)kWaves * WAVE_ELEMS;
-    __shared__ typename WordsOf<A>::type s_tot[kWaves];
-    __shared__ typename WordsOf<C>::type s_prefix;
-    __shared__ uint32_t s_ok;
+    __shared__ CommonExchange<A, C, kWaves> x;
     Op op;
     COp cop;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const uint32_t m = (ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
-    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const uint32_t m = (a.ntiles + kWindow - 1) / kWindow;   // row length of the transposed X array
+    uint32_t tile = first_tile(a, &x.first);
+    if (tile == kNoTile) return;
+    for (;;) {
         const size_t run_first = (size_t)tile * TILE + (size_t)wave * WAVE_ELEMS;
         ThreadItems<A, ROWS, 1> cur;
-        load_items_strided<IO, ROWS, Op>(in, in_stride, n, run_first, cur);
+        load_items_strided<IO, ROWS, Op>(in, in_stride, a.n, run_first, cur);
         const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, 1, Op>(cur, op);
         C aggregate;
-        const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
+        const C wave_carry = exchange_wave_totals<Op, kWaves>(x.tot, ws.wave_total, aggregate);
+        // no prefetch here: the next tile is only needed after the closing barrier; wave 1 draws it
+        // now and has it long before wave 0 is back from the look-back
+        if (a.tickets && wave == kDrawingWave && lane == 0) x.q.next_tile = draw_ticket(a.control);
         if (wave == 0) {
             if (lane == 0) {
-                desc_publish<C>(desc, tile, epoch, tile == 0 ? kPrefix : kPartial, aggregate);
-                if (tile == 0) desc_publish<C>(xdesc, 0, epoch, kPrefix, COp::identity());   // nothing before tile 0
+                desc_publish<C>(a.desc, tile, a.epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+                if (tile == 0) desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, COp::identity());   // nothing before tile 0
             }
             C excl = COp::identity();
             bool ok = true;
             if (tile != 0) {
-                ok = lookback<C, COp>(desc, xdesc, m, tile, epoch, spin_limit, abort_flag, excl);
-                if (ok && lane == 0) desc_publish<C>(desc, tile, epoch, kPrefix, cop(excl, aggregate));
+                ok = lookback<C, COp>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
+                if (ok && lane == 0) desc_publish<C>(a.desc, tile, a.epoch, kPrefix, cop(excl, aggregate));
             }
             if (lane == 0) {
-                s_prefix = to_words(excl);
-                s_ok = ok ? 1u : 0u;
+                x.prefix = to_words(excl);
+                x.ok = ok ? 1u : 0u;
             }
         }
         __syncthreads();
-        if (s_ok == 0u) return;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
-        const A prefix = convert<A>(cop(from_words<C>(s_prefix), wave_carry));
+        if (x.ok == 0u) break;   // a wait was abandoned: the host reports KS_ERR_TIMEOUT
+        const A prefix = convert<A>(cop(from_words<C>(x.prefix), wave_carry));
         finish_wave_run<INCLUSIVE, A, ROWS, 1, Op>(cur, ws, op);
-        apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, n, run_first, cur, prefix, op);
+        apply_prefix_and_store_strided<IO, ROWS, A, Op>(out, out_stride, a.n, run_first, cur, prefix, op);
+        // next_tile is written between the two barriers of a round and read after the second one;
+        // the next write comes after the first barrier of the next round (inside exchange_wave_totals)
+        tile = next_tile_of(a, x.q, tile);
+        if (tile >= a.ntiles) break;
     }
+    if (a.tickets && threadIdx.x == kDrawingWave * kWave) leave_grid(a.control);
 }
 
 template <int UNUSED = 0>

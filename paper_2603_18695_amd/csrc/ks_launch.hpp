@@ -183,7 +183,7 @@ struct Pair {
             // sized for the smallest tile any compiled variant uses, so a later change of the
             // shape options cannot outgrow a buffer sized earlier
             const size_t tiles = ceil_div(n, (size_t)kMinTileGranules * (16 / sizeof(T)));
-            return desc_bytes(tiles) + desc_bytes(ceil_div(tiles, kWindow) * kWindow);
+            return lookback_scratch_bytes(tiles + 1);   // + 1: tile 0 may be cut short (output-aligned tiles)
         }
         size_t total = 0, m = n;
         const size_t tile = tile_elems(kRtsRows);
@@ -197,59 +197,65 @@ struct Pair {
     }
 
     // ---- look-back ---------------------------------------------------------
-    // Resident workgroups per compute unit of one kernel variant on the call's device.  The runtime's
-    // occupancy query is an upper bound only; the kernel is run in its residency-check mode
-    // (launch_check(grid)) and the count stepped down until every workgroup of the grid is seen
-    // running at once.  One-off per variant and device; it synchronises the stream.
-    template <class Kernel, class LaunchCheck>
-    static int verified_residency(const ScanCall &c, std::map<int, int> &cache, Kernel kernel, int threads, int &per_cu,
-                                  LaunchCheck launch_check) {
+    // Scratch of a look-back call: control block, D descriptors, X descriptors.
+    static size_t lookback_scratch_bytes(size_t tiles) {
+        return kControlBytes + desc_bytes(tiles) + desc_bytes(ceil_div(tiles, kWindow) * kWindow);
+    }
+
+    // Workgroups per compute unit the runtime reports for a kernel variant, per device.  It can be
+    // higher than what the hardware grants; with tickets that only means some workgroups start late.
+    template <class Kernel>
+    static int occupancy(const ScanCall &c, std::map<int, int> &cache, Kernel kernel, int threads, int &per_cu) {
         int &known = cache[c.dev->device];
         if (known == 0) {
             int nb = 0;
             hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, threads, 0);
             if (e != hipSuccess) return set_hip_error(e);
-            int verified = 0;
-            for (int tryb = nb; tryb >= 1 && !verified; --tryb) {
-                uint32_t zero[2] = {0u, 0u};
-                e = hipMemcpyAsync(c.dev->residency, zero, sizeof(zero), hipMemcpyHostToDevice, c.stream);
-                if (e != hipSuccess) return set_hip_error(e);
-                launch_check((unsigned)(tryb * c.dev->cus));
-                if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e);
-                uint32_t seen[2] = {0u, 1u};
-                e = hipMemcpyAsync(seen, c.dev->residency, sizeof(seen), hipMemcpyDeviceToHost, c.stream);
-                if (e != hipSuccess) return set_hip_error(e);
-                if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return set_hip_error(e);
-                if (seen[1] == 0u) verified = tryb;
-            }
-            if (verified < 1) return KS_ERR_WORKSPACE;
-            known = verified;
+            known = nb > 0 ? nb : 1;
         }
         per_cu = known;
         return KS_OK;
     }
 
-    // grid of a persistent look-back launch and the cleared descriptor arrays for `tiles` tiles
-    static size_t persistent_grid(const ScanCall &c, int per_cu, size_t tiles) {
-        long long want = options().wgs_per_cu;
-        int use = (want > 0 && want < per_cu) ? (int)want : per_cu;
+    // grid of a persistent look-back launch, and whether first tiles come from tickets as well
+    static size_t persistent_grid(const ScanCall &c, int per_cu, size_t tiles, uint32_t &tickets) {
+        const long long want = options().wgs_per_cu;
+        const int use = want > 0 ? (int)(want < 64 ? want : 64) : per_cu;
         size_t grid = (size_t)use * (size_t)c.dev->cus;
-        if (options().grid_mode == 1 || grid > tiles) grid = tiles;
-        options().last_grid = (long long)grid;
-        options().last_resident_per_cu = per_cu;
+        if (grid > tiles) grid = tiles;
+        // up to one workgroup per compute unit every workgroup is sure to run, whatever else the
+        // device is doing: tiles by index (see "Tile assignment" in ks_kernels.hpp)
+        tickets = grid > (size_t)c.dev->cus || options().tickets == 1 ? 1u : 0u;
+        LastLaunch &l = last_launch();
+        l.grid = (long long)grid;
+        l.wgs_per_cu = per_cu;
+        l.tickets = tickets;
         return grid;
     }
-    static void clear_descriptors_if_asked(const ScanCall &c, uint64_t *desc, size_t tiles, size_t xentries) {
-        if (!c.clear_descriptors) return;
-        const size_t words = (desc_bytes(tiles) + desc_bytes(xentries)) / sizeof(uint64_t);
-        const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
-        hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, desc, words);
-    }
-    static uint32_t spin_limit_option() {
+    // Fills in everything of the kernel's arguments that the data pointers do not cover; clears the
+    // scratch first if its contents are unknown.
+    static LookbackArgs lookback_args(const ScanCall &c, size_t tiles, uint32_t tickets) {
+        char *base = static_cast<char *>(c.temp);
+        if (c.clear_descriptors) {
+            const size_t words = lookback_scratch_bytes(tiles) / sizeof(uint64_t);
+            const unsigned fb = (unsigned)(ceil_div(words, 256) < 1024 ? ceil_div(words, 256) : 1024);
+            hipLaunchKernelGGL((fill_zero_kernel<0>), dim3(fb), dim3(256), 0, c.stream, reinterpret_cast<uint64_t *>(base), words);
+        }
+        LookbackArgs a;
+        a.n = c.n;
+        a.control = reinterpret_cast<uint32_t *>(base);
+        a.desc = reinterpret_cast<uint64_t *>(base + kControlBytes);
+        a.xdesc = a.desc + desc_bytes(tiles) / sizeof(uint64_t);
+        a.epoch = c.epoch;
+        a.ntiles = (uint32_t)tiles;
         long long spin = options().spin_limit;
         if (spin < 0) spin = 0;
         if (spin > 0xffffffffll) spin = 0xffffffffll;
-        return (uint32_t)spin;
+        a.spin_limit = (uint32_t)spin;
+        a.abort_flag = c.abort_flag;
+        a.call_seq = c.call_seq;
+        a.tickets = tickets;
+        return a;
     }
 
     template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
@@ -264,29 +270,21 @@ struct Pair {
                                      ? tile_shift(static_cast<const T *>(c.out), shape_tile_elems(WAVES, ROWS))
                                      : 0;
             const size_t tiles = ceil_div(c.n + shift, shape_tile_elems(WAVES, ROWS));
-            const size_t xentries = ceil_div(tiles, kWindow) * kWindow;   // transposed second-level array, 64 rows
-            if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
-            // resident workgroups per compute unit of this variant, per device
-            static std::map<int, int> verified_per_cu;
+            if (tiles >= 0xfffffff0ull) return KS_ERR_INVALID_ARG;   // tile indices and tickets are 32-bit
+            if (lookback_scratch_bytes(tiles) > c.temp_bytes) return KS_ERR_WORKSPACE;
+            static std::map<int, int> reported_per_cu;
             int per_cu = 0;
-            const int vs = verified_residency(c, verified_per_cu, kernel, kThreads, per_cu, [&](unsigned grid) {
-                hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, c.stream, static_cast<const T *>(nullptr),
-                                   static_cast<T *>(nullptr), (size_t)0, static_cast<uint64_t *>(nullptr),
-                                   static_cast<uint64_t *>(nullptr), 0u, 0u, (uint32_t)(1u << 16), c.dev->abort_flag,
-                                   c.dev->residency);
-            });
-            if (vs != KS_OK) return vs;
-            const size_t grid = persistent_grid(c, per_cu, tiles);
-            options().last_waves = WAVES;
-            options().last_rows = ROWS;
-            options().last_form = FORM;
-            uint64_t *desc = static_cast<uint64_t *>(c.temp);
-            uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
-            clear_descriptors_if_asked(c, desc, tiles, xentries);
-            const uint32_t spin = spin_limit_option();
+            const int os = occupancy(c, reported_per_cu, kernel, kThreads, per_cu);
+            if (os != KS_OK) return os;
+            uint32_t tickets = 0;
+            const size_t grid = persistent_grid(c, per_cu, tiles, tickets);
+            LastLaunch &l = last_launch();
+            l.waves = WAVES;
+            l.rows = ROWS;
+            l.form = FORM;
+            const LookbackArgs a = lookback_args(c, tiles, tickets);
             hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream,
-                               static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n, desc, xdesc, c.epoch,
-                               (uint32_t)tiles, spin, c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
+                               static_cast<const T *>(c.in), static_cast<T *>(c.out), a);
             hipError_t e = hipGetLastError();
             return e == hipSuccess ? KS_OK : set_hip_error(e);
         }
@@ -384,27 +382,21 @@ struct Pair {
     static int launch_lookback_strided(const ScanCall &c) {
         auto kernel = scan_lookback_strided_kernel<T, Op, kStridedRows, INCLUSIVE>;
         const size_t tiles = ceil_div(c.n, kStridedTile);
-        const size_t xentries = ceil_div(tiles, kWindow) * kWindow;
-        if (desc_bytes(tiles) + desc_bytes(xentries) > c.temp_bytes) return KS_ERR_WORKSPACE;
-        static std::map<int, int> verified_per_cu;
+        if (tiles >= 0xfffffff0ull) return KS_ERR_INVALID_ARG;
+        if (lookback_scratch_bytes(tiles) > c.temp_bytes) return KS_ERR_WORKSPACE;
+        static std::map<int, int> reported_per_cu;
         int per_cu = 0;
-        const int vs = verified_residency(c, verified_per_cu, kernel, kBlock, per_cu, [&](unsigned grid) {
-            hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(nullptr), (size_t)1,
-                               static_cast<T *>(nullptr), (size_t)1, (size_t)0, static_cast<uint64_t *>(nullptr),
-                               static_cast<uint64_t *>(nullptr), 0u, 0u, (uint32_t)(1u << 16), c.dev->abort_flag,
-                               c.dev->residency);
-        });
-        if (vs != KS_OK) return vs;
-        const size_t grid = persistent_grid(c, per_cu, tiles);
-        options().last_waves = kWaves;
-        options().last_rows = kStridedRows;
-        options().last_form = kFormCommon;
-        uint64_t *desc = static_cast<uint64_t *>(c.temp);
-        uint64_t *xdesc = desc + desc_bytes(tiles) / sizeof(uint64_t);
-        clear_descriptors_if_asked(c, desc, tiles, xentries);
+        const int os = occupancy(c, reported_per_cu, kernel, kBlock, per_cu);
+        if (os != KS_OK) return os;
+        uint32_t tickets = 0;
+        const size_t grid = persistent_grid(c, per_cu, tiles, tickets);
+        LastLaunch &l = last_launch();
+        l.waves = kWaves;
+        l.rows = kStridedRows;
+        l.form = kFormCommon;
+        const LookbackArgs a = lookback_args(c, tiles, tickets);
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
-                           c.in_stride, static_cast<T *>(c.out), c.out_stride, c.n, desc, xdesc, c.epoch,
-                           (uint32_t)tiles, spin_limit_option(), c.dev->abort_flag, static_cast<uint32_t *>(nullptr));
+                           c.in_stride, static_cast<T *>(c.out), c.out_stride, a);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
     }

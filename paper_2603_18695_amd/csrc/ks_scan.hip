@@ -13,10 +13,11 @@
 
 namespace ks {
 
-// Set by a look-back wave that exhausted its spin limit; one word per device.
-__device__ uint32_t g_abort_flag;
-// {workgroups counted, gave-up flag} of a residency check.
-__device__ uint32_t g_residency[2];
+// Abort words: one per (device, stream) that has run a look-back scan, handed out in order of first
+// use.  A look-back wave that exhausts its spin limit writes its call's sequence number there.
+// Static device memory, so that handing out a slot allocates nothing.
+constexpr int kAbortSlots = 1024;
+__device__ uint32_t g_abort_table[kAbortSlots];
 
 const PairEntry *pair_entry_i32(int, int);
 const PairEntry *pair_entry_i64(int, int);
@@ -36,6 +37,10 @@ Options &options() {
     static Options o;
     return o;
 }
+LastLaunch &last_launch() {
+    static thread_local LastLaunch l;
+    return l;
+}
 
 static thread_local int t_last_hip = 0;
 int set_hip_error(hipError_t e) {
@@ -48,14 +53,23 @@ namespace {
 std::mutex g_mutex;
 std::map<int, DeviceInfo> g_devices;
 
-struct Workspace {
+// Per (device, stream): the library-owned scratch of ks_scan, the stream's abort word and the
+// sequence number of its calls.
+struct StreamState {
     void *ptr = nullptr;
     size_t bytes = 0;
-    uint32_t epoch = 0;   // last epoch handed out; descriptors carry (epoch << 2 | state)
+    uint32_t epoch = 0;       // last epoch handed out; descriptors carry (epoch << 2 | state)
+    bool captured = false;    // a stream capture has recorded a call that uses ptr: never freed again
+    int abort_slot = -1;
+    uint32_t seq = 0;         // sequence number of the last call; the next one takes seq + 1 (never zero)
 };
-std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
+std::map<std::pair<int, hipStream_t>, StreamState> g_streams;
+int g_next_abort_slot[64] = {0};   // per device
 
-constexpr uint32_t kMaxEpoch = (1u << 30) - 1;
+// Epochs 1 .. kMaxEagerEpoch tag ordinary calls; a call recorded into a graph clears its
+// descriptors itself and uses kCaptureEpoch, which no ordinary call ever carries.
+constexpr uint32_t kCaptureEpoch = (1u << 30) - 1;
+constexpr uint32_t kMaxEagerEpoch = kCaptureEpoch - 1;
 
 int device_info(const DeviceInfo **out) {
     int dev = 0;
@@ -68,16 +82,25 @@ int device_info(const DeviceInfo **out) {
         e = hipDeviceGetAttribute(&d.cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return set_hip_error(e);
         void *p = nullptr;
-        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_abort_flag));
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_abort_table));
         if (e != hipSuccess) return set_hip_error(e);
-        d.abort_flag = static_cast<uint32_t *>(p);
-        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_residency));
-        if (e != hipSuccess) return set_hip_error(e);
-        d.residency = static_cast<uint32_t *>(p);
+        d.abort_table = static_cast<uint32_t *>(p);
         it = g_devices.emplace(dev, d).first;
     }
     *out = &it->second;
     return KS_OK;
+}
+
+// The stream's state, with an abort word assigned and the next sequence number taken.
+StreamState &stream_state(const DeviceInfo *dev, hipStream_t stream) {
+    StreamState &st = g_streams[std::make_pair(dev->device, stream)];
+    if (st.abort_slot < 0) {
+        int &next = g_next_abort_slot[dev->device & 63];
+        st.abort_slot = next % kAbortSlots;   // more streams than slots: the oldest slots are shared
+        ++next;
+    }
+    if (++st.seq == 0) st.seq = 1;
+    return st;
 }
 
 int validate(ks_dtype dtype, ks_op op, const void *in, void *out, size_t n, const PairEntry **entry) {
@@ -113,11 +136,13 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
     std::lock_guard<std::mutex> lock(g_mutex);
     const DeviceInfo *dev = nullptr;
     if ((st = device_info(&dev)) != KS_OK) return st;
-    ScanCall c{inclusive, algo, in, out, n, temp, temp_bytes, (hipStream_t)stream, 1u, true, dev};
+    StreamState &ss = stream_state(dev, (hipStream_t)stream);
+    ScanCall c{inclusive, algo, in, out, n, temp, temp_bytes, (hipStream_t)stream, 1u, true, dev,
+               dev->abort_table + ss.abort_slot, ss.seq};
     return e->run(c);
 }
 
-// Common part of ks_scan, ks_scan_map and ks_scan_strided: library-owned, epoch-tagged workspace per
+// Common part of ks_scan, ks_scan_map and ks_scan_strided: library-owned, epoch-tagged scratch per
 // (device, stream).  Strided views always take the look-back algorithm.
 static int scan_with_library_workspace(const PairEntry *e, int inclusive, const void *in, void *out, size_t n,
                                        void *stream, size_t in_stride = 1, size_t out_stride = 1) {
@@ -128,15 +153,22 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
     const DeviceInfo *dev = nullptr;
     int st;
     if ((st = device_info(&dev)) != KS_OK) return st;
-    Workspace &ws = g_workspaces[std::make_pair(dev->device, (hipStream_t)stream)];
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    hipError_t he = hipStreamIsCapturing((hipStream_t)stream, &capture);
+    if (he != hipSuccess) return set_hip_error(he);
+    const bool capturing = capture != hipStreamCaptureStatusNone;
+    StreamState &ws = stream_state(dev, (hipStream_t)stream);
     bool fresh = false;
     if (ws.bytes < need) {
-        // growing: hipFree waits for the device, so nothing in flight still uses the old buffer
-        if (ws.ptr) (void)hipFree(ws.ptr);
+        if (capturing) return KS_ERR_WORKSPACE;   // no allocation under capture: make a larger eager call first
+        // growing: hipFree waits for the device, so nothing in flight still uses the old buffer.  A
+        // buffer that a graph has recorded stays allocated for good: the graph may be replayed.
+        if (ws.ptr && !ws.captured) (void)hipFree(ws.ptr);
         ws.ptr = nullptr;
         ws.bytes = 0;
+        ws.captured = false;
         const size_t want = need < ((size_t)1 << 20) ? ((size_t)1 << 20) : need;
-        hipError_t he = hipMalloc(&ws.ptr, want);
+        he = hipMalloc(&ws.ptr, want);
         if (he != hipSuccess) {
             ws.ptr = nullptr;
             set_hip_error(he);
@@ -145,19 +177,32 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
         ws.bytes = want;
         fresh = true;
     }
-    if (fresh || ws.epoch >= kMaxEpoch) {
-        // a fill kernel, not hipMemsetAsync: the call may be recorded into a HIP graph by the caller
-        const size_t words = ws.bytes / sizeof(uint64_t);
-        const size_t blocks = (words + 255) / 256;
-        hipLaunchKernelGGL((fill_zero_kernel<0>), dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0,
-                           (hipStream_t)stream, static_cast<uint64_t *>(ws.ptr), words);
-        hipError_t he = hipGetLastError();
-        if (he != hipSuccess) return set_hip_error(he);
-        ws.epoch = 0;
+    uint32_t epoch = 0;
+    bool clear = false;
+    if (capturing) {
+        // A graph replays the same kernel arguments every time, so the epoch cannot tell a replay's
+        // descriptors from those of the replay before: the recorded call clears its scratch itself
+        // (with a kernel) and carries an epoch of its own.
+        ws.captured = true;
+        epoch = kCaptureEpoch;
+        clear = true;
+    } else {
+        if (fresh || ws.epoch >= kMaxEagerEpoch) {
+            // a fill kernel, not hipMemsetAsync: memset nodes misbehave in graphs on this platform, and
+            // one code path for both is simpler
+            const size_t words = ws.bytes / sizeof(uint64_t);
+            const size_t blocks = (words + 255) / 256;
+            hipLaunchKernelGGL((fill_zero_kernel<0>), dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0,
+                               (hipStream_t)stream, static_cast<uint64_t *>(ws.ptr), words);
+            he = hipGetLastError();
+            if (he != hipSuccess) return set_hip_error(he);
+            ws.epoch = 0;
+        }
+        if (algo == KS_ALGO_LOOKBACK) ++ws.epoch;
+        epoch = ws.epoch;
     }
-    if (algo == KS_ALGO_LOOKBACK) ++ws.epoch;
-    ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, ws.epoch, false, dev,
-               in_stride, out_stride};
+    ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, epoch, clear, dev,
+               dev->abort_table + ws.abort_slot, ws.seq, in_stride, out_stride};
     return e->run(c);
 }
 
@@ -212,12 +257,19 @@ size_t ks_scan_temp_bytes(ks_dtype dtype, ks_op op, ks_algo algo, size_t n) {
 int ks_scan_check(void *stream) {
     hipError_t he = hipStreamSynchronize((hipStream_t)stream);
     if (he != hipSuccess) return set_hip_error(he);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    int st;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    auto it = g_streams.find(std::make_pair(dev->device, (hipStream_t)stream));
+    if (it == g_streams.end() || it->second.abort_slot < 0) return KS_OK;   // no scan has run on this stream
+    uint32_t *word = dev->abort_table + it->second.abort_slot;
     uint32_t flag = 0;
-    he = hipMemcpyFromSymbol(&flag, HIP_SYMBOL(g_abort_flag), sizeof(flag));
+    he = hipMemcpy(&flag, word, sizeof(flag), hipMemcpyDeviceToHost);
     if (he != hipSuccess) return set_hip_error(he);
     if (flag != 0) {
         const uint32_t zero = 0;
-        he = hipMemcpyToSymbol(HIP_SYMBOL(g_abort_flag), &zero, sizeof(zero));
+        he = hipMemcpy(word, &zero, sizeof(zero), hipMemcpyHostToDevice);
         if (he != hipSuccess) return set_hip_error(he);
         return KS_ERR_TIMEOUT;
     }
@@ -244,34 +296,41 @@ static long long *option_slot(const char *name) {
     if (!std::strcmp(name, "waves")) return &o.waves;
     if (!std::strcmp(name, "prefetch")) return &o.prefetch;
     if (!std::strcmp(name, "form")) return &o.form;
-    if (!std::strcmp(name, "grid_mode")) return &o.grid_mode;
-    if (!std::strcmp(name, "last_grid")) return &o.last_grid;
-    if (!std::strcmp(name, "last_resident_per_cu")) return &o.last_resident_per_cu;
-    if (!std::strcmp(name, "last_waves")) return &o.last_waves;
-    if (!std::strcmp(name, "last_rows")) return &o.last_rows;
-    if (!std::strcmp(name, "last_form")) return &o.last_form;
+    if (!std::strcmp(name, "tickets")) return &o.tickets;
+    return nullptr;
+}
+
+static const long long *last_slot(const char *name) {
+    if (!name) return nullptr;
+    const LastLaunch &l = last_launch();
+    if (!std::strcmp(name, "last_grid")) return &l.grid;
+    if (!std::strcmp(name, "last_wgs_per_cu")) return &l.wgs_per_cu;
+    if (!std::strcmp(name, "last_waves")) return &l.waves;
+    if (!std::strcmp(name, "last_rows")) return &l.rows;
+    if (!std::strcmp(name, "last_form")) return &l.form;
+    if (!std::strcmp(name, "last_tickets")) return &l.tickets;
     return nullptr;
 }
 
 int ks_set_option(const char *name, long long value) {
+    std::lock_guard<std::mutex> lock(g_mutex);
     long long *slot = option_slot(name);
-    if (!slot) return KS_ERR_INVALID_ARG;
+    if (!slot) return KS_ERR_INVALID_ARG;   // unknown, or one of the read-only "last_*" names
     Options &o = options();
-    if (slot == &o.last_grid || slot == &o.last_resident_per_cu || slot == &o.last_waves || slot == &o.last_rows ||
-        slot == &o.last_form)
-        return KS_ERR_INVALID_ARG;   // read-only
     if (slot == &o.waves && !(value == 0 || value == 4 || value == 8 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.rows && !(value == 0 || value == 4 || value == 8 || value == 9 || value == 12 || value == 16)) return KS_ERR_INVALID_ARG;
     if (slot == &o.spin_limit && value < 0) return KS_ERR_INVALID_ARG;
-    if (slot == &o.wgs_per_cu && value < 0) return KS_ERR_INVALID_ARG;
-    if (slot == &o.grid_mode && !(value == 0 || value == 1)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.wgs_per_cu && (value < 0 || value > 64)) return KS_ERR_INVALID_ARG;
     if (slot == &o.prefetch && !(value >= -1 && value <= 1)) return KS_ERR_INVALID_ARG;
     if (slot == &o.form && !(value >= -1 && value < kFormCount)) return KS_ERR_INVALID_ARG;
+    if (slot == &o.tickets && !(value == -1 || value == 1)) return KS_ERR_INVALID_ARG;
     *slot = value;
     return KS_OK;
 }
 
 long long ks_get_option(const char *name) {
+    if (const long long *last = last_slot(name)) return *last;
+    std::lock_guard<std::mutex> lock(g_mutex);
     long long *slot = option_slot(name);
     return slot ? *slot : -1;
 }

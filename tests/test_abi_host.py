@@ -140,19 +140,24 @@ def test_options_are_validated(ks):
     ks.ks_set_option("waves", 0)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("waves", 2)
-    for read_only in ("last_grid", "last_resident_per_cu", "last_waves", "last_rows", "last_form"):
+    for read_only in ("last_grid", "last_wgs_per_cu", "last_waves", "last_rows", "last_form", "last_tickets"):
         assert ks.ks_get_option(read_only) >= 0
         with pytest.raises(ks.KsError):
             ks.ks_set_option(read_only, 1)
     with pytest.raises(ks.KsError):
         ks.ks_set_option("no_such_option", 1)
     with pytest.raises(ks.KsError):
-        ks.ks_set_option("grid_mode", 5)
+        ks.ks_set_option("tickets", 0)        # by index is not safe for every grid: only -1 (default) and 1
+    ks.ks_set_option("tickets", 1)
+    assert ks.ks_get_option("tickets") == 1
+    ks.ks_set_option("tickets", -1)
+    with pytest.raises(ks.KsError):
+        ks.ks_set_option("wgs_per_cu", 65)
     ks.ks_set_option("form", 2)
     assert ks.ks_get_option("form") == 2
     ks.ks_set_option("form", -1)
     with pytest.raises(ks.KsError):
-        ks.ks_set_option("form", 6)
+        ks.ks_set_option("form", 3)
     assert ks.ks_get_option("no_such_option") == -1
 
 

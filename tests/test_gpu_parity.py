@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 def ks():
     import paper_2603_18695_amd as ks
     yield ks
-    for name, v in [("waves", 0), ("rows", 0), ("prefetch", -1), ("form", -1), ("grid_mode", 0), ("wgs_per_cu", 0),
+    for name, v in [("waves", 0), ("rows", 0), ("prefetch", -1), ("form", -1), ("tickets", -1), ("wgs_per_cu", 0),
                     ("spin_limit", 1 << 20)]:
         ks.ks_set_option(name, v)
 
@@ -299,16 +299,51 @@ def test_repeated_launches_give_identical_integer_results(ks):
     d_in = to_device(x)
     d_out = torch.empty_like(d_in)
     d_ref = to_device(ref)
-    for wgs in (0, 1, 3):
+    for wgs, tickets in ((0, -1), (0, 1), (3, -1)):
         ks.ks_set_option("wgs_per_cu", wgs)
+        ks.ks_set_option("tickets", tickets)
         for it in range(25):
             if it % 8 == 0:
-                say(f"[case] repeat int32 sum n={n} wgs_per_cu={wgs} iteration={it}")
+                say(f"[case] repeat int32 sum n={n} wgs_per_cu={wgs} tickets={tickets} iteration={it}")
             d_out.zero_()
             ks.ks_scan(d_in, d_out, dtype="i32", op="sum")
-            assert torch.equal(d_out, d_ref), (wgs, it)
+            assert torch.equal(d_out, d_ref), (wgs, tickets, it)
+        # more than one workgroup per compute unit is only ever run by ticket
+        assert ks.ks_get_option("last_tickets") == (1 if tickets == 1 or wgs == 3 else 0)
     ks.ks_set_option("wgs_per_cu", 0)
+    ks.ks_set_option("tickets", -1)
     ks.ks_scan_check()
+
+
+@pytest.mark.parametrize("dtype,op", [("f32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"),
+                                      ("mat2_u32", "mat2_mul"), ("affine_f32", "affine_compose")])
+def test_tiles_by_ticket(ks, dtype, op):
+    # Tile assignment by ticket: every default shape forced onto it, grids of one workgroup per compute
+    # unit and grids far larger than what can be resident (4 x 1024 threads per compute unit: most
+    # workgroups only start when others have left, draw a ticket past the end and leave too), the small
+    # shapes with many workgroups per compute unit, sizes from one tile to a dozen rounds.
+    tile = tile_elems(ks, dtype, 16, 9)
+    try:
+        for waves, wgs in ((0, 0), (0, 4), (4, 0), (8, 6)):
+            ks.ks_set_option("waves", waves)
+            ks.ks_set_option("wgs_per_cu", wgs)
+            ks.ks_set_option("tickets", 1)
+            for n in (17, tile + 1, 255 * tile + 3, 257 * tile, 700 * tile + 5, 3100 * tile + 11):
+                x = random_input(dtype, op, n, seed=n % 101)
+                for inclusive, api in ((True, "with_temp"), (False, "with_temp"), (True, "plain")):
+                    if api == "plain" and n <= tile:
+                        continue          # ks_scan hands a single tile to one workgroup without any look-back
+                    say(f"[case] by ticket ({dtype},{op}) waves={waves} wgs_per_cu={wgs} n={n} incl={inclusive} {api}")
+                    try:
+                        got = run(ks, dtype, op, x, inclusive, algo="lookback", api=api)
+                    except ks.KsError as e:
+                        assert e.status == ks.KS_ERR_UNSUPPORTED, e     # shape not compiled for this type
+                        continue
+                    assert ks.ks_get_option("last_tickets") == 1
+                    assert_matches(dtype, op, got, reference(dtype, op, x, inclusive), f"by ticket ({dtype},{op}) n={n}")
+    finally:
+        for name, v in (("waves", 0), ("wgs_per_cu", 0), ("tickets", -1)):
+            ks.ks_set_option(name, v)
 
 
 def test_abandoned_wait_is_reported_and_the_next_call_is_clean(ks):
@@ -507,6 +542,133 @@ def test_hip_graph_replays_match_eager_results(ks):
             ks.ks_scan_check()
             assert_matches(dtype, op, to_host(d_out, xs[r].dtype), refs[r], f"replay {r}")
         del graph
+
+
+def test_ks_scan_recorded_into_a_graph(ks):
+    # ks_scan with its library-owned scratch under stream capture: a replay repeats the kernel
+    # arguments of the recording, epoch included, so the recorded call must not rely on the epoch to
+    # tell its descriptors from those the previous replay (or an eager call in between) left behind.
+    for dtype, op, n in (("f32", "sum", 3_000_017), ("argmax_i32_cnt64", "argmax_count", 1_200_003)):
+        xs = [random_input(dtype, op, n, seed=60 + r) for r in range(4)]
+        refs = [reference(dtype, op, x, True) for x in xs]
+        side = random_input(dtype, op, n // 2 + 7, seed=59)
+        side_ref = reference(dtype, op, side, True)
+        d_in = to_device(xs[0])
+        d_out = torch.empty_like(d_in)
+        d_side, d_side_out = to_device(side), torch.empty_like(to_device(side))
+        # the scratch belongs to (device, stream): warm up, record and replay on one stream
+        s = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        say(f"[case] ks_scan in a graph ({dtype},{op}) n={n}: eager warm-up (allocates the scratch)")
+        with torch.cuda.stream(s):
+            ks.ks_scan(d_in, d_out, dtype=dtype, op=op)
+        ks.ks_scan_check(s)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            ks.ks_scan(d_in, d_out, dtype=dtype, op=op)
+        for r in range(4):
+            say(f"[case] ks_scan in a graph ({dtype},{op}) n={n}: replay {r}")
+            d_in.copy_(to_device(xs[r]))
+            d_out.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s):
+                # eager calls on the same stream and scratch between the replays
+                ks.ks_scan(d_side, d_side_out, dtype=dtype, op=op)
+                graph.replay()
+                graph.replay()             # twice in a row: the second finds the first one's descriptors
+            ks.ks_scan_check(s)
+            assert_matches(dtype, op, to_host(d_out, xs[r].dtype), refs[r], f"replay {r}")
+            assert_matches(dtype, op, to_host(d_side_out, side.dtype), side_ref, f"eager call before replay {r}")
+        # a recording that would have to allocate is refused, not attempted
+        big = torch.zeros(64 * n * (d_in.numel() // n), dtype=d_in.dtype, device="cuda")
+        big_out = torch.empty_like(big)
+        g2 = torch.cuda.CUDAGraph()
+        refused = False
+        with torch.cuda.graph(g2, stream=s):
+            try:
+                ks.ks_scan(big, big_out, dtype=dtype, op=op)
+            except ks.KsError as e:
+                assert e.status == ks.KS_ERR_WORKSPACE, e
+                refused = True
+        assert refused
+        del graph, g2, big, big_out
+
+
+def test_a_timeout_is_reported_on_the_stream_it_happened_on(ks):
+    # abort words are per stream: a wait abandoned on stream A is reported by the check of A and
+    # not by the check of B, and scans on B meanwhile are unaffected
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    tile = tile_elems(ks, "u64", 16, 8)
+    n = 900 * tile + 7
+    x = random_input("u64", "sum", n, seed=3)
+    ref = to_device(reference("u64", "sum", x, True))
+    d_in = to_device(x)
+    out_a, out_b = torch.empty_like(d_in), torch.empty_like(d_in)
+    with torch.cuda.stream(sa), torch.cuda.stream(sb):
+        pass
+    torch.cuda.synchronize()
+    seen = 0
+    for it in range(5):
+        ks.ks_set_option("spin_limit", 0)
+        try:
+            with torch.cuda.stream(sa):
+                ks.ks_scan(d_in, out_a, dtype="u64", op="sum")
+        finally:
+            ks.ks_set_option("spin_limit", 1 << 20)
+        with torch.cuda.stream(sb):
+            ks.ks_scan(d_in, out_b, dtype="u64", op="sum")
+        ks.ks_scan_check(sb)                       # must not raise: B's scans never gave up
+        assert torch.equal(out_b, ref), it
+        try:
+            ks.ks_scan_check(sa)
+        except ks.KsError as e:
+            assert e.status == ks.KS_ERR_TIMEOUT, e
+            seen += 1
+        ks.ks_scan_check(sa)                       # reported once, then clear
+        say(f"[case] per-stream abort word, iteration {it}: timeouts seen on A so far {seen}")
+    assert seen >= 1, "with a spin limit of zero some workgroup of 900 tiles has to wait at least once in five runs"
+
+
+@pytest.mark.parametrize("tickets", [-1, 1])
+def test_scan_while_another_stream_holds_the_compute_units(ks, tickets):
+    # A bounded queue of plain copies on another stream keeps the compute units busy while the scan
+    # is launched, so its workgroups start late and not together.  The scan must come out right, or
+    # its own stream's check must say KS_ERR_TIMEOUT; every kernel ends by itself either way.
+    other = torch.cuda.Stream()
+    n = 1 << 26
+    x = ks_inputs.whole("int32_sum", n)
+    want = to_device(reference("i32", "sum", x, True))
+    d_in = to_device(x)
+    d_out = torch.empty_like(d_in)
+    a = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    ks.ks_set_option("tickets", tickets)
+    try:
+        ks.ks_scan(d_in, d_out, dtype="i32", op="sum")      # warm-up: scratch allocated, clocks up
+        torch.cuda.synchronize()
+        outcomes = {"ok": 0, "timeout": 0}
+        for it in range(6):
+            d_out.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(other):
+                for _ in range(40):                         # about 4 ms of copies
+                    ks.ks_copy(a, b, stream=other)
+            for _ in range(3):                              # three scans land in the middle of them
+                ks.ks_scan(d_in, d_out, dtype="i32", op="sum")
+            try:
+                ks.ks_scan_check()
+                assert torch.equal(d_out, want), f"iteration {it}: wrong result without a reported timeout"
+                outcomes["ok"] += 1
+            except ks.KsError as e:
+                assert e.status == ks.KS_ERR_TIMEOUT, e
+                outcomes["timeout"] += 1
+            other.synchronize()
+        say(f"[case] scan beside a queue of copies, tickets={tickets}: {outcomes}")
+        if tickets == 1:
+            assert outcomes["timeout"] == 0      # by ticket nobody ever waits for a workgroup that has not started
+    finally:
+        ks.ks_set_option("tickets", -1)
+    ks.ks_scan_check()
 
 
 def test_more_than_2_pow_32_elements(ks):
