@@ -155,6 +155,26 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
                       void *out, size_t n, void *temp, size_t temp_bytes, void *stream);
 
 /*
+ * For callers that cannot allocate device memory or own a scratch buffer: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments and errors as ks_scan, but the scratch is a static
+ * device array of KS_STATIC_SCRATCH_BYTES that every device loading the library
+ * holds until the process ends.  The call allocates nothing, on the device or
+ * through any library, only launches kernels (the first one clears the part of
+ * the array the call uses) and may be recorded into a graph.  Limit: inputs with
+ * ks_scan_temp_bytes(dtype, op, KS_ALGO_AUTO, n) > KS_STATIC_SCRATCH_BYTES return
+ * KS_ERR_WORKSPACE and launch nothing (8 MiB covers n up to 2^29 for float32 and 2^30
+ * for the other 4-byte pairs, 2^28 for 8-byte scalars, 2^27 for the affine type and
+ * 2^26 for the 16-byte types).  All calls on one device
+ * share the one array: two calls that overlap in time on a device (different
+ * streams, or two graphs in flight) race and give wrong results; calls on one
+ * stream, one after the other, are fine.
+ */
+#define KS_STATIC_SCRATCH_BYTES (8u << 20)
+int ks_scan_static(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n,
+                   void *stream);
+
+/*
  * Synchronise `stream` and report whether any scan issued on this stream (of
  * the current device) since the last check gave up waiting for a predecessor
  * tile (KS_ERR_TIMEOUT; that call's output is invalid), or a HIP error surfaced

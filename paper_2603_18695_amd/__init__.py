@@ -33,7 +33,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3}
 
-EXPORTS = ["ks_scan", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_static", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -41,6 +41,8 @@ EXPORTS = ["ks_scan", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_
 _vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan.restype = _i
+_lib.ks_scan_static.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.ks_scan_static.restype = _i
 _lib.ks_scan_map.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_map.restype = _i
 _lib.ks_scan_strided.argtypes = [_i, _i, _i, _vp, _sz, _vp, _sz, _sz, _vp]
@@ -135,6 +137,21 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
                             _stream_ptr(stream)), "ks_scan")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def ks_scan_static(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclusive: bool = True,
+                   stream=None) -> torch.Tensor:
+    """out = scan(inp) using the library's static device scratch: allocates nothing; see ks_scan.h for the limit."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != n:
+        raise ValueError("inp and out differ in size")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_scan_static(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
+                                   _stream_ptr(stream)), "ks_scan_static")
     return out
 
 

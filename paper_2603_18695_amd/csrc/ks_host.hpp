@@ -35,6 +35,7 @@ struct DeviceInfo {
     int device = -1;
     int cus = 0;
     uint32_t *abort_table = nullptr;   // device address of the library's table of abort words on this device
+    void *static_scratch = nullptr;    // device address of this device's copy of the static scratch array
 };
 
 struct ScanCall {

@@ -19,6 +19,12 @@ namespace ks {
 constexpr int kAbortSlots = 1024;
 __device__ uint32_t g_abort_table[kAbortSlots];
 
+// Scratch of ks_scan_static: device memory that exists without any allocation call.  One array per
+// device that loads the library; host code reaches it through the address hipGetSymbolAddress
+// returns for the current device (DeviceInfo::static_scratch), never through this name.
+constexpr size_t kStaticScratchBytes = (size_t)KS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 const PairEntry *pair_entry_i32(int, int);
 const PairEntry *pair_entry_i64(int, int);
 const PairEntry *pair_entry_float(int, int);
@@ -85,6 +91,9 @@ int device_info(const DeviceInfo **out) {
         e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_abort_table));
         if (e != hipSuccess) return set_hip_error(e);
         d.abort_table = static_cast<uint32_t *>(p);
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return set_hip_error(e);
+        d.static_scratch = p;
         it = g_devices.emplace(dev, d).first;
     }
     *out = &it->second;
@@ -211,6 +220,22 @@ int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, 
     int st = validate(dtype, op, in, out, n, &e);
     if (st != KS_OK || n == 0) return st;
     return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_scan_static(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
+    const PairEntry *e = nullptr;
+    int st = validate(dtype, op, in, out, n, &e);
+    if (st != KS_OK || n == 0) return st;
+    const ks_algo algo = e->pick_algo(n);
+    if (e->temp_bytes(algo, n) > kStaticScratchBytes) return KS_ERR_WORKSPACE;   // beyond the stated maximum
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    StreamState &ss = stream_state(dev, (hipStream_t)stream);
+    // the array keeps what the last call left: the launch code clears what this call uses, with a kernel
+    ScanCall c{inclusive, algo, in, out, n, dev->static_scratch, kStaticScratchBytes, (hipStream_t)stream, 1u, true,
+               dev, dev->abort_table + ss.abort_slot, ss.seq};
+    return e->run(c);
 }
 
 int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void *in, void *out, size_t n,
