@@ -9,9 +9,14 @@ Definition followed (paper, Sec. II-C, scan; Sec. V-B first sentence):
 with ``out[0] = identity`` (exclusive), ``op`` associative and not necessarily
 commutative, the accumulated value always being the left operand.
 
-Every function here is pinned by tests/test_oracle_pins.py to closed forms,
-library special cases, exact per-prefix sums and brute force over every
-parenthesisation; none is "parity unpinned".
+``mapreduce`` (paper, Sec. II-C and V-A) is the same fold taken to the end:
+``op(f(src[1]), ..., f(src[n]))``, written as the left fold of the mapped
+elements, accumulated value on the left.
+
+Every function here is pinned by tests/test_oracle_pins.py and
+tests/test_oracle_mapreduce_pins.py to closed forms, library special cases,
+exact sums and brute force over every parenthesisation (and, for commutative
+operators, every order of the elements); none is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -185,6 +190,51 @@ def mapped_scan(map_name: str, op: str, dt: str, x: np.ndarray, inclusive: bool 
     if y.dtype == np.float64 and dt == "f32":
         dt = "f64"   # squares of float32 values, held exactly in float64
     return scan(op, dt, np.ascontiguousarray(y), inclusive)
+
+
+def identity_of(op: str, dt: str | None):
+    """The operator's identity in the oracle's output type (what an empty reduction returns)."""
+    if op == "sum":
+        return (np.float64 if dt in ("f32", "f64") else _NP[dt])(0)
+    if op in ("min", "max"):
+        t = _NP[dt]
+        if np.issubdtype(t, np.floating):
+            return t(np.inf if op == "min" else -np.inf)
+        info = np.iinfo(t)
+        return t(info.max if op == "min" else info.min)
+    if op == "affine":
+        return np.array([1.0, 0.0])
+    if op == "argmax":
+        return np.array([(np.iinfo(np.int32).min, np.iinfo(np.int32).max, 0)], dtype=ARGMAX_DTYPE)[0]
+    if op == "mat2":
+        return np.array([1, 0, 0, 1], dtype=np.uint32)
+    if op == "quat":
+        return np.array([1.0, 0.0, 0.0, 0.0])
+    raise KeyError(op)
+
+
+def mapreduce(map_name: str, op: str, dt: str | None, x: np.ndarray, chunk: int = 1 << 22):
+    """op(f(x[0]), f(x[1]), ..., f(x[n-1])) as one sequential left fold (paper Sec. II-C, mapreduce;
+    Sec. V-A), the accumulated value always on the left; the identity for an empty input.
+
+    The fold is the scan's own (the same C routine run to the end of the input, fed in chunks, the
+    running value carried in its state); what comes back is the last running value, in the oracle's
+    output type: float64 for float32 / float64 sums, affine maps and quaternions, the element type
+    for everything else.  The paper asks for a commutative operator here; the left fold is also
+    defined for the non-commutative ones, and that is what is returned for them.
+    """
+    x = np.asarray(x)
+    n = x.shape[0]
+    if n == 0:
+        return identity_of(op, dt)
+    probe = apply_map(map_name, x[:1])
+    if probe.dtype == np.float64 and dt == "f32":
+        dt = "f64"   # squares of float32 values, held exactly in float64
+    stream = ScanStream(op, dt, True)
+    last = None
+    for at in range(0, n, chunk):
+        last = stream.feed(np.ascontiguousarray(apply_map(map_name, x[at:at + chunk])))[-1]
+    return last
 
 
 def fold_scan(op, xs, inclusive=True, identity=None):
