@@ -7,10 +7,12 @@ Default workload: BASELINE's headline configuration, inclusive float32 sum scan 
 values uniform in [0, 1) from seed 1.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--stride S] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--stride S] [--mapreduce] [--no-cpu]
 
 With --stride S > 1 (scalar workloads) the same elements sit S elements apart in both buffers and
 ks_scan_strided runs; GB/s still counts the elements alone (2 * n * element size).
+With --mapreduce the step is one ks_mapreduce call (the workload's operator, identity map) on the same
+input, and GB/s counts n * element size: every element read once, one element written.
 """
 from __future__ import annotations
 
@@ -81,6 +83,7 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=0)
     ap.add_argument("--algo", default="auto", choices=["auto", "lookback", "reduce_then_scan"])
     ap.add_argument("--stride", type=int, default=1, help="element stride of both views (ks_scan_strided)")
+    ap.add_argument("--mapreduce", action="store_true", help="time ks_mapreduce (reads n elements) instead of the scan")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (cpu_baseline = null)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
     args = ap.parse_args()
@@ -105,7 +108,11 @@ def main() -> int:
     w = ks_inputs.WORKLOADS[args.workload]
     n = args.n or (w.n if args.workload != "argmax" else 1 << 26)
     eb = w.elem_bytes
-    algorithmic_bytes = 2 * n * eb                      # every element read once and written once
+    # every element read once and written once; a reduction only reads
+    algorithmic_bytes = n * eb if args.mapreduce else 2 * n * eb
+    if args.mapreduce and (args.stride > 1 or args.algo != "auto"):
+        log("bench.py: --mapreduce goes with --stride 1 and --algo auto")
+        return 2
 
     # ---- inputs: generated on the host from the seeded recipe, then resident in HBM
     t0 = time.time()
@@ -124,8 +131,12 @@ def main() -> int:
         s_in[::args.stride] = d_in
         s_out = torch.zeros_like(s_in)
 
+    d_one = torch.empty_like(d_in[:1])
+
     def step():
-        if args.stride > 1:
+        if args.mapreduce:
+            ks.ks_mapreduce(d_in, d_one, dtype=w.dtype, op=w.op)
+        elif args.stride > 1:
             ks.ks_scan_strided(s_in, s_out, dtype=w.dtype, op=w.op, n=n, in_stride=args.stride,
                                out_stride=args.stride, inclusive=w.inclusive)
         elif args.algo == "auto":
@@ -196,7 +207,7 @@ def main() -> int:
     c1.record()
     torch.cuda.synchronize()
     copy_ms = c0.elapsed_time(c1) / 50
-    copy_gbs = algorithmic_bytes / (copy_ms * 1e-3) / 1e9
+    copy_gbs = 2 * n * eb / (copy_ms * 1e-3) / 1e9      # the copy reads and writes n elements
     log(f"copy ceiling: {copy_ms:.4f} ms -> {copy_gbs:.1f} GB/s")
 
     # ---- oracle leg: the sequential CPU scan on this host, one core, and a parity check of the
@@ -211,7 +222,7 @@ def main() -> int:
             d_out = s_out[::args.stride].contiguous()
         oop, odt = ORACLE_KIND[args.workload]
         budget_elems = min(n, 1 << 28)
-        stream = oracle.ScanStream(oop, odt, w.inclusive)
+        stream = oracle.ScanStream(oop, odt, True if args.mapreduce else w.inclusive)
         cpu_s, done, at, worst = 0.0, 0, 0, 0.0
         for c in host_chunks:
             if done >= budget_elems:
@@ -219,12 +230,15 @@ def main() -> int:
             t = time.perf_counter()
             ref = stream.feed(c)
             cpu_s += time.perf_counter() - t
-            got = to_host(d_out[at:at + len(c)], c.dtype)
-            worst = max(worst, worst_ratio_or_raise(args.workload, got, ref, f"bench parity at {at}"))
+            if not args.mapreduce:
+                got = to_host(d_out[at:at + len(c)], c.dtype)
+                worst = max(worst, worst_ratio_or_raise(args.workload, got, ref, f"bench parity at {at}"))
             at += len(c)
             done += len(c)
+        if args.mapreduce and done == n:     # the fold's last running value is the reduction
+            worst = worst_ratio_or_raise(args.workload, to_host(d_one, host_chunks[0].dtype), ref[-1:], "bench parity, mapreduce")
         parity = {"checked_elements": done, "worst_float_ratio": worst}
-        cpu_gbs = 2 * done * eb / cpu_s / 1e9
+        cpu_gbs = (1 if args.mapreduce else 2) * done * eb / cpu_s / 1e9
         cpu = {"value": cpu_gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"first {done} elements of the same workload, sequential C left fold (fp64 accumulator "
                          f"for float inputs), {cpu_s:.2f} s on {os.cpu_count()} visible host cpus, 1 thread used",
@@ -235,7 +249,7 @@ def main() -> int:
     #      their parity is the GPU tests' business).  Only with the default workload and the oracle leg on.
     others = None
     if (not args.no_cpu and args.workload == "f32_sum" and not args.n and args.algo == "auto" and not args.opt
-            and args.stride == 1):
+            and args.stride == 1 and not args.mapreduce):
         del d_in, d_out, temp
         others = {}
 
@@ -271,7 +285,8 @@ def main() -> int:
         others["argmax_sweep"] = [time_config("argmax", on) for on in ks_inputs.ARGMAX_SWEEP if on != 1 << 26]
 
     result = {
-        "metric": "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X"
+        "metric": f"mapreduce GB/s (read), workload {args.workload} n={n}, 1 MI355X" if args.mapreduce
+                  else "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X"
                   if args.workload == "f32_sum" and n == 1 << 28 and args.stride == 1
                   else f"scan GB/s (read+write), workload {args.workload} n={n}"
                        f"{'' if args.stride == 1 else f' element stride {args.stride}'}, 1 MI355X",
@@ -297,7 +312,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": gbs_event, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs_event / HBM_PEAK_GBS,
                      "traffic": measured_traffic(args.workload, n)
-                                if args.algo == "auto" and not args.opt and args.stride == 1 else None,
+                                if args.algo == "auto" and not args.opt and args.stride == 1 and not args.mapreduce else None,
                      "traffic_source": f"rocprofv3 FETCH_SIZE / WRITE_SIZE of this kernel and size, read from {TRAFFIC_SUMMARY} "
                                        "(not measured in this run)",
                      "kernel_ms": event_ms, "algorithmic_bytes": algorithmic_bytes},

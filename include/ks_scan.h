@@ -132,7 +132,27 @@ int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void 
 int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, size_t in_stride,
                     void *out, size_t out_stride, size_t n, void *stream);
 
-/* 1 if ks_scan_map accepts this (dtype, map, op), else 0. */
+/*
+ * mapreduce(f, op, src) in one launch (paper Sec. II-C: op(f(src[1]), ..., f(src[n]));
+ * Sec. V-A for the single-launch scheme): out[0] = f(in[0]) op f(in[1]) op ... op
+ * f(in[n-1]), the left fold with the accumulated value on the left, so operators
+ * that do not commute give the ordered result too (the paper requires a
+ * commutative operator).  n == 0 writes the operator's identity.
+ *   in    device pointer, n contiguous elements of dtype (may be NULL if n == 0)
+ *   out   device pointer to ONE element of dtype, written by the call; it may lie
+ *         inside `in`
+ *   map   KS_MAP_IDENTITY or one of the maps; accepted (dtype, map, op) triples are
+ *         those of ks_map_supported, others return KS_ERR_UNSUPPORTED
+ * Float32 sums are accumulated in double and rounded once at the end.  Scratch,
+ * stream behaviour (asynchronous; recordable into a graph under ks_scan's
+ * conditions) and errors as for ks_scan; a finishing wave that does not see all
+ * partial results within "spin_limit" polls leaves `out` unwritten and
+ * ks_scan_check reports KS_ERR_TIMEOUT.
+ */
+int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n, void *out,
+                 void *stream);
+
+/* 1 if ks_scan_map and ks_mapreduce accept this (dtype, map, op), else 0. */
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op);
 
 /*

@@ -33,7 +33,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3}
 
-EXPORTS = ["ks_scan", "ks_scan_static", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -43,6 +43,8 @@ _lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan.restype = _i
 _lib.ks_scan_static.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_static.restype = _i
+_lib.ks_mapreduce.argtypes = [_i, _i, _i, _vp, _sz, _vp, _vp]
+_lib.ks_mapreduce.restype = _i
 _lib.ks_scan_map.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_map.restype = _i
 _lib.ks_scan_strided.argtypes = [_i, _i, _i, _vp, _sz, _vp, _sz, _sz, _vp]
@@ -137,6 +139,19 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
                             _stream_ptr(stream)), "ks_scan")
+    return out
+
+
+def ks_mapreduce(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, map: str = "identity",
+                 stream=None) -> torch.Tensor:
+    """out[0] = op(map(inp[0]), ..., map(inp[n-1])), one launch; `out` holds one element of `dtype`.
+    Asynchronous on the stream."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != 1:
+        raise ValueError("out must hold exactly one element")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_mapreduce(DTYPES[dtype], MAPS[map], OPS[op], inp.data_ptr() if n else None, n, out.data_ptr(),
+                                 _stream_ptr(stream)), "ks_mapreduce")
     return out
 
 

@@ -64,6 +64,7 @@ struct PairEntry {
     size_t (*temp_bytes)(ks_algo algo, size_t n);
     ks_algo (*pick_algo)(size_t n);
     int (*run)(const ScanCall &call);   // returns ks_status; HIP failures via set_hip_error
+    int (*mapreduce)(const ScanCall &call);   // call.out = one element; call.temp = control block + partials
 };
 
 int set_hip_error(hipError_t e);   // records e, returns KS_ERR_HIP

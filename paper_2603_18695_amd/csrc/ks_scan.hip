@@ -154,10 +154,12 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
 // Common part of ks_scan, ks_scan_map and ks_scan_strided: library-owned, epoch-tagged scratch per
 // (device, stream).  Strided views always take the look-back algorithm.
 static int scan_with_library_workspace(const PairEntry *e, int inclusive, const void *in, void *out, size_t n,
-                                       void *stream, size_t in_stride = 1, size_t out_stride = 1) {
+                                       void *stream, size_t in_stride = 1, size_t out_stride = 1,
+                                       bool reduce = false) {
     const bool strided = in_stride != 1 || out_stride != 1;
-    const ks_algo algo = strided ? KS_ALGO_LOOKBACK : e->pick_algo(n);
-    const size_t need = e->temp_bytes(algo, n);
+    const ks_algo algo = strided || reduce ? KS_ALGO_LOOKBACK : e->pick_algo(n);   // both tag their scratch with an epoch
+    // a reduction's scratch (control block and one partial per workgroup) always fits the smallest buffer
+    const size_t need = reduce ? 1 : e->temp_bytes(algo, n);
     std::lock_guard<std::mutex> lock(g_mutex);
     const DeviceInfo *dev = nullptr;
     int st;
@@ -212,7 +214,7 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
     }
     ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, epoch, clear, dev,
                dev->abort_table + ws.abort_slot, ws.seq, in_stride, out_stride};
-    return e->run(c);
+    return reduce ? e->mapreduce(c) : e->run(c);
 }
 
 int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
@@ -266,6 +268,17 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
     const bool same_view = a == b && in_stride == out_stride;
     if (!same_view && a < b + span_out && b < a + span_in) return KS_ERR_OVERLAP;
     return scan_with_library_workspace(e, inclusive, in, out, n, stream, in_stride, out_stride);
+}
+
+int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n, void *out, void *stream) {
+    if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
+    if ((int)map < KS_MAP_IDENTITY || (int)map > KS_MAP_NONZERO) return KS_ERR_INVALID_ARG;
+    const PairEntry *e = map == KS_MAP_IDENTITY ? pair_entry(dtype, op) : pair_entry_mapped((int)dtype, (int)map, (int)op);
+    if (!e) return KS_ERR_UNSUPPORTED;
+    if (!out || (n > 0 && !in)) return KS_ERR_INVALID_ARG;
+    if (n > ((size_t)1 << 40)) return KS_ERR_INVALID_ARG;
+    if (((uintptr_t)in % e->elem_align) || ((uintptr_t)out % e->elem_align)) return KS_ERR_MISALIGNED;
+    return scan_with_library_workspace(e, 1, in, out, n, stream, 1, 1, true);
 }
 
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {

@@ -1,0 +1,168 @@
+"""GPU parity of ks_mapreduce (paper Sec. II-C / V-A) against the oracle's sequential left fold, through
+the C ABI.  Integer and struct results bit for bit; float results within max(1e-4 |ref|, 1e-3) of the
+oracle's float64 fold (min / max of floats exactly)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import ks_inputs
+import oracle
+from parity import FLOAT_TOL, KINDS, float_bound, random_input, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2603_18695_amd as ks
+    return ks
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def reduce_on_gpu(ks, dtype, op, x, map_name="identity", d_in=None):
+    d_in = to_device(x) if d_in is None else d_in
+    one = to_device(x[:1]) if len(x) else to_device(np.zeros((1,) + x.shape[1:], x.dtype))
+    out = torch.full_like(one, 0x55)
+    ks.ks_mapreduce(d_in, out, dtype=dtype, op=op, map=map_name)
+    ks.ks_scan_check()
+    return to_host(out, x.dtype)[0]
+
+
+def check(dtype, op, got, ref, what):
+    if (dtype, op) in FLOAT_TOL:
+        g, r = np.asarray(got, dtype=np.float64).reshape(-1), np.asarray(ref, dtype=np.float64).reshape(-1)
+        assert np.all(np.abs(g - r) <= float_bound(r)), f"{what}: gpu={g} ref={r}"
+    elif np.asarray(got).dtype.names:
+        assert got == ref, f"{what}: gpu={got} ref={ref}"
+    else:
+        assert np.array_equal(np.asarray(got), np.asarray(ref).astype(np.asarray(got).dtype)), f"{what}: gpu={got} ref={ref}"
+
+
+def run_elems(ks, dtype):
+    return 64 * 8 * (16 // ks.ks_elem_bytes(dtype))       # elements one wave folds per step (4 or 8 rows per lane)
+
+
+@pytest.mark.parametrize("dtype,op", sorted(KINDS))
+def test_every_pair_edge_sizes(ks, dtype, op):
+    oop, odt, _, _ = KINDS[(dtype, op)]
+    run = run_elems(ks, dtype)
+    sizes = [0, 1, 2, 63, 64, 65, run - 1, run, run + 1, 4 * run - 1, 4 * run, 4 * run + 1, 37 * run + 5,
+             2048 * 4 * run - 1, 2048 * 4 * run + 1, 3 * 2048 * 4 * run + 12345]
+    for n in sizes:
+        x = random_input(dtype, op, n, seed=500 + n % 89)
+        say(f"[case] mapreduce ({dtype},{op}) n={n}")
+        check(dtype, op, reduce_on_gpu(ks, dtype, op, x), oracle.mapreduce("identity", oop, odt, x), f"({dtype},{op}) n={n}")
+
+
+MAP_TRIPLES = [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
+               ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]
+
+
+@pytest.mark.parametrize("dtype,map_name,op", MAP_TRIPLES)
+def test_mapped_triples(ks, dtype, map_name, op):
+    oop, odt, npdt, _ = KINDS[(dtype, op)]
+    rng = np.random.default_rng(77)
+    for n in (1, 5, 1000, 70_001, 5_000_003):
+        if np.issubdtype(npdt, np.integer):
+            x = (rng.integers(0, 3, size=n) * rng.integers(-1000, 1000, size=n)).astype(npdt)   # one third zeros
+        else:
+            x = rng.uniform(-2.0, 2.0, size=n).astype(npdt)
+        say(f"[case] mapreduce ({dtype},{map_name},{op}) n={n}")
+        got = reduce_on_gpu(ks, dtype, op, x, map_name)
+        ref = oracle.mapreduce(map_name, oop, odt, x)
+        check(dtype, op, got, ref, f"({dtype},{map_name},{op}) n={n}")
+    assert ks.ks_map_supported(dtype, map_name, op)
+    with pytest.raises(ks.KsError) as e:
+        ks.ks_mapreduce(torch.zeros(4, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"),
+                        dtype="i32", op="min", map="square")
+    assert e.value.status == ks.KS_ERR_UNSUPPORTED
+
+
+def test_closed_forms_and_operand_order(ks):
+    n = (1 << 24) + 12345
+    say("[case] mapreduce closed forms")
+    assert int(reduce_on_gpu(ks, "i32", "sum", np.ones(n, np.int32))) == n
+    i = np.arange(n, dtype=np.uint64)
+    assert int(reduce_on_gpu(ks, "u64", "sum", i)) == n * (n - 1) // 2
+    # double accumulation: exact past 2^24, rounded to float32 once at the end
+    assert float(reduce_on_gpu(ks, "f32", "sum", np.ones(n, np.float32))) == float(np.float32(n))
+    # Fibonacci matrices: the ordered product of n copies of [[1,1],[1,0]]
+    m = 70 * 1024 + 5
+    x = np.tile(np.array([[1, 1, 1, 0]], dtype=np.uint32), (m, 1))
+    a, b, mask = 1, 0, (1 << 32) - 1
+    for _ in range(m):
+        a, b = (a + b) & mask, a
+    assert reduce_on_gpu(ks, "mat2_u32", "mat2_mul", x).tolist() == [a, b, b, (a - b) & mask]
+    # alternating non-commuting factors: order kept across lanes, runs, waves and workgroups
+    y = np.where((np.arange(3_000_001) % 2 == 0)[:, None], np.array([[1, 1, 0, 1]]), np.array([[1, 0, 1, 1]])).astype(np.uint32)
+    assert reduce_on_gpu(ks, "mat2_u32", "mat2_mul", y).tolist() == oracle.mapreduce("identity", "mat2", "u32", y).tolist()
+
+
+def test_back_to_back_with_scans_on_the_same_stream(ks):
+    # the reduction shares the stream's scratch and epoch counter with ks_scan: interleave them,
+    # sizes going up and down; `out` inside the input is allowed
+    rng = np.random.default_rng(5)
+    for it in range(12):
+        n = int(rng.integers(1, 6_000_000))
+        x = rng.integers(-1000, 1000, size=n).astype(np.int32)
+        d = to_device(x)
+        scanned = torch.empty_like(d)
+        ks.ks_scan(d, scanned, dtype="i32", op="sum")
+        total = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ks.ks_mapreduce(d, total, dtype="i32", op="sum")
+        ks.ks_mapreduce(d, d[:1], dtype="i32", op="max")          # result over the first input element
+        ks.ks_scan_check()
+        say(f"[case] scan + mapreduce interleaved, n={n}")
+        assert int(total[0]) == int(scanned[-1]) == int(np.sum(x, dtype=np.int32))
+        assert int(d[0]) == int(x.max())
+
+
+def test_full_size_configs(ks):
+    for name, n in (("f32_sum", 1 << 28), ("argmax", 1 << 26), ("affine", 1 << 26)):
+        w = ks_inputs.WORKLOADS[name]
+        oop, odt, _, _ = KINDS[(w.dtype, w.op)]
+        parts = [to_device(c) for c in ks_inputs.chunks(name, n)]
+        d_in = torch.cat(parts)
+        del parts
+        out = torch.empty_like(d_in[:1])
+        say(f"[case] mapreduce workload={name} n={n}")
+        ks.ks_mapreduce(d_in, out, dtype=w.dtype, op=w.op)
+        ks.ks_scan_check()
+        stream = oracle.ScanStream(oop, odt, True)
+        last = None
+        for c in ks_inputs.chunks(name, n):
+            last = stream.feed(c)[-1]
+        got = to_host(out, next(iter(ks_inputs.chunks(name, 1))).dtype)[0]
+        check(w.dtype, w.op, got, last, name)
+        del d_in
+
+
+def test_recorded_into_a_graph(ks):
+    n = 3_000_001
+    xs = [np.random.default_rng(90 + r).integers(-50, 50, size=n).astype(np.int32) for r in range(3)]
+    d_in = to_device(xs[0])
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        ks.ks_mapreduce(d_in, out, dtype="i32", op="sum")     # eager first: allocates the stream's scratch
+    ks.ks_scan_check(s)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        ks.ks_mapreduce(d_in, out, dtype="i32", op="sum")
+    for r in range(3):
+        d_in.copy_(to_device(xs[r]))
+        out.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            graph.replay()
+            graph.replay()
+        ks.ks_scan_check(s)
+        say(f"[case] mapreduce graph replay {r}")
+        assert int(out[0]) == int(np.sum(xs[r], dtype=np.int32))
