@@ -101,6 +101,25 @@ def random_mat2(n: int, seed: int) -> np.ndarray:
     return np.random.default_rng(seed).integers(0, 1 << 32, size=(n, 4), dtype=np.uint32)
 
 
+def random_mat2_wide(n: int, seed: int) -> np.ndarray:
+    """n random 2x2 uint64 matrices, row-major (n, 4): the 32-byte exact non-commutative test type."""
+    return np.random.default_rng(seed).integers(0, 1 << 64, size=(n, 4), dtype=np.uint64)
+
+
+RANGE_DTYPE = np.dtype([("lo", "<i4"), ("hi", "<i4"), ("cnt", "<u4")])
+
+
+def random_ranges(n: int, seed: int) -> np.ndarray:
+    """n elements {x, x, c} of the 12-byte range-with-count type: x a random walk (new minima and maxima
+    keep appearing), c a random count so that the sums wrap."""
+    rng = np.random.default_rng(seed)
+    x = np.cumsum(rng.integers(-1000, 1001, size=n)).astype(np.int32)
+    out = np.empty(n, dtype=RANGE_DTYPE)
+    out["lo"], out["hi"] = x, x
+    out["cnt"] = rng.integers(0, 1 << 32, size=n, dtype=np.uint32)
+    return out
+
+
 def random_unit_quats(n: int, seed: int) -> np.ndarray:
     """n unit quaternions (w, x, y, z) as float32 (n, 4)."""
     q = np.random.default_rng(seed).normal(size=(n, 4))

@@ -31,6 +31,7 @@ _SRC = os.path.join(_HERE, "scan_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle_scan.so")
 
 ARGMAX_DTYPE = np.dtype([("v", "<i4"), ("idx", "<i4"), ("cnt", "<i8")])
+RANGE_DTYPE = np.dtype([("lo", "<i4"), ("hi", "<i4"), ("cnt", "<u4")])     # 12 bytes
 
 
 def build(force: bool = False) -> str:
@@ -84,6 +85,14 @@ class _Mat2State(ctypes.Structure):
     _fields_ = [("acc", ctypes.c_uint32 * 4), ("started", ctypes.c_int)]
 
 
+class _Mat2WideState(ctypes.Structure):
+    _fields_ = [("acc", ctypes.c_uint64 * 4), ("started", ctypes.c_int)]
+
+
+class _RangeState(ctypes.Structure):
+    _fields_ = [("acc", ctypes.c_int32 * 3), ("started", ctypes.c_int)]
+
+
 class _QuatState(ctypes.Structure):
     _fields_ = [("q", ctypes.c_double * 4), ("started", ctypes.c_int)]
 
@@ -106,9 +115,10 @@ class ScanStream:
     """A scan fed in chunks; the running value is carried between feed() calls.
 
     kind is one of: ("sum"|"min"|"max", "i32"|"u32"|"i64"|"u64"|"f32"|"f64"),
-    ("affine", "f32"), ("argmax", None), ("mat2", "u32"), ("quat", "f32").
-    Shapes: scalars (n,), affine (n, 2), quat (n, 4), mat2 (n, 4) uint32,
-    argmax (n,) of ARGMAX_DTYPE.
+    ("affine", "f32"), ("argmax", None), ("mat2", "u32"), ("mat2", "u64"), ("range", None),
+    ("quat", "f32").
+    Shapes: scalars (n,), affine (n, 2), quat (n, 4), mat2 (n, 4) uint32 or uint64,
+    argmax (n,) of ARGMAX_DTYPE, range (n,) of RANGE_DTYPE.
     """
 
     def __init__(self, op: str, dt: str | None, inclusive: bool = True):
@@ -123,9 +133,15 @@ class ScanStream:
         elif op == "argmax":
             sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
                 "oracle_argmax", ARGMAX_DTYPE, ARGMAX_DTYPE, _ArgmaxState, 1
+        elif op == "mat2" and dt == "u64":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_mat2_u64", np.uint64, np.uint64, _Mat2WideState, 4
         elif op == "mat2":
             sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
                 "oracle_mat2_u32", np.uint32, np.uint32, _Mat2State, 4
+        elif op == "range":
+            sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
+                "oracle_range_i32", RANGE_DTYPE, RANGE_DTYPE, _RangeState, 1
         elif op == "quat":
             sym, self.in_dtype, self.out_dtype, state_cls, self.width = \
                 "oracle_quat_f32", np.float32, np.float64, _QuatState, 4
@@ -207,7 +223,9 @@ def identity_of(op: str, dt: str | None):
     if op == "argmax":
         return np.array([(np.iinfo(np.int32).min, np.iinfo(np.int32).max, 0)], dtype=ARGMAX_DTYPE)[0]
     if op == "mat2":
-        return np.array([1, 0, 0, 1], dtype=np.uint32)
+        return np.array([1, 0, 0, 1], dtype=np.uint64 if dt == "u64" else np.uint32)
+    if op == "range":
+        return np.array([(np.iinfo(np.int32).max, np.iinfo(np.int32).min, 0)], dtype=RANGE_DTYPE)[0]
     if op == "quat":
         return np.array([1.0, 0.0, 0.0, 0.0])
     raise KeyError(op)

@@ -224,3 +224,65 @@ void oracle_quat_f32(const float *in, double *out, size_t n, int inclusive,
         state->q[0] = nw; state->q[1] = nx; state->q[2] = ny; state->q[3] = nz;
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* 2x2 matrix product over Z / 2^64: a 32-byte element                 */
+/* ------------------------------------------------------------------ */
+/*
+ * The same operator as above on 64-bit entries (paper Sec. IV-A: elements may
+ * be any struct of plain fields, whatever their size).  Row-major {m00, m01,
+ * m10, m11}; L op R = L * R, entries mod 2^64; identity = I.
+ */
+typedef struct { uint64_t m[4]; } oracle_mat2w_t;
+typedef struct { oracle_mat2w_t acc; int started; } oracle_mat2w_state;
+
+void oracle_mat2_u64(const oracle_mat2w_t *in, oracle_mat2w_t *out, size_t n,
+                     int inclusive, oracle_mat2w_state *state)
+{
+    for (size_t i = 0; i < n; ++i) {
+        if (!state->started) {
+            state->started = 1;
+            if (inclusive) { state->acc = in[i]; out[i] = in[i]; continue; }
+            state->acc.m[0] = 1; state->acc.m[1] = 0; state->acc.m[2] = 0; state->acc.m[3] = 1;
+        }
+        const oracle_mat2w_t l = state->acc, r = in[i];
+        oracle_mat2w_t next;
+        next.m[0] = l.m[0] * r.m[0] + l.m[1] * r.m[2];
+        next.m[1] = l.m[0] * r.m[1] + l.m[1] * r.m[3];
+        next.m[2] = l.m[2] * r.m[0] + l.m[3] * r.m[2];
+        next.m[3] = l.m[2] * r.m[1] + l.m[3] * r.m[3];
+        out[i] = inclusive ? next : state->acc;
+        state->acc = next;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* running range with count: a 12-byte element                         */
+/* ------------------------------------------------------------------ */
+/*
+ * Element {lo, hi, cnt}: the smallest and the largest value seen and how many
+ * (an input element is {x, x, 1}).  L op R = {min(L.lo, R.lo), max(L.hi, R.hi),
+ * L.cnt + R.cnt mod 2^32}.  Identity {INT32_MAX, INT32_MIN, 0}.  Commutative.
+ * Twelve bytes: a size that is not a power of two (paper Sec. IV-A).
+ */
+typedef struct { int32_t lo; int32_t hi; uint32_t cnt; } oracle_range_t;
+typedef struct { oracle_range_t acc; int started; } oracle_range_state;
+
+void oracle_range_i32(const oracle_range_t *in, oracle_range_t *out, size_t n,
+                      int inclusive, oracle_range_state *state)
+{
+    for (size_t i = 0; i < n; ++i) {
+        if (!state->started) {
+            state->started = 1;
+            if (inclusive) { state->acc = in[i]; out[i] = in[i]; continue; }
+            state->acc.lo = INT32_MAX; state->acc.hi = INT32_MIN; state->acc.cnt = 0;
+        }
+        const oracle_range_t l = state->acc, r = in[i];
+        oracle_range_t next;
+        next.lo = r.lo < l.lo ? r.lo : l.lo;
+        next.hi = r.hi > l.hi ? r.hi : l.hi;
+        next.cnt = l.cnt + r.cnt;
+        out[i] = inclusive ? next : state->acc;
+        state->acc = next;
+    }
+}

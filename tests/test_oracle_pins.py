@@ -517,3 +517,49 @@ def test_nonzero_sum_numbers_the_kept_elements_of_a_compaction():
     compacted = np.empty(len(kept), dtype=np.int32)
     compacted[excl[kept]] = x[kept]
     assert np.array_equal(compacted, x[x != 0])
+
+
+# ---------------------------------------------------------------- element types wider than / not a power of two of 16 bytes
+
+def test_mat2_u64_hand_product_fibonacci_and_big_integers():
+    # hand-worked: [[1,2],[3,4]] * [[5,6],[7,8]] = [[19,22],[43,50]], and the other order differs
+    a, b = [1, 2, 3, 4], [5, 6, 7, 8]
+    x = np.array([a, b], dtype=np.uint64)
+    assert oracle.scan("mat2", "u64", x)[1].tolist() == [19, 22, 43, 50]
+    assert oracle.scan("mat2", "u64", x[::-1].copy())[1].tolist() == [23, 34, 31, 46]
+    # Fibonacci closed form mod 2^64: [[1,1],[1,0]]^k = [[F(k+1), F(k)], [F(k), F(k-1)]]
+    n = 500
+    out = oracle.scan("mat2", "u64", np.tile(np.array([[1, 1, 1, 0]], dtype=np.uint64), (n, 1)))
+    f0, f1, mask = 0, 1, (1 << 64) - 1
+    for k in range(1, n + 1):
+        f0, f1 = f1, f0 + f1                       # f0 = F(k), f1 = F(k+1), exact Python integers
+        assert out[k - 1].tolist() == [f1 & mask, f0 & mask, f0 & mask, (f1 - f0) & mask]
+    # random matrices against Python big integers, inclusive and exclusive
+    m = ks_inputs.random_mat2_wide(200, seed=5)
+    inc, exc = oracle.scan("mat2", "u64", m, True), oracle.scan("mat2", "u64", m, False)
+    p = [1, 0, 0, 1]
+    for i, (e, f, g, h) in enumerate(m.tolist()):
+        assert exc[i].tolist() == [v & mask for v in p]
+        p = [p[0] * e + p[1] * g, p[0] * f + p[1] * h, p[2] * e + p[3] * g, p[2] * f + p[3] * h]
+        p = [v & mask for v in p]
+        assert inc[i].tolist() == p
+    # streamed in chunks = one shot
+    s = oracle.ScanStream("mat2", "u64", True)
+    assert np.array_equal(np.concatenate([s.feed(m[:77]), s.feed(m[77:])]), inc)
+
+
+def test_range_with_count_is_running_min_max_and_count():
+    x = ks_inputs.random_ranges(50_000, seed=6)
+    assert x.dtype.itemsize == 12
+    inc, exc = oracle.scan("range", None, x, True), oracle.scan("range", None, x, False)
+    assert np.array_equal(inc["lo"], np.minimum.accumulate(x["lo"]))
+    assert np.array_equal(inc["hi"], np.maximum.accumulate(x["hi"]))
+    assert np.array_equal(inc["cnt"], np.cumsum(x["cnt"].astype(np.uint64)).astype(np.uint32))   # mod 2^32
+    assert (int(exc[0]["lo"]), int(exc[0]["hi"]), int(exc[0]["cnt"])) == (2 ** 31 - 1, -2 ** 31, 0)
+    assert np.array_equal(exc[1:], inc[:-1])
+    # commutative and associative: every order of six elements folds to the same value
+    import itertools
+    six = x[:6]
+    want = oracle.mapreduce("identity", "range", None, six)
+    for perm in itertools.permutations(range(6)):
+        assert oracle.mapreduce("identity", "range", None, six[list(perm)]) == want
