@@ -13,6 +13,11 @@
  *     to the element's alignment (4 or 8 bytes, see ks_dtype).  Nothing more
  *     is needed: every access is a range-checked 16-byte buffer instruction,
  *     so slices that start at any element run at the same speed.
+ *   - Element sizes (paper Sec. IV-A: any struct of plain fields): 4, 8 and 16
+ *     bytes run in every kernel shape; other sizes that divide 128 or 144 bytes
+ *     (here 12 and 32) run in the one shape where a lane holds 8 or 9
+ *     consecutive 16-byte granules, in both strategies and in ks_scan_strided;
+ *     ks_mapreduce and the shape options "waves" / "form" do not apply to them.
  *   - in == out (exactly in place) is allowed; any other overlap is rejected.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise (except ks_scan_check)
@@ -53,7 +58,9 @@ typedef enum {
     KS_ARGMAX_I32_CNT64 = 7, /* struct { int32_t v; int32_t idx; int64_t cnt; }     16 B */
     KS_MAT2_U32 = 8,         /* struct { uint32_t m00, m01, m10, m11; } row-major   16 B */
     KS_QUAT_F32 = 9,         /* struct { float w, x, y, z; }                        16 B */
-    KS_DTYPE_COUNT = 10
+    KS_MAT2_U64 = 10,        /* struct { uint64_t m00, m01, m10, m11; } row-major   32 B */
+    KS_RANGE_I32_CNT32 = 11, /* struct { int32_t lo, hi; uint32_t cnt; }            12 B */
+    KS_DTYPE_COUNT = 12
 } ks_dtype;
 
 /* Operators; L is the accumulated (earlier) operand, R the later one. */
@@ -64,10 +71,13 @@ typedef enum {
     KS_AFFINE_COMPOSE = 3, /* apply L then R: (R.a*L.a, R.a*L.b + R.b); identity (1,0)           */
     KS_ARGMAX_COUNT = 4,   /* larger v wins, equal v: lower idx wins; cnt adds (wraps);
                               identity {INT32_MIN, INT32_MAX, 0}                                 */
-    KS_MAT2_MUL = 5,       /* 2x2 matrix product L*R, entries mod 2^32; identity I               */
+    KS_MAT2_MUL = 5,       /* 2x2 matrix product L*R, entries mod 2^32 (KS_MAT2_U32) or 2^64
+                              (KS_MAT2_U64); identity I                                          */
     KS_QUAT_MUL = 6,       /* Hamilton product L*R (paper Sec. V-B, non-commutative example);
                               identity (1,0,0,0)                                                 */
-    KS_OP_COUNT = 7
+    KS_RANGE_COUNT = 7,    /* {min(L.lo, R.lo), max(L.hi, R.hi), L.cnt + R.cnt mod 2^32}; identity
+                              {INT32_MAX, INT32_MIN, 0}                                          */
+    KS_OP_COUNT = 8
 } ks_op;
 
 /* Cross-workgroup strategy. */

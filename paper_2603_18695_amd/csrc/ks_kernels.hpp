@@ -552,7 +552,7 @@ __device__ __forceinline__ void blocked_data_wave_loop(
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     typename ChainOf<Op>::op cop;
-    using S = TileShape<IO, ROWS>;
+    using S = BlockedShape<IO, ROWS>;
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
     Op op;
     const size_t shift = tile_shift(out, TILE);   // see data_wave_loop
@@ -579,11 +579,11 @@ __device__ __forceinline__ void blocked_data_wave_loop(
     for (;;) {
         const uint32_t tile = __builtin_amdgcn_readfirstlane(loop_tile);   // see data_wave_loop
         if (drawing) x.q.next_tile = drawn;
-        ThreadItems<A, ROWS, S::G> cur;
+        LaneItems<A, S::E> cur;
         A lane_before;
         striped_to_blocked<ROWS>(region, raw);
         unpack_blocked<IO, ROWS, Op>(raw, run_bytes, valid_bytes, tile + 1 == a.ntiles || (tile == 0 && shift != 0), cur);
-        const A wave_total = scan_blocked_run<A, ROWS, S::G, Op>(cur, lane_before, op);
+        const A wave_total = scan_blocked_run<A, S::E, Op>(cur, lane_before, op);
         if (lane == 0) x.tot[wave] = to_words(wave_total);
         __syncthreads();
         const uint32_t next = next_tile_of(a, x.q, tile);
@@ -758,49 +758,95 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_kernel(const IO *i
 // Reduce-then-scan (no waiting between workgroups; one workgroup per tile).
 // Aggregates and seeds are arrays of the operator's chain type.
 // ---------------------------------------------------------------------------
-template <class IO, class Op, int ROWS>
+// BLOCKED: the blocked arrangement of ks_tile.hpp (every wave exchanges its granules through a
+// region of LDS of its own), which is what serves element sizes other than 4, 8 and 16 bytes;
+// otherwise the striped arrangement.
+template <class IO, int ROWS, bool BLOCKED>
+constexpr size_t rts_tile_elems() {
+    if constexpr (BLOCKED) return (size_t)kWaves * BlockedShape<IO, ROWS>::WAVE_ELEMS;
+    else return (size_t)kWaves * TileShape<IO, ROWS>::WAVE_ELEMS;
+}
+
+template <class IO, class Op, int ROWS, bool BLOCKED>
 __global__ __launch_bounds__(kBlock) void tile_reduce_kernel(const IO *__restrict__ in, size_t n,
                                                              typename ChainOf<Op>::type *__restrict__ aggregates) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
-    using S = TileShape<IO, ROWS>;
-    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    constexpr size_t TILE = rts_tile_elems<IO, ROWS, BLOCKED>();
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
     Op op;
     const size_t tile = blockIdx.x;
-    const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
-    ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
-    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+    const int wave = threadIdx.x >> 6;
+    const int lane_bytes = lane_tile_bytes<ROWS>(wave);
+    const TileWindow w = tile_window<IO>(in, n, tile * TILE, TILE);
+    const bool partial = (tile + 1) * TILE > n;
+    A wave_total;
+    if constexpr (BLOCKED) {
+        __shared__ u32x4 stage[kWaves * Stage<ROWS>::SLOTS];
+        RawItems<ROWS> raw;
+        load_raw<ROWS, false>(w, lane_bytes, raw);
+        striped_to_blocked<ROWS>(stage + wave * Stage<ROWS>::SLOTS, raw);
+        LaneItems<A, BlockedShape<IO, ROWS>::E> cur;
+        unpack_blocked<IO, ROWS, Op>(raw, wave * (kWave * ROWS * 16), w.valid_bytes, partial, cur);
+        A lane_before;
+        wave_total = scan_blocked_run<A, BlockedShape<IO, ROWS>::E, Op>(cur, lane_before, op);
+    } else {
+        using S = TileShape<IO, ROWS>;
+        ThreadItems<A, ROWS, S::G> cur;
+        load_items<IO, ROWS, Op, false>(w, lane_bytes, partial, cur);
+        wave_total = scan_wave_run<A, ROWS, S::G, Op>(cur, op).wave_total;
+    }
     C aggregate;
-    (void)exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
+    (void)exchange_wave_totals<Op, kWaves>(s_tot, wave_total, aggregate);
     if (threadIdx.x == 0) aggregates[tile] = aggregate;
 }
 
 // seeds == nullptr: every tile starts from the identity (used when one tile
 // covers the whole input).  Otherwise seeds[tile] = combination of all earlier tiles.
-template <class IO, class Op, int ROWS, bool INCLUSIVE>
+template <class IO, class Op, int ROWS, bool INCLUSIVE, bool BLOCKED>
 __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out, size_t n,
                                                            const typename ChainOf<Op>::type *__restrict__ seeds) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
     COp cop;
-    using S = TileShape<IO, ROWS>;
-    constexpr size_t TILE = (size_t)kWaves * S::WAVE_ELEMS;
+    constexpr size_t TILE = rts_tile_elems<IO, ROWS, BLOCKED>();
     __shared__ typename WordsOf<A>::type s_tot[kWaves];
     Op op;
     const size_t tile = blockIdx.x;
-    const int lane_bytes = lane_tile_bytes<ROWS>(threadIdx.x >> 6);
-    ThreadItems<A, ROWS, S::G> cur;
-    load_items<IO, ROWS, Op, false>(tile_window<IO>(in, n, tile * TILE, TILE), lane_bytes, (tile + 1) * TILE > n, cur);
-    const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
-    C aggregate;
-    const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
-    finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
+    const int wave = threadIdx.x >> 6;
+    const int lane_bytes = lane_tile_bytes<ROWS>(wave);
+    const TileWindow w = tile_window<IO>(in, n, tile * TILE, TILE);
+    const TileWindow wo = tile_window<IO>(out, n, tile * TILE, TILE);
+    const bool partial = (tile + 1) * TILE > n;
     const C seed = seeds ? seeds[tile] : COp::identity();
-    apply_prefix_and_store<IO, ROWS, A, Op, false>(tile_window<IO>(out, n, tile * TILE, TILE), lane_bytes, cur,
-                                               convert<A>(cop(seed, wave_carry)), op);
+    if constexpr (BLOCKED) {
+        __shared__ u32x4 stage[kWaves * Stage<ROWS>::SLOTS];
+        u32x4 *region = stage + wave * Stage<ROWS>::SLOTS;
+        RawItems<ROWS> raw;
+        load_raw<ROWS, false>(w, lane_bytes, raw);
+        striped_to_blocked<ROWS>(region, raw);
+        LaneItems<A, BlockedShape<IO, ROWS>::E> cur;
+        unpack_blocked<IO, ROWS, Op>(raw, wave * (kWave * ROWS * 16), w.valid_bytes, partial, cur);
+        A lane_before;
+        const A wave_total = scan_blocked_run<A, BlockedShape<IO, ROWS>::E, Op>(cur, lane_before, op);
+        C aggregate;
+        const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, wave_total, aggregate);
+        const A before = op(convert<A>(cop(seed, wave_carry)), lane_before);
+        RawItems<ROWS> result;
+        apply_blocked<INCLUSIVE, IO, ROWS, A, Op>(cur, before, op, result);
+        blocked_to_striped<ROWS>(region, result);
+        store_raw<ROWS, false>(wo, lane_bytes, result);
+    } else {
+        using S = TileShape<IO, ROWS>;
+        ThreadItems<A, ROWS, S::G> cur;
+        load_items<IO, ROWS, Op, false>(w, lane_bytes, partial, cur);
+        const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, S::G, Op>(cur, op);
+        C aggregate;
+        const C wave_carry = exchange_wave_totals<Op, kWaves>(s_tot, ws.wave_total, aggregate);
+        finish_wave_run<INCLUSIVE, A, ROWS, S::G, Op>(cur, ws, op);
+        apply_prefix_and_store<IO, ROWS, A, Op, false>(wo, lane_bytes, cur, convert<A>(cop(seed, wave_carry)), op);
+    }
 }
 
 // Single-pass scan of a strided view (element i at base[i * stride], paper Sec. IV-C): the

@@ -36,6 +36,10 @@ struct Shape {
 template <class T, class A, int WAVES, int ROWS, bool PREFETCH, int FORM>
 constexpr bool variant_fits() {
     if (dedicated_lookback_wave(WAVES) != (FORM != kFormCommon)) return false;   // see scan_lookback_kernel
+    // element sizes other than 4, 8 and 16 bytes: the blocked arrangement only, and the lane's ROWS
+    // granules have to hold whole elements
+    if (!granule_sized<T>() && (FORM != kFormBlocked || !blocked_fits<T, ROWS>())) return false;
+    if (FORM == kFormBlocked && !blocked_fits<T, ROWS>()) return false;
     if (WAVES == 16 && ROWS == 4) return false;                   // never competitive, not compiled
     if (FORM == kFormBlocked)   // bounded by LDS; every element type compiles without spills at 8 and 9 rows
         return (size_t)(WAVES - 1) * Stage<ROWS>::SLOTS * 16 <= 150 * 1024;
@@ -69,6 +73,7 @@ struct PairDefaults {
     using A = typename Op::acc;
     static constexpr bool kSum = std::is_same<typename MapOf<Op>::unmapped, SumOp<T>>::value;
     static constexpr Shape shape() {
+        if (!granule_sized<T>()) return Shape{16, blocked_fits<T, 9>() ? 9 : 8, true, kFormBlocked};
         if (sizeof(A) == 4) return Shape{16, 9, true, kFormSeparate};
         // 8-byte scalars, sums: 8 rows in striped separate loops measure 1 % above 9 rows blocked
         // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s).  Minimum and maximum of 8-byte values
@@ -95,6 +100,7 @@ struct PairDefaults {
     // 1 MiB 6.8 / 7.4; at 4 MiB the blocked shape is ahead, 7.7 / 8.8).
     static constexpr size_t kSmallInputBytes16 = (size_t)1 << 20;
     static constexpr Shape shape_for(size_t n) {
+        if (!granule_sized<T>()) return shape();   // one shape at every size
         if (sizeof(T) >= 16 && n * sizeof(T) <= kSmallInputBytes16) return Shape{4, 4, true, kFormCommon};
         if (sizeof(T) < 16 && n * sizeof(T) <= kSmallInputBytes) return small_shape();
         if (sizeof(T) < 16 && n * sizeof(T) <= kMidInputBytes) return mid_shape();
@@ -109,11 +115,16 @@ struct Pair {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     static constexpr int W = WordsOf<C>::W;
-    static constexpr int kRtsRows = 4;
+    // The reduce-then-scan kernels run 4 waves x 4 rows in the striped arrangement; element sizes
+    // other than 4, 8 and 16 bytes take the blocked arrangement with the rows of their look-back shape.
+    static constexpr bool kRtsBlocked = !granule_sized<T>();
+    static constexpr int kRtsRows = kRtsBlocked ? PairDefaults<T, Op>::shape().rows : 4;
     static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
 
-    static size_t tile_elems(int rows) { return (size_t)kWaves * kWave * rows * (16 / sizeof(T)); }
-    static size_t shape_tile_elems(int waves, int rows) { return (size_t)data_waves(waves) * kWave * rows * (16 / sizeof(T)); }
+    // elements in `granules` 16-byte granules (callers pass whole tiles, which hold whole elements)
+    static size_t granule_elems(size_t granules) { return granules * 16 / sizeof(T); }
+    static size_t tile_elems(int rows) { return granule_elems((size_t)kWaves * kWave * rows); }
+    static size_t shape_tile_elems(int waves, int rows) { return granule_elems((size_t)data_waves(waves) * kWave * rows); }
 
     static size_t desc_bytes(size_t count) { return align_up((count > 0 ? count : 1) * W * sizeof(uint64_t), 256); }
 
@@ -183,7 +194,7 @@ struct Pair {
         if (algo == KS_ALGO_LOOKBACK) {
             // sized for the smallest tile any compiled variant uses, so a later change of the
             // shape options cannot outgrow a buffer sized earlier
-            const size_t tiles = ceil_div(n, (size_t)kMinTileGranules * (16 / sizeof(T)));
+            const size_t tiles = ceil_div(n * sizeof(T), (size_t)kMinTileGranules * 16);
             return lookback_scratch_bytes(tiles + 1);   // + 1: tile 0 may be cut short (output-aligned tiles)
         }
         size_t total = 0, m = n;
@@ -192,7 +203,7 @@ struct Pair {
             m = ceil_div(m, tile);
             total = align_up(m * sizeof(C), 256);
             using Upper = Pair<C, typename ChainOf<Op>::op>;
-            if (m > Upper::tile_elems(kRtsRows)) total += Upper::temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, m);
+            if (m > Upper::tile_elems(Upper::kRtsRows)) total += Upper::temp_bytes(KS_ALGO_REDUCE_THEN_SCAN, m);
         }
         return total > 0 ? total : 256;
     }
@@ -345,10 +356,10 @@ struct Pair {
     static int launch_tile_scan(bool inclusive, const T *in, T *out, size_t n, const C *seeds, hipStream_t s) {
         const size_t tiles = ceil_div(n, tile_elems(kRtsRows));
         if (inclusive)
-            hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, true>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in,
+            hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, true, kRtsBlocked>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in,
                                out, n, seeds);
         else
-            hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, false>), dim3((unsigned)tiles), dim3(kBlock), 0, s,
+            hipLaunchKernelGGL((tile_scan_kernel<T, Op, kRtsRows, false, kRtsBlocked>), dim3((unsigned)tiles), dim3(kBlock), 0, s,
                                in, out, n, seeds);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
@@ -361,7 +372,7 @@ struct Pair {
         const size_t need = align_up(tiles * sizeof(C), 256);
         if (need > temp_bytes) return KS_ERR_WORKSPACE;
         C *agg = reinterpret_cast<C *>(temp);
-        hipLaunchKernelGGL((tile_reduce_kernel<T, Op, kRtsRows>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in, n, agg);
+        hipLaunchKernelGGL((tile_reduce_kernel<T, Op, kRtsRows, kRtsBlocked>), dim3((unsigned)tiles), dim3(kBlock), 0, s, in, n, agg);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return set_hip_error(e);
         // aggregates -> exclusive prefixes of the tiles, in place (scratch is 256-byte aligned)
@@ -378,7 +389,7 @@ struct Pair {
     static constexpr int kStridedRows = sizeof(A) >= 16 ? 8 : 16;
     static constexpr size_t kStridedTile = (size_t)kWaves * kWave * kStridedRows;
     // temp_bytes(KS_ALGO_LOOKBACK, n) sizes the descriptors for the smallest contiguous tile
-    static_assert(kStridedTile >= (size_t)kMinTileGranules * (16 / sizeof(T)), "strided tile below the smallest tile");
+    static_assert(kStridedTile * sizeof(T) >= (size_t)kMinTileGranules * 16, "strided tile below the smallest tile");
     template <bool INCLUSIVE>
     static int launch_lookback_strided(const ScanCall &c) {
         auto kernel = scan_lookback_strided_kernel<T, Op, kStridedRows, INCLUSIVE>;
@@ -412,9 +423,16 @@ struct Pair {
     // 5058, 4 x 8 4930, 8 x 2 4633; affine 8 x 8 5305, 2 x 8 5521, 4 x 2 4860.
     static constexpr int kReduceRows = Op::commutative ? 4 : 8;
     static constexpr int kReduceWgsPerCu = Op::commutative ? 2 : 8;
-    static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * (16 / sizeof(T));   // elements per run
+    static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * 16 / sizeof(T);   // elements per run
     static size_t reduce_scratch_bytes(size_t grid) { return kControlBytes + desc_bytes(grid); }
     static int run_mapreduce(const ScanCall &c) {
+        if constexpr (!granule_sized<T>()) {
+            return KS_ERR_UNSUPPORTED;   // the reduction kernel is written for the striped arrangement
+        } else {
+            return run_mapreduce_striped(c);
+        }
+    }
+    static int run_mapreduce_striped(const ScanCall &c) {
         auto kernel = mapreduce_kernel<T, Op, kReduceRows>;
         static std::map<int, int> reported_per_cu;
         int per_cu = 0;

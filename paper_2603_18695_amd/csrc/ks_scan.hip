@@ -321,6 +321,8 @@ size_t ks_elem_bytes(ks_dtype dtype) {
         case KS_I32: case KS_U32: case KS_F32: return 4;
         case KS_I64: case KS_U64: case KS_F64: case KS_AFFINE_F32: return 8;
         case KS_ARGMAX_I32_CNT64: case KS_MAT2_U32: case KS_QUAT_F32: return 16;
+        case KS_MAT2_U64: return 32;
+        case KS_RANGE_I32_CNT32: return 12;
         default: return 0;
     }
 }

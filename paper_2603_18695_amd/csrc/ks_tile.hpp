@@ -23,9 +23,14 @@ namespace ks {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Element sizes that fit a 16-byte granule a whole number of times run in every arrangement;
+// the others only in the blocked one (BlockedShape, below).
+template <class IO>
+constexpr bool granule_sized() { return sizeof(IO) == 4 || sizeof(IO) == 8 || sizeof(IO) == 16; }
+
 template <class IO, int ROWS_>
 struct TileShape {
-    static_assert(sizeof(IO) == 4 || sizeof(IO) == 8 || sizeof(IO) == 16, "element must be 4, 8 or 16 bytes");
+    static_assert(granule_sized<IO>(), "element must be 4, 8 or 16 bytes in the striped arrangement");
     static constexpr int ROWS = ROWS_;
     static constexpr int G = 16 / (int)sizeof(IO);  // elements per 16-byte granule
     static constexpr int ITEMS = ROWS * G;          // elements per thread
@@ -331,76 +336,78 @@ __device__ __forceinline__ void blocked_to_striped(u32x4 *region, RawItems<ROWS>
     for (int j = 0; j < ROWS; ++j) r.v[j] = region[stage_slot_of_striped<ROWS>(j, lane)];
 }
 
-// Blocked raw granules -> accumulation type; x[i][k] = element k of the lane's
-// i-th consecutive granule.  run_bytes = byte offset of the wave's run inside
+// In the blocked view a lane holds ROWS consecutive granules, i.e. ROWS * 16 consecutive bytes of
+// the wave's run: E whole elements of any size that divides that (ROWS = 8: 128 bytes, ROWS = 9:
+// 144 bytes).  This is what serves elements that are not 4, 8 or 16 bytes: the global accesses
+// stay 16-byte granules whatever the element (paper Sec. IV-A: composite types of any size).
+template <class IO, int ROWS>
+struct BlockedShape {
+    static_assert((ROWS * 16) % sizeof(IO) == 0, "the element size must divide the lane's ROWS * 16 bytes");
+    static constexpr int E = ROWS * 16 / (int)sizeof(IO);   // elements per lane
+    static constexpr int WAVE_ELEMS = kWave * E;
+};
+template <class IO, int ROWS>
+constexpr bool blocked_fits() { return (ROWS * 16) % sizeof(IO) == 0; }
+
+// Items of one lane in the blocked view: y[k] = the lane's k-th consecutive element.
+template <class A, int E>
+struct LaneItems {
+    A y[E];
+};
+template <class IO, int E>
+struct LaneChunk {
+    IO e[E];
+};
+
+// Blocked raw granules -> accumulation type.  run_bytes = byte offset of the wave's run inside
 // the tile (for the identity fix-up of a partial tile).
 template <class IO, int ROWS, class Op>
 __device__ __forceinline__ void unpack_blocked(const RawItems<ROWS> &raw, int run_bytes, uint32_t valid_bytes, bool partial,
-                                               ThreadItems<typename Op::acc, ROWS, TileShape<IO, ROWS>::G> &it) {
+                                               LaneItems<typename Op::acc, BlockedShape<IO, ROWS>::E> &it) {
     using A = typename Op::acc;
-    constexpr int G = TileShape<IO, ROWS>::G;
+    constexpr int E = BlockedShape<IO, ROWS>::E;
+    const LaneChunk<IO, E> c = __builtin_bit_cast(LaneChunk<IO, E>, raw);
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-        Granule<IO, G> g = __builtin_bit_cast(Granule<IO, G>, raw.v[i]);
-#pragma unroll
-        for (int k = 0; k < G; ++k) it.x[i][k] = convert<A>(typename MapOf<Op>::type()(g.e[k]));
-    }
+    for (int k = 0; k < E; ++k) it.y[k] = convert<A>(typename MapOf<Op>::type()(c.e[k]));
     if (partial) {
         const int lane = threadIdx.x & (kWave - 1);
         const int at0 = pinned<true>(run_bytes + lane * (ROWS * 16));
 #pragma unroll
-        for (int i = 0; i < ROWS; ++i) {
-#pragma unroll
-            for (int k = 0; k < G; ++k) {
-                const int at = at0 + i * 16 + k * (int)sizeof(IO);
-                if ((uint32_t)at >= valid_bytes) it.x[i][k] = Op::identity();
-            }
+        for (int k = 0; k < E; ++k) {
+            if ((uint32_t)(at0 + k * (int)sizeof(IO)) >= valid_bytes) it.y[k] = Op::identity();
         }
     }
 }
 
-// Serial inclusive scan of the lane's ROWS * G consecutive elements, then one
-// wave scan of the lane totals.  Returns the combination of the whole run;
-// lane_before = combination of the lanes before this one.
-template <class A, int ROWS, int G, class Op>
-__device__ __forceinline__ A scan_blocked_run(ThreadItems<A, ROWS, G> &it, A &lane_before, Op op) {
+// Serial inclusive scan of the lane's E consecutive elements, then one wave scan of the lane
+// totals.  Returns the combination of the whole run; lane_before = combination of the lanes
+// before this one.
+template <class A, int E, class Op>
+__device__ __forceinline__ A scan_blocked_run(LaneItems<A, E> &it, A &lane_before, Op op) {
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-#pragma unroll
-        for (int k = 0; k < G; ++k) {
-            if (i == 0 && k == 0) continue;
-            const A &prev = (k == 0) ? it.x[i - 1][G - 1] : it.x[i][k - 1];
-            it.x[i][k] = op(prev, it.x[i][k]);
-        }
-    }
-    const A upto = wave_inclusive_scan(it.x[ROWS - 1][G - 1], op);
+    for (int k = 1; k < E; ++k) it.y[k] = op(it.y[k - 1], it.y[k]);
+    const A upto = wave_inclusive_scan(it.y[E - 1], op);
     lane_before = wave_shift_up(upto, Op::identity());
     return read_lane(upto, kWave - 1);
 }
 
-// Final outputs of the blocked view as raw granules: `before` (everything
-// before this lane's first element) in front of every item, shifted by one
-// element for the exclusive scan.
+// Final outputs of the blocked view as raw granules: `before` (everything before this lane's
+// first element) in front of every item, shifted by one element for the exclusive scan.
 template <bool INCLUSIVE, class IO, int ROWS, class A, class Op>
-__device__ __forceinline__ void apply_blocked(const ThreadItems<A, ROWS, TileShape<IO, ROWS>::G> &it, const A &before, Op op,
+__device__ __forceinline__ void apply_blocked(const LaneItems<A, BlockedShape<IO, ROWS>::E> &it, const A &before, Op op,
                                               RawItems<ROWS> &out) {
-    constexpr int G = TileShape<IO, ROWS>::G;
+    constexpr int E = BlockedShape<IO, ROWS>::E;
+    LaneChunk<IO, E> c;
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-        Granule<IO, G> g;
-#pragma unroll
-        for (int k = 0; k < G; ++k) {
-            if (INCLUSIVE) {
-                g.e[k] = convert<IO>(op(before, it.x[i][k]));
-            } else if (i == 0 && k == 0) {
-                g.e[k] = convert<IO>(before);
-            } else {
-                const A &prev = (k == 0) ? it.x[i - 1][G - 1] : it.x[i][k - 1];
-                g.e[k] = convert<IO>(op(before, prev));
-            }
-        }
-        out.v[i] = __builtin_bit_cast(u32x4, g);
+    for (int k = 0; k < E; ++k) {
+        if (INCLUSIVE)
+            c.e[k] = convert<IO>(op(before, it.y[k]));
+        else if (k == 0)
+            c.e[k] = convert<IO>(before);
+        else
+            c.e[k] = convert<IO>(op(before, it.y[k - 1]));
     }
+    out = __builtin_bit_cast(RawItems<ROWS>, c);
 }
 
 template <int ROWS, bool PIN>

@@ -8,9 +8,12 @@
 //     using chain = ...;                  // optional: a wider operator for everything above one wave's run
 // The element type in memory ("io" type) is converted to acc on load and back
 // on store (convert<>); for most pairs the two are the same type.  io types are
-// trivially copyable, 4, 8 or 16 bytes; acc types are a multiple of 4 bytes and
-// are moved between lanes and through memory as arrays of 32-bit words (paper
-// Sec. IV-A: any composite type is shuffled field by field as 32-bit pieces).
+// trivially copyable and a multiple of 4 bytes: 4, 8 and 16 bytes run in every
+// kernel shape, any other size that divides 128 or 144 bytes (12, 24, 32, 36, 48,
+// 64, 72 ...) in the blocked arrangement, where a lane holds 8 or 9 consecutive
+// 16-byte granules.  acc types are a multiple of 4 bytes and are moved between
+// lanes and through memory as arrays of 32-bit words (paper Sec. IV-A: any
+// composite type is shuffled field by field as 32-bit pieces).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -57,6 +60,13 @@ struct Mat2U32 {        // row-major 2x2 matrix over Z/2^32
 };
 struct QuatF32 {
     float w, x, y, z;
+};
+struct Mat2U64 {        // row-major 2x2 matrix over Z/2^64: a 32-byte element
+    uint64_t m00, m01, m10, m11;
+};
+struct RangeI32Cnt32 {  // smallest and largest value seen and how many: a 12-byte element
+    int32_t lo, hi;
+    uint32_t cnt;
 };
 
 // ---- limits for min / max identities ---------------------------------------
@@ -161,6 +171,25 @@ struct Mat2MulOp {
     __device__ __forceinline__ Mat2U32 operator()(Mat2U32 l, Mat2U32 r) const {
         return Mat2U32{l.m00 * r.m00 + l.m01 * r.m10, l.m00 * r.m01 + l.m01 * r.m11,
                        l.m10 * r.m00 + l.m11 * r.m10, l.m10 * r.m01 + l.m11 * r.m11};
+    }
+};
+
+struct Mat2WideMulOp {
+    static constexpr bool commutative = false;
+    using acc = Mat2U64;
+    __device__ static Mat2U64 identity() { return Mat2U64{1ull, 0ull, 0ull, 1ull}; }
+    __device__ __forceinline__ Mat2U64 operator()(Mat2U64 l, Mat2U64 r) const {
+        return Mat2U64{l.m00 * r.m00 + l.m01 * r.m10, l.m00 * r.m01 + l.m01 * r.m11,
+                       l.m10 * r.m00 + l.m11 * r.m10, l.m10 * r.m01 + l.m11 * r.m11};
+    }
+};
+
+struct RangeCountOp {
+    static constexpr bool commutative = true;
+    using acc = RangeI32Cnt32;
+    __device__ static RangeI32Cnt32 identity() { return RangeI32Cnt32{INT32_MAX, INT32_MIN, 0u}; }
+    __device__ __forceinline__ RangeI32Cnt32 operator()(RangeI32Cnt32 l, RangeI32Cnt32 r) const {
+        return RangeI32Cnt32{r.lo < l.lo ? r.lo : l.lo, r.hi > l.hi ? r.hi : l.hi, l.cnt + r.cnt};
     }
 };
 

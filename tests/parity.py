@@ -33,6 +33,8 @@ KINDS = {
     ("argmax_i32_cnt64", "argmax_count"): ("argmax", None, oracle.ARGMAX_DTYPE, 1),
     ("mat2_u32", "mat2_mul"): ("mat2", "u32", np.uint32, 4),
     ("quat_f32", "quat_mul"): ("quat", "f32", np.float32, 4),
+    ("mat2_u64", "mat2_mul"): ("mat2", "u64", np.uint64, 4),                       # 32-byte elements
+    ("range_i32_cnt32", "range_count"): ("range", None, oracle.RANGE_DTYPE, 1),     # 12-byte elements
 }
 FLOAT_TOL = {("f32", "sum"), ("f64", "sum"), ("affine_f32", "affine_compose"), ("quat_f32", "quat_mul")}
 
@@ -52,6 +54,10 @@ def random_input(dtype: str, op: str, n: int, seed: int) -> np.ndarray:
         return ks_inputs.random_mat2(n, seed)
     if dtype == "quat_f32":
         return ks_inputs.random_unit_quats(n, seed)
+    if dtype == "mat2_u64":
+        return ks_inputs.random_mat2_wide(n, seed)
+    if dtype == "range_i32_cnt32":
+        return ks_inputs.random_ranges(n, seed)
     if np.issubdtype(npdt, np.integer):
         info = np.iinfo(npdt)
         return rng.integers(info.min, info.max, size=n, dtype=npdt, endpoint=True)
@@ -86,10 +92,10 @@ def assert_matches(dtype: str, op: str, got: np.ndarray, ref: np.ndarray, what: 
             raise AssertionError(f"{what}: float mismatch, worst ratio {worst:.3g} at flat index {i}: "
                                  f"gpu={g.reshape(-1)[i]!r} ref={ref.reshape(-1)[i]!r}")
         return worst
-    g = got.reshape(ref.shape) if got.dtype != oracle.ARGMAX_DTYPE else got
+    g = got.reshape(ref.shape) if not got.dtype.names else got
     if g.tobytes() != ref.tobytes():
-        if g.dtype == oracle.ARGMAX_DTYPE:
-            bad = np.nonzero((g["v"] != ref["v"]) | (g["idx"] != ref["idx"]) | (g["cnt"] != ref["cnt"]))[0]
+        if g.dtype.names:
+            bad = np.nonzero(np.any([g[f] != ref[f] for f in g.dtype.names], axis=0))[0]
         else:
             bad = np.nonzero((g != ref).reshape(len(ref), -1).any(axis=1))[0]
         i = int(bad[0]) if len(bad) else -1

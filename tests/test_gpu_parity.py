@@ -32,7 +32,7 @@ def say(msg):
 def tile_elems(ks, dtype, waves, rows, lookback=True):
     # in the 16-wave look-back kernel one wave of the workgroup holds no data
     data_waves = waves - 1 if (lookback and waves >= 16) else waves
-    return data_waves * 64 * rows * (16 // ks.ks_elem_bytes(dtype))
+    return data_waves * 64 * rows * 16 // ks.ks_elem_bytes(dtype)
 
 
 SMALL_INPUT_BYTES = 8 << 20   # up to here the default look-back shape of 4- and 8-byte elements is SMALL_SHAPE
@@ -45,6 +45,8 @@ MID_SHAPE = (8, 8)            # between SMALL_INPUT_BYTES and 16 MiB (not for th
 def default_shape(ks, dtype, n=None, op="sum"):
     """(waves, rows) the library picks for the look-back kernel of this element type and size."""
     eb = ks.ks_elem_bytes(dtype)
+    if eb not in (4, 8, 16):      # other sizes: the blocked arrangement, rows such that a lane holds whole elements
+        return (16, 9) if 144 % eb == 0 else (16, 8)
     if n is not None and eb >= 16 and n * eb <= (1 << 20):
         return 4, 4
     if n is not None and eb < 16:
@@ -199,7 +201,8 @@ def test_operand_order_is_kept_at_every_level(ks):
 
 
 def test_in_place_and_misaligned_pointers(ks):
-    for dtype, op in [("i32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")]:
+    for dtype, op in [("i32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul"),
+                      ("mat2_u64", "mat2_mul"), ("range_i32_cnt32", "range_count")]:
         tile = tile_elems(ks, dtype, *default_shape(ks, dtype))
         n = 37 * tile + 11
         x = random_input(dtype, op, n, seed=5)
@@ -213,7 +216,7 @@ def test_in_place_and_misaligned_pointers(ks):
         d_in = d_all[1:]
         d_out_all = torch.empty_like(d_all)
         d_out = d_out_all[1:]
-        if ks.ks_elem_bytes(dtype) < 16:
+        if ks.ks_elem_bytes(dtype) % 16:
             assert d_in.data_ptr() % 16 != 0
         for algo in ("lookback", "reduce_then_scan"):
             temp = torch.empty(ks.ks_scan_temp_bytes(dtype=dtype, op=op, n=n - 1, algo=algo), dtype=torch.uint8, device="cuda")
@@ -224,12 +227,17 @@ def test_in_place_and_misaligned_pointers(ks):
 
 
 @pytest.mark.parametrize("dtype,op", [("f32", "sum"), ("i32", "max"), ("u64", "sum"), ("affine_f32", "affine_compose"),
-                                      ("argmax_i32_cnt64", "argmax_count")])
+                                      ("argmax_i32_cnt64", "argmax_count"), ("mat2_u64", "mat2_mul"),
+                                      ("range_i32_cnt32", "range_count")])
 def test_output_pointers_off_the_128_byte_lines(ks, dtype, op):
     # the 16-wave kernels move their tiles to the output's line boundaries (tile 0 is cut short);
     # sizes of a few rounds (12 rows), several rounds and a dozen rounds
     tile9 = tile_elems(ks, dtype, 16, 9)
-    for tiles, offsets in ((290, [(1, 1)]), (700, [(1, 1), (0, 3), (5, 2)]), (3300, [(7, 7), (2, 0)])):
+    if ks.ks_elem_bytes(dtype) in (12, 32):
+        plan = ((290, [(1, 1)]), (700, [(1, 1), (0, 3), (5, 2)]))     # large elements: keep the host side short
+    else:
+        plan = ((290, [(1, 1)]), (700, [(1, 1), (0, 3), (5, 2)]), (3300, [(7, 7), (2, 0)]))
+    for tiles, offsets in plan:
         n = tiles * tile9 + 11
         x = random_input(dtype, op, n + 8, seed=tiles)
         d_all = to_device(x)
@@ -316,13 +324,13 @@ def test_repeated_launches_give_identical_integer_results(ks):
 
 
 @pytest.mark.parametrize("dtype,op", [("f32", "sum"), ("u64", "sum"), ("argmax_i32_cnt64", "argmax_count"),
-                                      ("mat2_u32", "mat2_mul"), ("affine_f32", "affine_compose")])
+                                      ("mat2_u32", "mat2_mul"), ("affine_f32", "affine_compose"), ("mat2_u64", "mat2_mul")])
 def test_tiles_by_ticket(ks, dtype, op):
     # Tile assignment by ticket: every default shape forced onto it, grids of one workgroup per compute
     # unit and grids far larger than what can be resident (4 x 1024 threads per compute unit: most
     # workgroups only start when others have left, draw a ticket past the end and leave too), the small
     # shapes with many workgroups per compute unit, sizes from one tile to a dozen rounds.
-    tile = tile_elems(ks, dtype, 16, 9)
+    tile = tile_elems(ks, dtype, *default_shape(ks, dtype))
     try:
         for waves, wgs in ((0, 0), (0, 4), (4, 0), (8, 6)):
             ks.ks_set_option("waves", waves)
@@ -417,7 +425,8 @@ def test_map_fused_scan(ks, dtype, map_name, op):
 
 
 @pytest.mark.parametrize("dtype,op", [("i32", "sum"), ("f32", "sum"), ("u64", "max"),
-                                      ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul")])
+                                      ("argmax_i32_cnt64", "argmax_count"), ("mat2_u32", "mat2_mul"),
+                                      ("mat2_u64", "mat2_mul"), ("range_i32_cnt32", "range_count")])
 def test_strided_views(ks, dtype, op):
     # one column of a row-major [n, stride] matrix in, another layout out; the rest must stay untouched
     rts = tile_elems(ks, dtype, *RTS_SHAPE, lookback=False)
