@@ -482,7 +482,9 @@ __device__ __forceinline__ void data_wave_loop(
     constexpr size_t TILE = (size_t)(WAVES - 1) * S::WAVE_ELEMS;
     // see pinned(): 4-byte elements measure 1 % faster without it (float32 sum 2^28 6.43 against 6.37 TB/s,
     // int32 sum 6.38 / 6.32), 8-byte ones 0.3-0.8 % slower (uint64 sum 6.42 / 6.43, 2^25 6.11 / 6.16)
-    constexpr bool PIN = sizeof(IO) != 4;
+    // (more than 9 rows of 4-byte elements need it to stay inside the 128 registers: 12 rows with the
+    // next tile parked spill 70 registers without it and none with it)
+    constexpr bool PIN = sizeof(IO) != 4 || ROWS > 9;
     Op op;
     const size_t shift = tile_shift(out, TILE);   // tiles start on 128-byte lines of the output
     const int lane = threadIdx.x & (kWave - 1);

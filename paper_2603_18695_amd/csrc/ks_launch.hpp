@@ -164,6 +164,9 @@ struct Pair {
         // less than one round: smaller tiles keep more compute units busy
         if (s.rows == 9 && sizeof(A) == 4 && variant_fits<T, A, 16, 8, true, kFormSeparate>())
             consider(Shape{16, 8, true, kFormSeparate});
+        // one round: there is no next tile to park, and the kernel without the parking registers is
+        // the leaner one (float32 sum n = 10^7 in 12 rows: 15.5 us against 21.7 us)
+        if (rounds(best.rows) == 1) best.prefetch = false;
         return best;
     }
 
@@ -342,13 +345,14 @@ struct Pair {
                     return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
             }
             return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
-        }
-        const Shape s = lookback_shape(c.n, c.dev->cus);
-        switch (s.waves) {
-            case 4: return lookback_rows_dispatch<4>(c, s);
-            case 8: return lookback_rows_dispatch<8>(c, s);
-            case 16: return lookback_rows_dispatch<16>(c, s);
-            default: return KS_ERR_INVALID_ARG;
+        } else {
+            const Shape s = lookback_shape(c.n, c.dev->cus);
+            switch (s.waves) {
+                case 4: return lookback_rows_dispatch<4>(c, s);
+                case 8: return lookback_rows_dispatch<8>(c, s);
+                case 16: return lookback_rows_dispatch<16>(c, s);
+                default: return KS_ERR_INVALID_ARG;
+            }
         }
     }
 
