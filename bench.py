@@ -51,8 +51,8 @@ def measured_traffic(workload: str, n: int):
 
 # the oracle's names for the workloads' (operator, element type): only the oracle leg uses them
 ORACLE_KIND = {"int32_sum": ("sum", "i32"), "f32_sum": ("sum", "f32"), "u64_exsum": ("sum", "u64"),
-               "affine": ("affine", "f32"), "argmax": ("argmax", None)}
-FLOAT_WORKLOADS = {"f32_sum", "affine"}
+               "affine": ("affine", "f32"), "argmax": ("argmax", None), "f64_sum": ("sum", "f64")}
+FLOAT_WORKLOADS = {"f32_sum", "affine", "f64_sum"}
 PREHEAT_S = 0.1
 
 
@@ -300,7 +300,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64"}[args.workload],
+        "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64",
+                  "f64_sum": "f64"}[args.workload],
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
                                f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb, "stride": args.stride,

@@ -67,7 +67,10 @@ typedef enum {
 typedef enum {
     KS_SUM = 0,            /* L + R (integers wrap); identity 0.  All six scalar types           */
     KS_MIN = 1,            /* min(L, R); identity = largest value (+inf).  Scalar types          */
-    KS_MAX = 2,            /* max(L, R); identity = smallest value (-inf). Scalar types          */
+    KS_MAX = 2,            /* max(L, R); identity = smallest value (-inf). Scalar types.  With NaN
+                              among float inputs the results of min / max from that element on
+                              are unspecified (the comparisons are evaluated in an order that
+                              depends on the tiling); the sign of a zero sum is unspecified too */
     KS_AFFINE_COMPOSE = 3, /* apply L then R: (R.a*L.a, R.a*L.b + R.b); identity (1,0)           */
     KS_ARGMAX_COUNT = 4,   /* larger v wins, equal v: lower idx wins; cnt adds (wraps);
                               identity {INT32_MIN, INT32_MAX, 0}                                 */

@@ -19,6 +19,8 @@ Workloads (they stand in for the paper's unstated Float32/Float64 arrays of
   argmax       inclusive running arg-max with count, 16-byte struct
                {int32 v, int32 idx, int64 cnt}: v uniform in [0, 2**20),
                idx = position, cnt = 1,                                    seed 4
+  f64_sum      inclusive sum,  float64, uniform [0, 1),                   seed 5
+               (the paper's other benchmarked element type, Tables II and IV)
 """
 from __future__ import annotations
 
@@ -49,6 +51,7 @@ WORKLOADS = {
     "u64_exsum": Workload("u64_exsum", "u64", "sum", False, 1 << 27, 2, 8),
     "affine": Workload("affine", "affine_f32", "affine_compose", True, 1 << 26, 3, 8),
     "argmax": Workload("argmax", "argmax_i32_cnt64", "argmax_count", True, 1 << 30, 4, 16),
+    "f64_sum": Workload("f64_sum", "f64", "sum", True, 1 << 27, 5, 8),
 }
 
 ARGMAX_SWEEP = [1 << k for k in range(10, 31, 2)]   # 2^10 .. 2^30 in powers of 4
@@ -59,6 +62,8 @@ def _draw(name: str, rng: np.random.Generator, start: int, m: int) -> np.ndarray
         return rng.integers(-100, 101, size=m, dtype=np.int32)
     if name == "f32_sum":
         return rng.random(size=m, dtype=np.float32)
+    if name == "f64_sum":
+        return rng.random(size=m, dtype=np.float64)
     if name == "u64_exsum":
         return rng.integers(0, 1 << 32, size=m, dtype=np.uint64)
     if name == "affine":

@@ -856,15 +856,15 @@ __global__ __launch_bounds__(kBlock) void tile_scan_kernel(const IO *in, IO *out
 // granules (a tile is 4 waves x ROWS rows x 64 elements).  Four waves, all holding data, no
 // prefetch: a strided access pattern is bound by the sectors it touches, and many small workgroups
 // per compute unit keep more of them in flight than one large one.
-template <class IO, class Op, int ROWS, bool INCLUSIVE>
-__global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO *in, size_t in_stride, IO *out,
+template <class IO, class Op, int WAVES, int ROWS, bool INCLUSIVE>
+__global__ __launch_bounds__(WAVES *kWave) void scan_lookback_strided_kernel(const IO *in, size_t in_stride, IO *out,
                                                                        size_t out_stride, LookbackArgs a) {
     using A = typename Op::acc;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
     constexpr size_t WAVE_ELEMS = (size_t)kWave * ROWS;   // one-element granules
-    constexpr size_t TILE = (size_t)kWaves * WAVE_ELEMS;
-    __shared__ CommonExchange<A, C, kWaves> x;
+    constexpr size_t TILE = (size_t)WAVES * WAVE_ELEMS;
+    __shared__ CommonExchange<A, C, WAVES> x;
     Op op;
     COp cop;
     const int lane = threadIdx.x & (kWave - 1);
@@ -878,7 +878,7 @@ __global__ __launch_bounds__(kBlock) void scan_lookback_strided_kernel(const IO 
         load_items_strided<IO, ROWS, Op>(in, in_stride, a.n, run_first, cur);
         const WaveScan<A, ROWS> ws = scan_wave_run<A, ROWS, 1, Op>(cur, op);
         C aggregate;
-        const C wave_carry = exchange_wave_totals<Op, kWaves>(x.tot, ws.wave_total, aggregate);
+        const C wave_carry = exchange_wave_totals<Op, WAVES>(x.tot, ws.wave_total, aggregate);
         // no prefetch here: the next tile is only needed after the closing barrier; wave 1 draws it
         // now and has it long before wave 0 is back from the look-back
         if (a.tickets && wave == kDrawingWave && lane == 0) x.q.next_tile = draw_ticket(a.control);

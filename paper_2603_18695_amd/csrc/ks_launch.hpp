@@ -388,33 +388,48 @@ struct Pair {
     }
 
     // ---- strided views -------------------------------------------------------
-    // The look-back scan with element-wise accesses and one-element granules, 4 waves x kStridedRows
-    // rows x 64 elements per tile; one tile or many.
-    static constexpr int kStridedRows = sizeof(A) >= 16 ? 8 : 16;
-    static constexpr size_t kStridedTile = (size_t)kWaves * kWave * kStridedRows;
+    // The look-back scan with element-wise accesses and one-element granules, WAVES waves x
+    // kStridedRows rows x 64 elements per tile; one tile or many.  One workgroup per compute unit,
+    // tiles by index.
+    static constexpr int kStridedRows = sizeof(A) >= 32 ? 4 : sizeof(A) >= 16 ? 8 : 16;
+    static size_t strided_tile(int waves) { return (size_t)waves * kWave * kStridedRows; }
     // temp_bytes(KS_ALGO_LOOKBACK, n) sizes the descriptors for the smallest contiguous tile
-    static_assert(kStridedTile * sizeof(T) >= (size_t)kMinTileGranules * 16, "strided tile below the smallest tile");
-    template <bool INCLUSIVE>
+    static_assert((size_t)4 * kWave * kStridedRows * sizeof(T) >= (size_t)kMinTileGranules * 16,
+                  "strided tile below the smallest tile");
+    template <int WAVES, bool INCLUSIVE>
     static int launch_lookback_strided(const ScanCall &c) {
-        auto kernel = scan_lookback_strided_kernel<T, Op, kStridedRows, INCLUSIVE>;
-        const size_t tiles = ceil_div(c.n, kStridedTile);
+        auto kernel = scan_lookback_strided_kernel<T, Op, WAVES, kStridedRows, INCLUSIVE>;
+        constexpr int kThreads = WAVES * kWave;
+        const size_t tiles = ceil_div(c.n, strided_tile(WAVES));
         if (tiles >= 0xfffffff0ull) return KS_ERR_INVALID_ARG;
         if (lookback_scratch_bytes(tiles) > c.temp_bytes) return KS_ERR_WORKSPACE;
-        static std::map<int, int> reported_per_cu;
-        int per_cu = 0;
-        const int os = occupancy(c, reported_per_cu, kernel, kBlock, per_cu);
-        if (os != KS_OK) return os;
         uint32_t tickets = 0;
-        const size_t grid = persistent_grid(c, per_cu, tiles, tickets);
+        const size_t grid = persistent_grid(c, 1, tiles, tickets);
         LastLaunch &l = last_launch();
-        l.waves = kWaves;
+        l.waves = WAVES;
         l.rows = kStridedRows;
         l.form = kFormCommon;
         const LookbackArgs a = lookback_args(c, tiles, tickets);
-        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream, static_cast<const T *>(c.in),
                            c.in_stride, static_cast<T *>(c.out), c.out_stride, a);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? KS_OK : set_hip_error(e);
+    }
+    // Workgroup size by the distance between neighbouring elements: the closer they are, the more
+    // of each cache line a wave uses and the more waves a compute unit can feed.  Measured, n = 2^24,
+    // us per call with 4 / 8 / 16 waves: float32 stride 2 (8 bytes apart) 99 / 73 / 68, stride 4 160 / 151 /
+    // 163, stride 8 287 / 290 / 332, stride 32 1109 / 1121 / 1169; float64 stride 2 (16 bytes) 161 / 152 / 204,
+    // stride 4 294 / 295 / 404, stride 8 593 / 637 / 763.
+    static int run_strided(const ScanCall &c) {
+        const size_t apart = (c.in_stride > c.out_stride ? c.in_stride : c.out_stride) * sizeof(T);
+        int waves = apart <= 8 ? 16 : apart <= 16 ? 8 : 4;
+        const long long want = options().waves;
+        if (want == 4 || want == 8 || want == 16) waves = (int)want;
+        switch (waves) {
+            case 4: return c.inclusive ? launch_lookback_strided<4, true>(c) : launch_lookback_strided<4, false>(c);
+            case 8: return c.inclusive ? launch_lookback_strided<8, true>(c) : launch_lookback_strided<8, false>(c);
+            default: return c.inclusive ? launch_lookback_strided<16, true>(c) : launch_lookback_strided<16, false>(c);
+        }
     }
 
     // ---- mapreduce ---------------------------------------------------------------
@@ -484,7 +499,7 @@ struct Pair {
 
     static int run(const ScanCall &c) {
         if (c.in_stride != 1 || c.out_stride != 1)
-            return c.inclusive ? launch_lookback_strided<true>(c) : launch_lookback_strided<false>(c);
+            return run_strided(c);
         if (c.algo == KS_ALGO_LOOKBACK) return run_lookback(c);
         return run_rts(c.inclusive != 0, static_cast<const T *>(c.in), static_cast<T *>(c.out), c.n,
                        static_cast<char *>(c.temp), c.temp_bytes, c.stream);
