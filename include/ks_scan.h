@@ -70,7 +70,8 @@ typedef enum {
     KS_MAX = 2,            /* max(L, R); identity = smallest value (-inf). Scalar types.  With NaN
                               among float inputs the results of min / max from that element on
                               are unspecified (the comparisons are evaluated in an order that
-                              depends on the tiling); the sign of a zero sum is unspecified too */
+                              depends on the tiling); the sign of a zero result (a sum that comes
+                              out as zero, a minimum or maximum over +0 and -0) is unspecified too */
     KS_AFFINE_COMPOSE = 3, /* apply L then R: (R.a*L.a, R.a*L.b + R.b); identity (1,0)           */
     KS_ARGMAX_COUNT = 4,   /* larger v wins, equal v: lower idx wins; cnt adds (wraps);
                               identity {INT32_MIN, INT32_MAX, 0}                                 */

@@ -134,6 +134,37 @@ struct MaxOp {
     __device__ __forceinline__ T operator()(T l, T r) const { return r > l ? r : l; }
 };
 
+// floating point minimum and maximum: the hardware's own instructions (one instead of a compare and
+// a select); with NaN among the inputs the results from there on are unspecified
+template <>
+struct MinOp<float> {
+    static constexpr bool commutative = true;
+    using acc = float;
+    __device__ static float identity() { return Limits<float>::hi(); }
+    __device__ __forceinline__ float operator()(float l, float r) const { return __builtin_fminf(l, r); }
+};
+template <>
+struct MaxOp<float> {
+    static constexpr bool commutative = true;
+    using acc = float;
+    __device__ static float identity() { return Limits<float>::lo(); }
+    __device__ __forceinline__ float operator()(float l, float r) const { return __builtin_fmaxf(l, r); }
+};
+template <>
+struct MinOp<double> {
+    static constexpr bool commutative = true;
+    using acc = double;
+    __device__ static double identity() { return Limits<double>::hi(); }
+    __device__ __forceinline__ double operator()(double l, double r) const { return __builtin_fmin(l, r); }
+};
+template <>
+struct MaxOp<double> {
+    static constexpr bool commutative = true;
+    using acc = double;
+    __device__ static double identity() { return Limits<double>::lo(); }
+    __device__ __forceinline__ double operator()(double l, double r) const { return __builtin_fmax(l, r); }
+};
+
 // Apply l first, then r.  Carried in double: the offset b of a long composition
 // is a cancelling sum that reaches 1e2..1e3 in magnitude and crosses zero, and
 // every later composition multiplies it by a: an a carried in float32 (relative
