@@ -3,7 +3,7 @@
 
 A step is one pass of the whole hot path (one ks_scan call: load, register scan, wave scan, LDS
 exchange, look-back, store) over one batch of synthetic input that is already resident in HBM.
-Default workload: BASELINE's headline configuration, inclusive float32 sum scan of n = 2^28
+Default workload: the headline configuration, inclusive float32 sum scan of n = 2^28
 values uniform in [0, 1) from seed 1.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 

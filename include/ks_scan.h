@@ -213,7 +213,8 @@ int ks_scan_static(ks_dtype dtype, ks_op op, int inclusive, const void *in, void
  * the current device) since the last check gave up waiting for a predecessor
  * tile (KS_ERR_TIMEOUT; that call's output is invalid), or a HIP error surfaced
  * (KS_ERR_HIP).  The stream's flag is cleared; scans on other streams have flags
- * of their own and are neither blamed nor disturbed.  Waits are bounded
+ * of their own and are neither blamed nor disturbed (a device has 1024 flags,
+ * handed out in order of a stream's first scan; beyond that streams share).  Waits are bounded
  * ("spin_limit") so that a scan can never hang the device: a workgroup waits
  * for tiles of workgroups that may not have started yet when other work holds
  * the compute units, and gives up if that lasts longer than the limit allows

@@ -54,6 +54,31 @@ def test_enums_and_sizes(ks):
     assert ks.ks_pair_supported("mat2_u32", "mat2_mul") and ks.ks_pair_supported("quat_f32", "quat_mul")
     assert not ks.ks_pair_supported("f32", "affine_compose")
     assert not ks.ks_pair_supported("affine_f32", "sum")
+    # element sizes other than 4, 8 and 16 bytes
+    assert ks.ks_elem_bytes("mat2_u64") == 32 and ks.ks_elem_bytes("range_i32_cnt32") == 12
+    assert ks.ks_pair_supported("mat2_u64", "mat2_mul") and ks.ks_pair_supported("range_i32_cnt32", "range_count")
+    assert not ks.ks_pair_supported("mat2_u64", "sum")
+    for dt in ("mat2_u64", "range_i32_cnt32"):
+        op = "mat2_mul" if dt == "mat2_u64" else "range_count"
+        for n in (1, 1000, 10**6, 10**9):
+            assert ks.ks_scan_temp_bytes(dtype=dt, op=op, n=n, algo="lookback") % 256 == 0
+            assert ks.ks_scan_temp_bytes(dtype=dt, op=op, n=n, algo="reduce_then_scan") >= 256
+
+
+def test_mapreduce_and_static_argument_checks_need_no_gpu(ks):
+    lib = ks.raw_library()
+    lib.ks_mapreduce.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.ks_mapreduce(99, 0, 0, None, 0, 16, None) == ks.KS_ERR_INVALID_ARG          # bad dtype
+    assert lib.ks_mapreduce(0, 9, 0, None, 0, 16, None) == ks.KS_ERR_INVALID_ARG           # bad map
+    assert lib.ks_mapreduce(4, 1, 1, None, 0, 16, None) == ks.KS_ERR_UNSUPPORTED           # (f32, square, min) is no triple
+    assert lib.ks_mapreduce(4, 0, 0, None, 0, None, None) == ks.KS_ERR_INVALID_ARG         # no output
+    assert lib.ks_mapreduce(4, 0, 0, None, 5, 16, None) == ks.KS_ERR_INVALID_ARG           # n > 0 without input
+    assert lib.ks_mapreduce(4, 0, 0, 18, 5, 16, None) == ks.KS_ERR_MISALIGNED
+    lib.ks_scan_static.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.ks_scan_static(4, 0, 1, None, None, 0, None) == ks.KS_OK                    # n == 0: nothing to do
+    assert lib.ks_scan_static(4, 0, 1, None, 16, 4, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan_static(4, 3, 1, 16, 32, 4, None) == ks.KS_ERR_UNSUPPORTED           # (f32, affine_compose)
+    assert lib.ks_scan_static(7, 4, 1, 1 << 40, 1 << 41, 1 << 27, None) == ks.KS_ERR_WORKSPACE   # beyond the static scratch
 
 
 def test_map_triples(ks):
