@@ -4,8 +4,9 @@
 //   tile_reduce_kernel     reduce-then-scan, first kernel: one aggregate per tile
 //   tile_scan_kernel       reduce-then-scan, last kernel: scan a tile from a seed
 //   scan_lookback_strided_kernel  the look-back scan over strided views (paper Sec. IV-C)
-//   fill_zero_kernel       clears caller-provided descriptors
+//   fill_zero_kernel       clears scratch whose contents are unknown
 //   copy_kernel            vectorised copy, the bandwidth ceiling (paper Sec. IV-C)
+// (mapreduce_kernel, the single-launch reduction of Sec. V-A, is in ks_reduce.hpp.)
 //
 // Tile descriptors (paper Sec. V-B: per-tile aggregate, inclusive prefix and a
 // partial / prefix status flag; Sec. IV-B for the hazard the flag guards).  The
