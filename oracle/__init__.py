@@ -179,8 +179,21 @@ def apply_map(name: str, x: np.ndarray) -> np.ndarray:
     identity: x;  square: x * x (integers wrap in their own width; float32 inputs are squared in
     float64, where the product of two float32 values is exact);  abs: |x| (the most negative integer
     maps to itself);  nonzero: 1 where x != 0 else 0, in x's type.
+
+    Two maps change the type, f: T -> S of the paper's Sec. II-C, and take uint8 codes only:
+    unit_float8: code c stands for level c of 256 evenly spaced levels from -1 to +1 (paper
+    Sec. VII-B, the 8-bit type of the mapreduce benchmark), (2c - 255) / 255, promoted to float32:
+    the float32 nearest to that rational (float64 division, then one rounding to float32; the
+    quotient of two small integers is far from any float32 tie, which the pins check code by code);
+    widen64: the code as a uint64, so that a sum of bytes cannot wrap.
     """
     x = np.asarray(x)
+    if name in ("unit_float8", "widen64"):
+        if x.dtype != np.uint8:
+            raise TypeError(f"map {name!r} takes uint8 codes")
+        if name == "widen64":
+            return x.astype(np.uint64)
+        return ((2.0 * x.astype(np.float64) - 255.0) / 255.0).astype(np.float32)
     if name == "identity":
         return x
     if name == "square":
@@ -238,11 +251,20 @@ def mapreduce(map_name: str, op: str, dt: str | None, x: np.ndarray, chunk: int 
     The fold is the scan's own (the same C routine run to the end of the input, fed in chunks, the
     running value carried in its state); what comes back is the last running value, in the oracle's
     output type: float64 for float32 / float64 sums, affine maps and quaternions, the element type
-    for everything else.  The paper asks for a commutative operator here; the left fold is also
+    (the map's result type, where the map changes it) for everything else.  The paper asks for a commutative operator here; the left fold is also
     defined for the non-commutative ones, and that is what is returned for them.
     """
     x = np.asarray(x)
     n = x.shape[0]
+    if dt == "u8":
+        # bytes: sums only.  unit_float8 -> a float32 sum, widen64 -> a uint64 sum; with no map the
+        # sum stays in the element type, i.e. modulo 2^8 (what UInt8 + UInt8 is), and the exact sum
+        # reduced modulo 2^8 is that value whatever the order of the additions.
+        if op != "sum":
+            raise KeyError((op, dt))
+        if map_name == "identity":
+            return np.uint8(int(mapreduce("widen64", "sum", "u8", x, chunk)) & 0xFF)
+        dt = {"unit_float8": "f32", "widen64": "u64"}[map_name]
     if n == 0:
         return identity_of(op, dt)
     probe = apply_map(map_name, x[:1])

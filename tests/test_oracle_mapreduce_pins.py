@@ -201,3 +201,63 @@ def test_every_order_and_grouping_on_tiny_inputs():
     swapped = mats.copy()
     swapped[[0, 1]] = swapped[[1, 0]]
     assert tuple(oracle.mapreduce("identity", "mat2", "u32", swapped).tolist()) != want
+
+
+# ---- bytes: the 8-bit types of the paper's mapreduce benchmark (Sec. VII-B, Tables I and III) ----
+
+def _nearest_float32(fr: Fraction) -> np.float32:
+    guess = np.float32(float(fr))
+    around = (np.nextafter(guess, np.float32(-4)), guess, np.nextafter(guess, np.float32(4)))
+    return min(around, key=lambda c: abs(Fraction(float(c)) - fr))
+
+
+def test_unit_float8_levels_code_by_code():
+    codes = np.arange(256, dtype=np.uint8)
+    levels = oracle.apply_map("unit_float8", codes)
+    assert levels.dtype == np.float32
+    # 256 evenly spaced levels from -1 to +1: the end points, the order and the spacing fix the formula
+    assert levels[0] == -1.0 and levels[255] == 1.0
+    assert np.all(np.diff(levels.astype(np.float64)) > 0)
+    assert np.abs(np.diff(levels.astype(np.float64)) - 2.0 / 255.0).max() <= 2.0 ** -24
+    assert np.array_equal(levels, -levels[::-1])          # level(c) = -level(255 - c); no level is zero
+    # promoted to float32 = the float32 NEAREST to the rational level, for every one of the 256 codes
+    for c in range(256):
+        assert levels[c] == _nearest_float32(Fraction(2 * c - 255, 255)), c
+    with pytest.raises(TypeError):
+        oracle.apply_map("unit_float8", np.zeros(4, np.int32))
+
+
+def test_unit_float8_sum_closed_forms_and_exact_sum():
+    codes = np.arange(256, dtype=np.uint8)
+    # every level once: the levels cancel in pairs, and float64 holds every partial sum exactly
+    assert float(oracle.mapreduce("unit_float8", "sum", "u8", codes)) == 0.0
+    assert float(oracle.mapreduce("unit_float8", "sum", "u8", np.tile(codes, 1000))) == 0.0
+    # n copies of one code: n times its float32 level, exact in float64
+    n = 100_001
+    for c in (0, 255, 128, 37):
+        level = float(oracle.apply_map("unit_float8", np.array([c], np.uint8))[0])
+        assert float(oracle.mapreduce("unit_float8", "sum", "u8", np.full(n, c, np.uint8))) == n * level
+    x = np.random.default_rng(21).integers(0, 256, size=300_007, dtype=np.uint8)
+    exact = math.fsum(float(_nearest_float32(Fraction(2 * c - 255, 255))) * k for c, k in enumerate(np.bincount(x, minlength=256)))
+    assert abs(float(oracle.mapreduce("unit_float8", "sum", "u8", x)) - exact) <= 1e-9
+    assert float(oracle.mapreduce("unit_float8", "sum", "u8", x, chunk=999)) == float(oracle.mapreduce("unit_float8", "sum", "u8", x))
+    # the sign of the result is what the paper validates against a float64 reference
+    assert float(oracle.mapreduce("unit_float8", "sum", "u8", np.full(7, 127, np.uint8))) < 0 < \
+        float(oracle.mapreduce("unit_float8", "sum", "u8", np.full(7, 128, np.uint8)))
+    assert float(oracle.mapreduce("unit_float8", "sum", "u8", x[:0])) == 0.0
+
+
+def test_byte_sums_wide_and_in_the_element_type():
+    x = np.random.default_rng(22).integers(0, 256, size=400_003, dtype=np.uint8)
+    exact = sum(int(v) for v in x)
+    assert int(oracle.mapreduce("widen64", "sum", "u8", x)) == exact == int(x.sum(dtype=np.uint64))
+    assert oracle.mapreduce("widen64", "sum", "u8", x).dtype == np.uint64
+    full = np.full(1 << 25, 255, np.uint8)                 # 255 * 2^25 > 2^32: a 32-bit sum would have wrapped
+    assert int(oracle.mapreduce("widen64", "sum", "u8", full)) == 255 << 25
+    # no map: UInt8 + UInt8 stays UInt8, so the sum is the exact sum modulo 2^8; numpy's own uint8 reduction agrees
+    got = oracle.mapreduce("identity", "sum", "u8", x)
+    assert got.dtype == np.uint8 and int(got) == exact % 256 == int(np.add.reduce(x, dtype=np.uint8))
+    assert int(oracle.mapreduce("identity", "sum", "u8", x, chunk=1234)) == exact % 256
+    assert int(oracle.mapreduce("identity", "sum", "u8", x[:0])) == 0 and int(oracle.mapreduce("widen64", "sum", "u8", x[:0])) == 0
+    with pytest.raises(KeyError):
+        oracle.mapreduce("identity", "max", "u8", x)
