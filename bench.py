@@ -7,12 +7,14 @@ Default workload: the headline configuration, inclusive float32 sum scan of n = 
 values uniform in [0, 1) from seed 1.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--stride S] [--mapreduce] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--n N] [--stride S]
+                    [--mapreduce [--map MAP]] [--no-cpu]
 
 With --stride S > 1 (scalar workloads) the same elements sit S elements apart in both buffers and
 ks_scan_strided runs; GB/s still counts the elements alone (2 * n * element size).
-With --mapreduce the step is one ks_mapreduce call (the workload's operator, identity map) on the same
-input, and GB/s counts n * element size: every element read once, one element written.
+With --mapreduce the step is one ks_mapreduce call (the workload's operator, the map of --map) on the same
+input, and GB/s counts n * element size: every element read once, one element written.  The workload
+u8_codes (uint8 codes; maps unit_float8, widen64 or identity) exists for --mapreduce only.
 """
 from __future__ import annotations
 
@@ -51,7 +53,7 @@ def measured_traffic(workload: str, n: int):
 
 # the oracle's names for the workloads' (operator, element type): only the oracle leg uses them
 ORACLE_KIND = {"int32_sum": ("sum", "i32"), "f32_sum": ("sum", "f32"), "u64_exsum": ("sum", "u64"),
-               "affine": ("affine", "f32"), "argmax": ("argmax", None), "f64_sum": ("sum", "f64")}
+               "affine": ("affine", "f32"), "argmax": ("argmax", None), "f64_sum": ("sum", "f64"), "u8_codes": ("sum", "u64")}
 FLOAT_WORKLOADS = {"f32_sum", "affine", "f64_sum"}
 PREHEAT_S = 0.1
 
@@ -84,6 +86,8 @@ def main() -> int:
     ap.add_argument("--algo", default="auto", choices=["auto", "lookback", "reduce_then_scan"])
     ap.add_argument("--stride", type=int, default=1, help="element stride of both views (ks_scan_strided)")
     ap.add_argument("--mapreduce", action="store_true", help="time ks_mapreduce (reads n elements) instead of the scan")
+    ap.add_argument("--map", default="identity", help="with --mapreduce: the map f of mapreduce(f, op, src), e.g. "
+                    "unit_float8 or widen64 for --workload u8_codes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (cpu_baseline = null)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
     args = ap.parse_args()
@@ -113,6 +117,12 @@ def main() -> int:
     if args.mapreduce and (args.stride > 1 or args.algo != "auto"):
         log("bench.py: --mapreduce goes with --stride 1 and --algo auto")
         return 2
+    if not args.mapreduce and (args.map != "identity" or w.dtype == "u8"):
+        log("bench.py: --map and the byte workload go with --mapreduce (the scans take neither)")
+        return 2
+    if args.mapreduce and not ks.ks_mapreduce_result_bytes(dtype=w.dtype, op=w.op, map=args.map):
+        log(f"bench.py: ks_mapreduce does not take ({w.dtype}, {args.map}, {w.op})")
+        return 2
 
     # ---- inputs: generated on the host from the seeded recipe, then resident in HBM
     t0 = time.time()
@@ -132,10 +142,13 @@ def main() -> int:
         s_out = torch.zeros_like(s_in)
 
     d_one = torch.empty_like(d_in[:1])
+    if args.mapreduce:    # one element of the result type, which a map may have changed
+        d_one = torch.empty(ks.ks_mapreduce_result_bytes(dtype=w.dtype, op=w.op, map=args.map), dtype=torch.uint8,
+                            device="cuda")
 
     def step():
         if args.mapreduce:
-            ks.ks_mapreduce(d_in, d_one, dtype=w.dtype, op=w.op)
+            ks.ks_mapreduce(d_in, d_one, dtype=w.dtype, op=w.op, map=args.map)
         elif args.stride > 1:
             ks.ks_scan_strided(s_in, s_out, dtype=w.dtype, op=w.op, n=n, in_stride=args.stride,
                                out_stride=args.stride, inclusive=w.inclusive)
@@ -221,13 +234,19 @@ def main() -> int:
         if args.stride > 1:
             d_out = s_out[::args.stride].contiguous()
         oop, odt = ORACLE_KIND[args.workload]
-        budget_elems = min(n, 1 << 28)
+        if args.mapreduce:    # the fold runs over the mapped elements, in the type the map gives them
+            odt = {"unit_float8": "f32", "widen64": "u64"}.get(args.map, "u64" if w.dtype == "u8" else odt)
+            if args.map == "square" and odt == "f32":
+                odt = "f64"
+        budget_elems = n if w.dtype == "u8" else min(n, 1 << 28)
         stream = oracle.ScanStream(oop, odt, True if args.mapreduce else w.inclusive)
         cpu_s, done, at, worst = 0.0, 0, 0, 0.0
         for c in host_chunks:
             if done >= budget_elems:
                 break
             t = time.perf_counter()
+            if args.mapreduce and (args.map != "identity" or w.dtype == "u8"):
+                c = oracle.apply_map("widen64" if (w.dtype, args.map) == ("u8", "identity") else args.map, c)
             ref = stream.feed(c)
             cpu_s += time.perf_counter() - t
             if not args.mapreduce:
@@ -236,7 +255,16 @@ def main() -> int:
             at += len(c)
             done += len(c)
         if args.mapreduce and done == n:     # the fold's last running value is the reduction
-            worst = worst_ratio_or_raise(args.workload, to_host(d_one, host_chunks[0].dtype), ref[-1:], "bench parity, mapreduce")
+            last = ref[-1:]
+            if (w.dtype, args.map) == ("u8", "identity"):
+                last = (last & np.uint64(0xFF)).astype(np.uint8)      # the element type's own addition: modulo 2^8
+            if w.dtype == "u8":
+                got = d_one.cpu().numpy().view(np.float32 if args.map == "unit_float8" else last.dtype)
+                kind = "f32_sum" if args.map == "unit_float8" else "int32_sum"    # float bar, or bit for bit
+            else:
+                got = to_host(d_one.view(d_in.dtype).reshape((1,) + tuple(d_in.shape[1:])), host_chunks[0].dtype)
+                kind = args.workload
+            worst = worst_ratio_or_raise(kind, got, last, "bench parity, mapreduce")
         parity = {"checked_elements": done, "worst_float_ratio": worst}
         cpu_gbs = (1 if args.mapreduce else 2) * done * eb / cpu_s / 1e9
         cpu = {"value": cpu_gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
@@ -285,7 +313,8 @@ def main() -> int:
         others["argmax_sweep"] = [time_config("argmax", on) for on in ks_inputs.ARGMAX_SWEEP if on != 1 << 26]
 
     result = {
-        "metric": f"mapreduce GB/s (read), workload {args.workload} n={n}, 1 MI355X" if args.mapreduce
+        "metric": f"mapreduce GB/s (read), workload {args.workload}{'' if args.map == 'identity' else ' map ' + args.map} n={n}, "
+                  "1 MI355X" if args.mapreduce
                   else "scan GB/s (read+write), float32 inclusive sum n=2^28, 1 MI355X"
                   if args.workload == "f32_sum" and n == 1 << 28 and args.stride == 1
                   else f"scan GB/s (read+write), workload {args.workload} n={n}"
@@ -301,7 +330,7 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64",
-                  "f64_sum": "f64"}[args.workload],
+                  "f64_sum": "f64", "u8_codes": {"unit_float8": "f32", "widen64": "u64"}.get(args.map, "u8")}[args.workload],
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
                                f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb, "stride": args.stride,

@@ -60,7 +60,8 @@ typedef enum {
     KS_QUAT_F32 = 9,         /* struct { float w, x, y, z; }                        16 B */
     KS_MAT2_U64 = 10,        /* struct { uint64_t m00, m01, m10, m11; } row-major   32 B */
     KS_RANGE_I32_CNT32 = 11, /* struct { int32_t lo, hi; uint32_t cnt; }            12 B */
-    KS_DTYPE_COUNT = 12
+    KS_U8 = 12,              /* uint8_t; ks_mapreduce only (the scans refuse it)     1 B */
+    KS_DTYPE_COUNT = 13
 } ks_dtype;
 
 /* Operators; L is the accumulated (earlier) operand, R the later one. */
@@ -93,15 +94,22 @@ typedef enum {
 } ks_algo;
 
 /*
- * Element-wise maps T -> T for the map-fused scan (paper Sec. IV-A: the
- * high-level interface scan(f, op, src)).  The map is applied as elements are
- * loaded; the output has the input's element type.
+ * Element-wise maps for the map-fused scan and mapreduce (paper Sec. IV-A: the
+ * high-level interface scan(f, op, src), mapreduce(f, op, src)).  The map is
+ * applied as elements are loaded.  The first four are T -> T: the output has the
+ * input's element type.  The last two take KS_U8 and change the type (f: T -> S of
+ * Sec. II-C); only ks_mapreduce accepts them, and its result is an S.
  */
 typedef enum {
     KS_MAP_IDENTITY = 0,
-    KS_MAP_SQUARE = 1,  /* x * x (integers wrap)                                            */
-    KS_MAP_ABS = 2,     /* |x| (the most negative integer maps to itself)                   */
-    KS_MAP_NONZERO = 3  /* x != 0 ? 1 : 0, e.g. sum scan = positions of a stream compaction */
+    KS_MAP_SQUARE = 1,      /* x * x (integers wrap)                                            */
+    KS_MAP_ABS = 2,         /* |x| (the most negative integer maps to itself)                   */
+    KS_MAP_NONZERO = 3,     /* x != 0 ? 1 : 0, e.g. sum scan = positions of a stream compaction */
+    KS_MAP_UNIT_FLOAT8 = 4, /* uint8_t code c -> float: level c of 256 evenly spaced levels from
+                               -1 to +1 (the 8-bit type of the paper's mapreduce benchmark,
+                               Sec. VII-B), the float nearest to (2c - 255) / 255           */
+    KS_MAP_WIDEN64 = 5,     /* uint8_t -> uint64_t, so that a sum of bytes cannot wrap          */
+    KS_MAP_COUNT = 6
 } ks_map;
 
 /*
@@ -153,10 +161,17 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
  * that do not commute give the ordered result too (the paper requires a
  * commutative operator).  n == 0 writes the operator's identity.
  *   in    device pointer, n contiguous elements of dtype (may be NULL if n == 0)
- *   out   device pointer to ONE element of dtype, written by the call; it may lie
- *         inside `in`
+ *   out   device pointer to ONE element of the result type, aligned to it, written
+ *         by the call; it may lie inside `in`.  The result type is dtype, except
+ *         where the map changes it: float for KS_MAP_UNIT_FLOAT8, uint64_t for
+ *         KS_MAP_WIDEN64 (ks_mapreduce_result_bytes gives its size)
  *   map   KS_MAP_IDENTITY or one of the maps; accepted (dtype, map, op) triples are
- *         those of ks_map_supported, others return KS_ERR_UNSUPPORTED
+ *         those for which ks_mapreduce_result_bytes is not 0: the triples of
+ *         ks_map_supported, all of them for element sizes 4, 8 and 16 bytes, and
+ *         the three sums over bytes (paper Sec. VII-B, Tables I and III):
+ *         (KS_U8, KS_MAP_UNIT_FLOAT8, KS_SUM), (KS_U8, KS_MAP_WIDEN64, KS_SUM) and
+ *         (KS_U8, KS_MAP_IDENTITY, KS_SUM), the last one modulo 2^8 as the element
+ *         type's own addition is.  Others return KS_ERR_UNSUPPORTED.
  * Float32 sums are accumulated in double and rounded once at the end.  Scratch,
  * stream behaviour (asynchronous; recordable into a graph under ks_scan's
  * conditions) and errors as for ks_scan; a finishing wave that does not see all
@@ -166,8 +181,11 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
 int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n, void *out,
                  void *stream);
 
-/* 1 if ks_scan_map and ks_mapreduce accept this (dtype, map, op), else 0. */
+/* 1 if ks_scan_map accepts this (dtype, map, op), else 0. */
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op);
+
+/* sizeof what ks_mapreduce writes for this (dtype, map, op); 0 if it does not accept the triple. */
+size_t ks_mapreduce_result_bytes(ks_dtype dtype, ks_map map, ks_op op);
 
 /*
  * Bytes of device scratch ks_scan_with_temp needs for this problem (the paper's

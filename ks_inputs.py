@@ -52,6 +52,8 @@ WORKLOADS = {
     "affine": Workload("affine", "affine_f32", "affine_compose", True, 1 << 26, 3, 8),
     "argmax": Workload("argmax", "argmax_i32_cnt64", "argmax_count", True, 1 << 30, 4, 16),
     "f64_sum": Workload("f64_sum", "f64", "sum", True, 1 << 27, 5, 8),
+    # uint8 codes, uniform over 0 .. 255: the 8-bit types of the paper's mapreduce benchmark (reductions only)
+    "u8_codes": Workload("u8_codes", "u8", "sum", True, 10 ** 9, 6, 1),
 }
 
 ARGMAX_SWEEP = [1 << k for k in range(10, 31, 2)]   # 2^10 .. 2^30 in powers of 4
@@ -66,6 +68,8 @@ def _draw(name: str, rng: np.random.Generator, start: int, m: int) -> np.ndarray
         return rng.random(size=m, dtype=np.float64)
     if name == "u64_exsum":
         return rng.integers(0, 1 << 32, size=m, dtype=np.uint64)
+    if name == "u8_codes":
+        return rng.integers(0, 256, size=m, dtype=np.uint8)
     if name == "affine":
         out = np.empty((m, 2), dtype=np.float32)
         out[:, 0] = rng.uniform(0.99, 1.01, size=m).astype(np.float32)
@@ -122,6 +126,22 @@ def random_ranges(n: int, seed: int) -> np.ndarray:
     out = np.empty(n, dtype=RANGE_DTYPE)
     out["lo"], out["hi"] = x, x
     out["cnt"] = rng.integers(0, 1 << 32, size=n, dtype=np.uint32)
+    return out
+
+
+def random_codes(n: int, seed: int, skew: float = 0.0) -> np.ndarray:
+    """n uint8 codes, drawn in fixed chunks so that any prefix of a longer draw is the shorter draw.
+    skew = 0: uniform over 0 .. 255 (as UnitFloat8 levels: mixed signs, the sum a random walk
+    around zero); skew > 0: that share of the codes is moved into the upper half (a sum that grows)."""
+    out = np.empty(n, np.uint8)
+    for i, at in enumerate(range(0, n, CHUNK)):
+        rng = np.random.default_rng([seed, 77, i])
+        m = min(CHUNK, n - at)
+        c = rng.integers(0, 256, size=CHUNK, dtype=np.uint8)[:m]
+        if skew > 0.0:
+            up = rng.random(CHUNK)[:m] < skew
+            c = np.where(up, c | np.uint8(0x80), c)
+        out[at:at + m] = c
     return out
 
 

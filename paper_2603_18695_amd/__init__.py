@@ -28,13 +28,13 @@ KS_ERR_INVALID_ARG, KS_ERR_UNSUPPORTED, KS_ERR_MISALIGNED, KS_ERR_OVERLAP = -1, 
 KS_ERR_WORKSPACE, KS_ERR_HIP, KS_ERR_TIMEOUT = -5, -6, -7
 
 DTYPES = {"i32": 0, "u32": 1, "i64": 2, "u64": 3, "f32": 4, "f64": 5, "affine_f32": 6,
-          "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9, "mat2_u64": 10, "range_i32_cnt32": 11}
+          "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9, "mat2_u64": 10, "range_i32_cnt32": 11, "u8": 12}
 OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "mat2_mul": 5, "quat_mul": 6,
        "range_count": 7}
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
-MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3}
+MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5}
 
-EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -46,6 +46,8 @@ _lib.ks_scan_static.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_static.restype = _i
 _lib.ks_mapreduce.argtypes = [_i, _i, _i, _vp, _sz, _vp, _vp]
 _lib.ks_mapreduce.restype = _i
+_lib.ks_mapreduce_result_bytes.argtypes = [_i, _i, _i]
+_lib.ks_mapreduce_result_bytes.restype = _sz
 _lib.ks_scan_map.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_map.restype = _i
 _lib.ks_scan_strided.argtypes = [_i, _i, _i, _vp, _sz, _vp, _sz, _sz, _vp]
@@ -145,15 +147,23 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
 
 def ks_mapreduce(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, map: str = "identity",
                  stream=None) -> torch.Tensor:
-    """out[0] = op(map(inp[0]), ..., map(inp[n-1])), one launch; `out` holds one element of `dtype`.
-    Asynchronous on the stream."""
+    """out[0] = op(map(inp[0]), ..., map(inp[n-1])), one launch; `out` holds one element of the result
+    type (`dtype`, or what the map turns it into: see ks_mapreduce_result_bytes).  Asynchronous on the stream."""
     n = _elements(inp, dtype)
-    if _elements(out, dtype) != 1:
-        raise ValueError("out must hold exactly one element")
+    if not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must be a contiguous device tensor")
+    want = ks_mapreduce_result_bytes(dtype=dtype, map=map, op=op)
+    if want and _nbytes(out) != want:    # a triple the library does not take is for the library to refuse
+        raise ValueError("out must hold exactly one element of the result type")
     with _OnDeviceOf(inp):
         _check(_lib.ks_mapreduce(DTYPES[dtype], MAPS[map], OPS[op], inp.data_ptr() if n else None, n, out.data_ptr(),
                                  _stream_ptr(stream)), "ks_mapreduce")
     return out
+
+
+def ks_mapreduce_result_bytes(*, dtype: str, op: str, map: str = "identity") -> int:
+    """Size of what ks_mapreduce writes for this triple; 0 if it does not accept it."""
+    return int(_lib.ks_mapreduce_result_bytes(DTYPES[dtype], MAPS[map], OPS[op]))
 
 
 STATIC_SCRATCH_BYTES = 8 << 20

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libks_scan.so")
 SOURCES = ["ks_scan.hip", "ks_pairs_i32.hip", "ks_pairs_i64.hip", "ks_pairs_float.hip", "ks_pairs_struct.hip",
-           "ks_pairs_mapped.hip"]
+           "ks_pairs_mapped.hip", "ks_pairs_bytes.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

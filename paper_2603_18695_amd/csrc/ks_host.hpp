@@ -65,6 +65,8 @@ struct PairEntry {
     ks_algo (*pick_algo)(size_t n);
     int (*run)(const ScanCall &call);   // returns ks_status; HIP failures via set_hip_error
     int (*mapreduce)(const ScanCall &call);   // call.out = one element; call.temp = control block + partials
+    size_t result_bytes, result_align;        // of what mapreduce writes (the map's result type)
+    // temp_bytes, pick_algo and run are null for pairs that are only reduced (byte elements)
 };
 
 int set_hip_error(hipError_t e);   // records e, returns KS_ERR_HIP

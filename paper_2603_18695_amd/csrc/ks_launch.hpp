@@ -108,6 +108,104 @@ struct PairDefaults {
     }
 };
 
+// Workgroups per compute unit the runtime reports for a kernel variant, per device.  It can be
+// higher than what the hardware grants; with tickets that only means some workgroups start late.
+template <class Kernel>
+inline int reported_occupancy(const ScanCall &c, std::map<int, int> &cache, Kernel kernel, int threads, int &per_cu) {
+    int &known = cache[c.dev->device];
+    if (known == 0) {
+        int nb = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, threads, 0);
+        if (e != hipSuccess) return set_hip_error(e);
+        known = nb > 0 ? nb : 1;
+    }
+    per_cu = known;
+    return KS_OK;
+}
+
+// ---- mapreduce: the launch -----------------------------------------------------------
+// Every pair whose elements fill a 16-byte granule evenly (1, 2, 4, 8, 16 bytes) can be reduced;
+// pairs that are also scanned reach this through Pair, the byte types through ReducePair.
+template <class T, class Op>
+struct ReduceLaunch {
+    using C = typename ChainOf<Op>::type;
+    using R = typename ResultOf<Op, T>::type;
+    // c.out points to ONE element; c.temp holds the control block and the workgroups' partials.
+    // Shape, measured on MI355X (GB/s of the bytes read, rows x workgroups per compute unit).  Commutative
+    // operators (strided runs): float32 sum 2^28 4 x 2 7186, 2 x 4 6970, 4 x 4 6876, 8 x 2 6871, 4 x 8 6459;
+    // arg-max struct 2^26 4 x 2 7120, 4 x 4 6771, 4 x 8 6344: two workgroups per compute unit keep enough
+    // loads in flight, more only add partials to fold at the end.  Ordered operators (contiguous
+    // ranges, one ordered wave reduction per row, bound by instruction issue): 2x2 matrices 8 x 8
+    // 5058, 4 x 8 4930, 8 x 2 4633; affine 8 x 8 5305, 2 x 8 5521, 4 x 2 4860.
+    static constexpr int kReduceRows = Op::commutative ? 4 : 8;
+    // Bytes decoded to float32 (UnitFloat8): five instructions per byte read make that kernel bound by
+    // arithmetic, and a third workgroup per compute unit hides more of it: n = 10^9, us per call with
+    // 1 / 2 / 3 / 4 / 6 workgroups 294 / 181 / 168 / 177 / 161 (10^8: 33 / 24.7 / 24.6 / 27 / 31); the plain
+    // byte sums stay at two: 240 / 145 / 146 / 168 / 152.
+    static constexpr bool kDecodesBytes = sizeof(T) == 1 && std::is_same<typename Op::acc, float>::value;
+    static constexpr int kReduceWgsPerCu = !Op::commutative ? 8 : kDecodesBytes ? 3 : 2;
+    static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * 16 / sizeof(T);   // elements per run
+    static size_t reduce_scratch_bytes(size_t grid) {
+        return kControlBytes + align_up((grid > 0 ? grid : 1) * WordsOf<C>::W * sizeof(uint64_t), 256);
+    }
+    static int run(const ScanCall &c) {
+        auto kernel = mapreduce_kernel<T, Op, kReduceRows>;
+        static std::map<int, int> reported_per_cu;
+        int per_cu = 0;
+        const int os = reported_occupancy(c, reported_per_cu, kernel, kBlock, per_cu);
+        if (os != KS_OK) return os;
+        if (per_cu > kReduceWgsPerCu) per_cu = kReduceWgsPerCu;
+        const long long want = options().wgs_per_cu;
+        if (want > 0) per_cu = (int)(want < 64 ? want : 64);   // any grid is safe here: nobody waits for a workgroup
+        // Elements narrower than a dword: the kernel's 16-byte reads start on a dword boundary, so the
+        // input is taken from the boundary at or below `in` (the same dword, hence the same
+        // allocation) and the kernel drops the bytes in front of the first element.
+        const T *in = static_cast<const T *>(c.in);
+        size_t n = c.n;
+        uint32_t head_skip = 0;
+        if (sizeof(T) < 4 && n > 0) {
+            head_skip = (uint32_t)(reinterpret_cast<uintptr_t>(in) & 3u);
+            in = reinterpret_cast<const T *>(reinterpret_cast<uintptr_t>(in) - head_skip);
+            n += head_skip / sizeof(T);
+        }
+        const size_t total_runs = ceil_div(n, kReduceRun);
+        size_t grid = (size_t)per_cu * (size_t)c.dev->cus;
+        if (grid > ceil_div(total_runs, (size_t)kWaves)) grid = ceil_div(total_runs, (size_t)kWaves);
+        if (grid < 1) grid = 1;   // n == 0: one workgroup writes the identity
+        if (reduce_scratch_bytes(grid) > c.temp_bytes) return KS_ERR_WORKSPACE;
+        char *base = static_cast<char *>(c.temp);
+        if (c.clear_descriptors) {
+            const size_t words = reduce_scratch_bytes(grid) / sizeof(uint64_t);
+            hipLaunchKernelGGL((fill_zero_kernel<0>), dim3((unsigned)ceil_div(words, 256)), dim3(256), 0, c.stream,
+                               reinterpret_cast<uint64_t *>(base), words);
+        }
+        ReduceArgs a;
+        a.n = n;
+        a.head_skip = head_skip;
+        a.total_runs = total_runs;
+        a.control = reinterpret_cast<uint32_t *>(base);
+        a.partials = reinterpret_cast<uint64_t *>(base + kControlBytes);
+        a.epoch = c.epoch;
+        long long spin = options().spin_limit;
+        a.spin_limit = (uint32_t)(spin < 0 ? 0 : (spin > 0xffffffffll ? 0xffffffffll : spin));
+        a.abort_flag = c.abort_flag;
+        a.call_seq = c.call_seq;
+        const size_t per_wave = ceil_div(total_runs, grid * kWaves);
+        if (per_wave > 0xffffffffull) return KS_ERR_INVALID_ARG;
+        a.runs_per_wave = (uint32_t)per_wave;
+        LastLaunch &l = last_launch();
+        l.grid = (long long)grid;
+        l.wgs_per_cu = per_cu;
+        l.waves = kWaves;
+        l.rows = kReduceRows;
+        l.form = kFormCommon;
+        l.tickets = 0;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, in, static_cast<R *>(c.out), a);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? KS_OK : set_hip_error(e);
+    }
+};
+
 // T = element type in memory; A = Op::acc = type held in registers; C = the operator's chain type =
 // type of aggregates, seeds and descriptors.
 template <class T, class Op>
@@ -217,21 +315,6 @@ struct Pair {
         return kControlBytes + desc_bytes(tiles) + desc_bytes(ceil_div(tiles, kWindow) * kWindow);
     }
 
-    // Workgroups per compute unit the runtime reports for a kernel variant, per device.  It can be
-    // higher than what the hardware grants; with tickets that only means some workgroups start late.
-    template <class Kernel>
-    static int occupancy(const ScanCall &c, std::map<int, int> &cache, Kernel kernel, int threads, int &per_cu) {
-        int &known = cache[c.dev->device];
-        if (known == 0) {
-            int nb = 0;
-            hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, threads, 0);
-            if (e != hipSuccess) return set_hip_error(e);
-            known = nb > 0 ? nb : 1;
-        }
-        per_cu = known;
-        return KS_OK;
-    }
-
     // grid of a persistent look-back launch, and whether first tiles come from tickets as well
     static size_t persistent_grid(const ScanCall &c, int per_cu, size_t tiles, uint32_t &tickets) {
         const long long want = options().wgs_per_cu;
@@ -289,7 +372,7 @@ struct Pair {
             if (lookback_scratch_bytes(tiles) > c.temp_bytes) return KS_ERR_WORKSPACE;
             static std::map<int, int> reported_per_cu;
             int per_cu = 0;
-            const int os = occupancy(c, reported_per_cu, kernel, kThreads, per_cu);
+            const int os = reported_occupancy(c, reported_per_cu, kernel, kThreads, per_cu);
             if (os != KS_OK) return os;
             uint32_t tickets = 0;
             const size_t grid = persistent_grid(c, per_cu, tiles, tickets);
@@ -433,68 +516,12 @@ struct Pair {
     }
 
     // ---- mapreduce ---------------------------------------------------------------
-    // c.out points to ONE element; c.temp holds the control block and the workgroups' partials.
-    // Shape, measured on MI355X (GB/s of the bytes read, rows x workgroups per compute unit).  Commutative
-    // operators (strided runs): float32 sum 2^28 4 x 2 7186, 2 x 4 6970, 4 x 4 6876, 8 x 2 6871, 4 x 8 6459;
-    // arg-max struct 2^26 4 x 2 7120, 4 x 4 6771, 4 x 8 6344: two workgroups per compute unit keep enough
-    // loads in flight, more only add partials to fold at the end.  Ordered operators (contiguous
-    // ranges, one ordered wave reduction per row, bound by instruction issue): 2x2 matrices 8 x 8
-    // 5058, 4 x 8 4930, 8 x 2 4633; affine 8 x 8 5305, 2 x 8 5521, 4 x 2 4860.
-    static constexpr int kReduceRows = Op::commutative ? 4 : 8;
-    static constexpr int kReduceWgsPerCu = Op::commutative ? 2 : 8;
-    static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * 16 / sizeof(T);   // elements per run
-    static size_t reduce_scratch_bytes(size_t grid) { return kControlBytes + desc_bytes(grid); }
     static int run_mapreduce(const ScanCall &c) {
         if constexpr (!granule_sized<T>()) {
             return KS_ERR_UNSUPPORTED;   // the reduction kernel is written for the striped arrangement
         } else {
-            return run_mapreduce_striped(c);
+            return ReduceLaunch<T, Op>::run(c);
         }
-    }
-    static int run_mapreduce_striped(const ScanCall &c) {
-        auto kernel = mapreduce_kernel<T, Op, kReduceRows>;
-        static std::map<int, int> reported_per_cu;
-        int per_cu = 0;
-        const int os = occupancy(c, reported_per_cu, kernel, kBlock, per_cu);
-        if (os != KS_OK) return os;
-        if (per_cu > kReduceWgsPerCu) per_cu = kReduceWgsPerCu;
-        const long long want = options().wgs_per_cu;
-        if (want > 0) per_cu = (int)(want < 64 ? want : 64);   // any grid is safe here: nobody waits for a workgroup
-        const size_t total_runs = ceil_div(c.n, kReduceRun);
-        size_t grid = (size_t)per_cu * (size_t)c.dev->cus;
-        if (grid > ceil_div(total_runs, (size_t)kWaves)) grid = ceil_div(total_runs, (size_t)kWaves);
-        if (grid < 1) grid = 1;   // n == 0: one workgroup writes the identity
-        if (reduce_scratch_bytes(grid) > c.temp_bytes) return KS_ERR_WORKSPACE;
-        char *base = static_cast<char *>(c.temp);
-        if (c.clear_descriptors) {
-            const size_t words = reduce_scratch_bytes(grid) / sizeof(uint64_t);
-            hipLaunchKernelGGL((fill_zero_kernel<0>), dim3((unsigned)ceil_div(words, 256)), dim3(256), 0, c.stream,
-                               reinterpret_cast<uint64_t *>(base), words);
-        }
-        ReduceArgs a;
-        a.n = c.n;
-        a.total_runs = total_runs;
-        a.control = reinterpret_cast<uint32_t *>(base);
-        a.partials = reinterpret_cast<uint64_t *>(base + kControlBytes);
-        a.epoch = c.epoch;
-        long long spin = options().spin_limit;
-        a.spin_limit = (uint32_t)(spin < 0 ? 0 : (spin > 0xffffffffll ? 0xffffffffll : spin));
-        a.abort_flag = c.abort_flag;
-        a.call_seq = c.call_seq;
-        const size_t per_wave = ceil_div(total_runs, grid * kWaves);
-        if (per_wave > 0xffffffffull) return KS_ERR_INVALID_ARG;
-        a.runs_per_wave = (uint32_t)per_wave;
-        LastLaunch &l = last_launch();
-        l.grid = (long long)grid;
-        l.wgs_per_cu = per_cu;
-        l.waves = kWaves;
-        l.rows = kReduceRows;
-        l.form = kFormCommon;
-        l.tickets = 0;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kBlock), 0, c.stream, static_cast<const T *>(c.in),
-                           static_cast<T *>(c.out), a);
-        hipError_t e = hipGetLastError();
-        return e == hipSuccess ? KS_OK : set_hip_error(e);
     }
 
     static int run(const ScanCall &c) {
@@ -507,7 +534,17 @@ struct Pair {
 
     static const PairEntry *entry() {
         static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
-                                    &Pair::run_mapreduce};
+                                    &Pair::run_mapreduce, sizeof(T), alignof(T)};
+        return &e;
+    }
+};
+
+// A pair that is only reduced: its elements are narrower than the scan kernels' 4 bytes.
+template <class T, class Op>
+struct ReducePair {
+    static const PairEntry *entry() {
+        static const PairEntry e = {sizeof(T), alignof(T), nullptr, nullptr, nullptr, &ReduceLaunch<T, Op>::run,
+                                    sizeof(typename ResultOf<Op, T>::type), alignof(typename ResultOf<Op, T>::type)};
         return &e;
     }
 };

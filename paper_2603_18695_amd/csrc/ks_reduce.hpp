@@ -32,13 +32,17 @@ struct ReduceArgs {
     uint32_t *abort_flag;
     uint32_t call_seq;
     uint32_t runs_per_wave;   // ordered (non-commutative) operators: contiguous runs per wave
+    uint32_t head_skip;       // elements narrower than a dword: `in` was moved down to a dword boundary,
+                              // and this many leading bytes of run 0 are not part of the input
 };
 
 constexpr int kFinishWindows = 4;   // windows of 64 partials a finishing wave has in flight at once
 
 template <class IO, class Op, int ROWS>
-__global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, IO *out, ReduceArgs a) {
+__global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typename ResultOf<Op, IO>::type *out,
+                                                           ReduceArgs a) {
     using A = typename Op::acc;
+    using R = typename ResultOf<Op, IO>::type;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
     using S = TileShape<IO, ROWS>;
@@ -48,7 +52,8 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, IO *out
     Op op;
     COp cop;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    // uniform for the compiler too: the runs' buffer descriptors then stay in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane_bytes = lane * 16;
     const size_t gw = (size_t)blockIdx.x * kWaves + wave;
     // commutative: runs gw, gw + W, gw + 2W, ... (W = waves of the grid); ordered: a contiguous range
@@ -74,6 +79,13 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, IO *out
         }
         ThreadItems<A, ROWS, S::G> it;
         unpack_items<IO, ROWS, Op, false>(raw, lane_bytes, w.valid_bytes, (run + 1) * RUN > a.n, it);
+        if constexpr (sizeof(IO) < 4) {
+            if (run == 0 && a.head_skip != 0) {   // the bytes in front of the caller's first element
+#pragma unroll
+                for (int k = 0; k < S::G; ++k)
+                    if (lane_bytes + k * (int)sizeof(IO) < (int)a.head_skip) it.x[0][k] = Op::identity();
+            }
+        }
         if constexpr (Op::commutative) {
             A mine = it.x[0][0];
 #pragma unroll
@@ -160,7 +172,8 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, IO *out
             C total = from_words<C>(s_tot[0]);
 #pragma unroll
             for (int k = 1; k < kWaves; ++k) total = cop(total, from_words<C>(s_tot[k]));
-            out[0] = convert<IO>(convert<A>(total));
+            if constexpr (ResultOf<Op, IO>::from_map) out[0] = convert<R>(total);   // f: T -> S, the result is an S
+            else out[0] = convert<IO>(convert<A>(total));
         }
         __hip_atomic_store(&a.control[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
     }

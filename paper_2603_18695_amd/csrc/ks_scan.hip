@@ -30,6 +30,7 @@ const PairEntry *pair_entry_i64(int, int);
 const PairEntry *pair_entry_float(int, int);
 const PairEntry *pair_entry_struct(int, int);
 const PairEntry *pair_entry_mapped(int, int, int);
+const PairEntry *pair_entry_bytes(int, int, int);
 
 const PairEntry *pair_entry(int dtype, int op) {
     if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT) return nullptr;
@@ -115,7 +116,7 @@ StreamState &stream_state(const DeviceInfo *dev, hipStream_t stream) {
 int validate(ks_dtype dtype, ks_op op, const void *in, void *out, size_t n, const PairEntry **entry) {
     if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
     const PairEntry *e = pair_entry(dtype, op);
-    if (!e) return KS_ERR_UNSUPPORTED;
+    if (!e || !e->run) return KS_ERR_UNSUPPORTED;
     *entry = e;
     if (n == 0) return KS_OK;
     if (!in || !out) return KS_ERR_INVALID_ARG;
@@ -270,15 +271,30 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
     return scan_with_library_workspace(e, inclusive, in, out, n, stream, in_stride, out_stride);
 }
 
+// the entry whose mapreduce serves (dtype, map, op), or null
+static const PairEntry *reduce_entry(int dtype, int map, int op) {
+    if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT || map < 0 || map >= KS_MAP_COUNT)
+        return nullptr;
+    if (dtype == KS_U8) return pair_entry_bytes(dtype, map, op);
+    return map == KS_MAP_IDENTITY ? pair_entry(dtype, op) : pair_entry_mapped(dtype, map, op);
+}
+
 int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n, void *out, void *stream) {
     if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
-    if ((int)map < KS_MAP_IDENTITY || (int)map > KS_MAP_NONZERO) return KS_ERR_INVALID_ARG;
-    const PairEntry *e = map == KS_MAP_IDENTITY ? pair_entry(dtype, op) : pair_entry_mapped((int)dtype, (int)map, (int)op);
+    if ((int)map < KS_MAP_IDENTITY || (int)map >= KS_MAP_COUNT) return KS_ERR_INVALID_ARG;
+    const PairEntry *e = reduce_entry((int)dtype, (int)map, (int)op);
     if (!e) return KS_ERR_UNSUPPORTED;
     if (!out || (n > 0 && !in)) return KS_ERR_INVALID_ARG;
     if (n > ((size_t)1 << 40)) return KS_ERR_INVALID_ARG;
-    if (((uintptr_t)in % e->elem_align) || ((uintptr_t)out % e->elem_align)) return KS_ERR_MISALIGNED;
+    if (((uintptr_t)in % e->elem_align) || ((uintptr_t)out % e->result_align)) return KS_ERR_MISALIGNED;
     return scan_with_library_workspace(e, 1, in, out, n, stream, 1, 1, true);
+}
+
+size_t ks_mapreduce_result_bytes(ks_dtype dtype, ks_map map, ks_op op) {
+    const PairEntry *e = reduce_entry((int)dtype, (int)map, (int)op);
+    if (!e) return 0;
+    if (e->elem_bytes != 1 && e->elem_bytes != 4 && e->elem_bytes != 8 && e->elem_bytes != 16) return 0;
+    return e->result_bytes;
 }
 
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {
@@ -323,6 +339,7 @@ size_t ks_elem_bytes(ks_dtype dtype) {
         case KS_ARGMAX_I32_CNT64: case KS_MAT2_U32: case KS_QUAT_F32: return 16;
         case KS_MAT2_U64: return 32;
         case KS_RANGE_I32_CNT32: return 12;
+        case KS_U8: return 1;
         default: return 0;
     }
 }

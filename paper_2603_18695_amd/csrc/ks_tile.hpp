@@ -30,7 +30,7 @@ constexpr bool granule_sized() { return sizeof(IO) == 4 || sizeof(IO) == 8 || si
 
 template <class IO, int ROWS_>
 struct TileShape {
-    static_assert(granule_sized<IO>(), "element must be 4, 8 or 16 bytes in the striped arrangement");
+    static_assert(16 % sizeof(IO) == 0, "a 16-byte granule must hold whole elements in the striped arrangement");
     static constexpr int ROWS = ROWS_;
     static constexpr int G = 16 / (int)sizeof(IO);  // elements per 16-byte granule
     static constexpr int ITEMS = ROWS * G;          // elements per thread
@@ -72,8 +72,12 @@ __device__ __forceinline__ TileWindow tile_window(const IO *base, size_t n, size
     const size_t left = n > tile_first ? n - tile_first : 0;
     const uint32_t valid = (uint32_t)((left < tile_elems ? left : tile_elems) * sizeof(IO));
     TileWindow w;
+    // Elements narrower than a dword (read only, by the reduction): the range check works on
+    // dwords, so the extent is rounded up to the dword that holds the last element; `base` is
+    // dword-aligned there, the surplus bytes lie in the same dword, and valid_bytes stays exact.
+    const uint32_t extent = sizeof(IO) < 4 ? (valid + 3u) & ~3u : valid;
     // raw buffer (stride 0), 32-bit data format, no swizzle: the gfx90a / gfx94x / gfx950 encoding
-    w.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<IO *>(base + tile_first), 0, (int)valid, 0x00020000);
+    w.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<IO *>(base + tile_first), 0, (int)extent, 0x00020000);
     w.valid_bytes = valid;
     return w;
 }

@@ -119,6 +119,20 @@ struct SumOp<int64_t> {
     __device__ __forceinline__ int64_t operator()(int64_t l, int64_t r) const { return (int64_t)((uint64_t)l + (uint64_t)r); }
 };
 
+// Sums over bytes (mapreduce only; the 8-bit types of the paper's mapreduce benchmark, Sec. VII-B).
+// A lane adds the bytes of one run in 32 bits (64 bytes of at most 255 each); above the run the
+// sum is carried in the chain type: 32 bits when the result is a byte again (the sum modulo 2^8
+// is the low byte of any wider wrapped sum), 64 bits when the caller asked for the widened sum.
+struct ByteSumOp {
+    static constexpr bool commutative = true;
+    using acc = uint32_t;
+    __device__ static uint32_t identity() { return 0u; }
+    __device__ __forceinline__ uint32_t operator()(uint32_t l, uint32_t r) const { return l + r; }
+};
+struct ByteWideSumOp : ByteSumOp {
+    using chain = SumOp<uint64_t>;
+};
+
 template <class T>
 struct MinOp {
     static constexpr bool commutative = true;
@@ -263,6 +277,28 @@ struct NonzeroMap {  // 1 where x != 0, else 0: a sum scan of it numbers the kep
     __device__ __forceinline__ T operator()(const T &x) const { return x != T(0) ? T(1) : T(0); }
 };
 
+// Maps that change the type, f: T -> S (paper Sec. II-C): `result` is S, the type of what a
+// mapreduce with this map writes.
+struct Widen64Map {   // a byte as an integer that sums of any length cannot wrap
+    using result = uint64_t;
+    __device__ __forceinline__ uint32_t operator()(uint8_t c) const { return c; }
+};
+// Code c = level c of 256 evenly spaced levels from -1 to +1 (paper Sec. VII-B, UnitFloat8),
+// (2c - 255) / 255, promoted to float32.  x = 2c - 255 is exact.  One multiplication by the
+// float32 nearest to 1/255 would be off by one unit in the last place for half of the codes, so
+// 1/255 is carried as two float32 constants, hi + lo, and x * hi + (x * lo) is rounded once by
+// the fused operation: the float32 nearest to the rational level for every one of the 256 codes
+// (checked code by code against exact rationals).
+struct UnitFloat8Map {
+    using result = float;
+    static constexpr float kHi = 0x1.010102p-8f;     // float32 nearest to 1/255
+    static constexpr float kLo = -0x1.fdfdfep-33f;   // float32 nearest to 1/255 - kHi
+    __device__ __forceinline__ float operator()(uint8_t c) const {
+        const float x = __builtin_fmaf((float)c, 2.0f, -255.0f);
+        return __builtin_fmaf(x, kHi, x * kLo);
+    }
+};
+
 template <class Op, class Map>
 struct MappedOp : Op {
     using map = Map;
@@ -297,6 +333,18 @@ struct ChainOf<Op, decltype((void)sizeof(typename Op::chain))> {
     using type = typename op::acc;
 };
 
+// ResultOf<Op, IO>::type: what a mapreduce writes: the map's result type if it names one, else IO.
+template <class Op, class IO, class = void>
+struct ResultOf {
+    using type = IO;
+    static constexpr bool from_map = false;
+};
+template <class Op, class IO>
+struct ResultOf<Op, IO, decltype((void)sizeof(typename MapOf<Op>::type::result))> {
+    using type = typename MapOf<Op>::type::result;
+    static constexpr bool from_map = true;
+};
+
 // ---- conversions between memory type, accumulation type and chain type ------------
 
 template <class To, class From>
@@ -314,6 +362,18 @@ struct Convert<double, float> {
 template <>
 struct Convert<float, double> {
     __device__ __forceinline__ static float apply(const double &x) { return (float)x; }
+};
+template <>
+struct Convert<uint32_t, uint8_t> {
+    __device__ __forceinline__ static uint32_t apply(const uint8_t &x) { return x; }
+};
+template <>
+struct Convert<uint8_t, uint32_t> {   // modulo 2^8
+    __device__ __forceinline__ static uint8_t apply(const uint32_t &x) { return (uint8_t)x; }
+};
+template <>
+struct Convert<uint64_t, uint32_t> {
+    __device__ __forceinline__ static uint64_t apply(const uint32_t &x) { return x; }
 };
 template <>
 struct Convert<AffineF64, AffineF32> {

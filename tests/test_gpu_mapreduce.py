@@ -149,6 +149,89 @@ def test_full_size_configs(ks):
         del d_in
 
 
+# ---- bytes: the 8-bit types of the paper's mapreduce benchmark (Sec. VII-B, Tables I and III) ----
+BYTE_MAPS = {"unit_float8": np.float32, "widen64": np.uint64, "identity": np.uint8}
+
+
+def reduce_bytes_on_gpu(ks, d_in, map_name):
+    """d_in: a uint8 device tensor (any slice); returns the result as a numpy scalar of the result type."""
+    rt = BYTE_MAPS[map_name]
+    out = torch.full((np.dtype(rt).itemsize,), 0x55, dtype=torch.uint8, device="cuda")
+    ks.ks_mapreduce(d_in, out, dtype="u8", op="sum", map=map_name)
+    ks.ks_scan_check()
+    return out.cpu().numpy().view(rt)[0]
+
+
+def check_bytes(map_name, got, x, what):
+    ref = oracle.mapreduce(map_name, "sum", "u8", x)
+    if map_name == "unit_float8":
+        assert abs(float(got) - float(ref)) <= float_bound(np.array([float(ref)]))[0], f"{what}: gpu={got} ref={ref}"
+    else:
+        assert int(got) == int(ref), f"{what}: gpu={got} ref={ref}"
+
+
+def test_unit_float8_levels_one_by_one(ks):
+    # n = 1: the result is the level itself, promoted to float32: bit for bit the oracle's, for all 256 codes
+    codes = to_device(np.arange(256, dtype=np.uint8))
+    levels = oracle.apply_map("unit_float8", np.arange(256, dtype=np.uint8))
+    say("[case] mapreduce unit_float8: the 256 levels")
+    for c in range(256):
+        got = reduce_bytes_on_gpu(ks, codes[c:c + 1], "unit_float8")
+        assert got.dtype == np.float32 and got == levels[c], (c, got, levels[c])
+
+
+@pytest.mark.parametrize("map_name", sorted(BYTE_MAPS))
+def test_byte_sums_edge_sizes_and_offsets(ks, map_name):
+    run = 64 * 4 * 16                       # bytes one wave folds per step
+    sizes = [0, 1, 2, 3, 4, 5, 15, 16, 17, 63, 64, 65, 1023, 1024, 1025, run - 1, run, run + 1, 4 * run - 3, 4 * run,
+             4 * run + 1, 37 * run + 5, 512 * 4 * run - 1, 512 * 4 * run + 2, 3 * 512 * 4 * run + 12345]
+    x_all = ks_inputs.random_codes(sizes[-1] + 16, seed=31)
+    d_all = to_device(x_all)
+    for n in sizes:
+        for off in ((0, 1, 2, 3, 5) if n < 70_000 else (0, 3)):      # the input need not start on a dword
+            say(f"[case] mapreduce (u8,{map_name},sum) n={n} +{off}")
+            got = reduce_bytes_on_gpu(ks, d_all[off:off + n], map_name)
+            check_bytes(map_name, got, x_all[off:off + n], f"(u8,{map_name}) n={n} +{off}")
+
+
+def test_byte_sums_closed_forms(ks):
+    n = (1 << 25) + 77
+    full = torch.full((n,), 255, dtype=torch.uint8, device="cuda")
+    say(f"[case] mapreduce u8 closed forms n={n}")
+    assert int(reduce_bytes_on_gpu(ks, full, "widen64")) == 255 * n          # > 2^32: carried in 64 bits
+    assert int(reduce_bytes_on_gpu(ks, full, "identity")) == (255 * n) % 256
+    assert float(reduce_bytes_on_gpu(ks, full, "unit_float8")) == float(np.float32(n))   # level 255 = +1
+    full.fill_(0)
+    assert float(reduce_bytes_on_gpu(ks, full, "unit_float8")) == -float(np.float32(n))  # level 0 = -1
+    # every level equally often: the levels cancel in pairs and the exact sum is 0.  The input is as
+    # regular as can be (every lane adds the same 16 levels in every run), so the float32 roundings
+    # inside the runs repeat instead of averaging out; what bounds them is the error of a
+    # recursive float32 sum of the 64 terms of one lane and run, 63 * 2^-24 * sum |level|
+    # (above the run the sum is carried in double)
+    reps = 1 << 14
+    cyc = to_device(np.tile(np.arange(256, dtype=np.uint8), reps))
+    sum_abs = reps * float(np.abs(oracle.apply_map("unit_float8", np.arange(256, dtype=np.uint8)).astype(np.float64)).sum())
+    assert abs(float(reduce_bytes_on_gpu(ks, cyc, "unit_float8"))) <= 63 * 2.0 ** -24 * sum_abs
+    assert abs(float(reduce_bytes_on_gpu(ks, cyc, "unit_float8"))) <= 1e-8 * sum_abs    # and far inside it
+    # the scans refuse bytes, and so does every other operator
+    with pytest.raises(ks.KsError) as e:
+        ks.ks_scan(cyc, torch.empty_like(cyc), dtype="u8", op="sum")
+    assert e.value.status == ks.KS_ERR_UNSUPPORTED
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="max") == 0
+
+
+def test_byte_sums_at_the_paper_sizes(ks):
+    # n = 10^6 ... 10^9 (Tables I and III); uniform codes (the sum of the levels wanders around zero)
+    # and codes skewed upwards (it grows)
+    for n, skew in ((10 ** 6, 0.0), (10 ** 7, 0.25), (10 ** 8, 0.0), (10 ** 9, 0.25)):
+        x = ks_inputs.random_codes(n, seed=41, skew=skew)
+        d = to_device(x)
+        for map_name in sorted(BYTE_MAPS):
+            say(f"[case] mapreduce (u8,{map_name},sum) n={n} skew={skew}")
+            check_bytes(map_name, reduce_bytes_on_gpu(ks, d, map_name), x, f"(u8,{map_name}) n={n} skew={skew}")
+        del d, x
+
+
 def test_recorded_into_a_graph(ks):
     n = 3_000_001
     xs = [np.random.default_rng(90 + r).integers(-50, 50, size=n).astype(np.int32) for r in range(3)]
