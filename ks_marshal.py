@@ -21,7 +21,7 @@ def to_device(x: np.ndarray, device="cuda") -> torch.Tensor:
     if x.dtype == ARGMAX_DTYPE:
         x = x.view(np.int32).reshape(-1, 4)
     elif x.dtype.names:                      # any other struct of 32-bit words
-        x = x.view(np.int32).reshape(len(x), -1)
+        x = x.view(np.int32).reshape(len(x), x.dtype.itemsize // 4)
     elif x.dtype in _SIGNED_VIEW:
         x = x.view(_SIGNED_VIEW[x.dtype])
     return torch.from_numpy(x).to(device)

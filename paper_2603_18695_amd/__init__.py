@@ -92,9 +92,16 @@ def _check(status: int, where: str) -> None:
         raise KsError(status, where)
 
 
-def _stream_ptr(stream) -> int:
+# torch.cuda.current_stream() builds a Stream object (about 3 us, as much as the launch itself);
+# the raw handle of the device's current stream comes straight from the C layer where torch has it.
+_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
+def _stream_ptr(stream, device_index=None) -> int:
     if stream is None:
-        stream = torch.cuda.current_stream()
+        if _raw_current_stream is not None:
+            return _raw_current_stream(torch.cuda.current_device() if device_index is None else device_index)
+        stream = torch.cuda.current_stream(device_index)
     return int(stream.cuda_stream)
 
 
@@ -114,6 +121,7 @@ class _OnDeviceOf:
 
 
 _ELEM_BYTES: dict = {}
+_RESULT_BYTES: dict = {}
 
 
 def _nbytes(t: torch.Tensor) -> int:
@@ -141,7 +149,7 @@ def ks_scan(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, inclus
         raise ValueError("inp and out differ in size")
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
-                            _stream_ptr(stream)), "ks_scan")
+                            _stream_ptr(stream, inp.device.index)), "ks_scan")
     return out
 
 
@@ -152,12 +160,14 @@ def ks_mapreduce(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, m
     n = _elements(inp, dtype)
     if not out.is_cuda or not out.is_contiguous():
         raise ValueError("out must be a contiguous device tensor")
-    want = ks_mapreduce_result_bytes(dtype=dtype, map=map, op=op)
+    want = _RESULT_BYTES.get((dtype, map, op))
+    if want is None:     # asked of the library once per triple
+        want = _RESULT_BYTES[(dtype, map, op)] = ks_mapreduce_result_bytes(dtype=dtype, map=map, op=op)
     if want and _nbytes(out) != want:    # a triple the library does not take is for the library to refuse
         raise ValueError("out must hold exactly one element of the result type")
     with _OnDeviceOf(inp):
         _check(_lib.ks_mapreduce(DTYPES[dtype], MAPS[map], OPS[op], inp.data_ptr() if n else None, n, out.data_ptr(),
-                                 _stream_ptr(stream)), "ks_mapreduce")
+                                 _stream_ptr(stream, inp.device.index)), "ks_mapreduce")
     return out
 
 
@@ -177,7 +187,7 @@ def ks_scan_static(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str,
         raise ValueError("inp and out differ in size")
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan_static(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
-                                   _stream_ptr(stream)), "ks_scan_static")
+                                   _stream_ptr(stream, inp.device.index)), "ks_scan_static")
     return out
 
 
@@ -189,7 +199,7 @@ def ks_scan_map(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, map: str, o
         raise ValueError("inp and out differ in size")
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan_map(DTYPES[dtype], MAPS[map], OPS[op], int(bool(inclusive)), inp.data_ptr(),
-                                out.data_ptr(), n, _stream_ptr(stream)), "ks_scan_map")
+                                out.data_ptr(), n, _stream_ptr(stream, inp.device.index)), "ks_scan_map")
     return out
 
 
@@ -202,7 +212,8 @@ def ks_scan_strided(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str
             raise ValueError("tensor too small for the requested view")
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan_strided(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), in_stride,
-                                    out.data_ptr(), out_stride, n, _stream_ptr(stream)), "ks_scan_strided")
+                                    out.data_ptr(), out_stride, n, _stream_ptr(stream, inp.device.index)),
+               "ks_scan_strided")
     return out
 
 
@@ -224,7 +235,8 @@ def ks_scan_with_temp(inp: torch.Tensor, out: torch.Tensor, temp: torch.Tensor, 
         raise ValueError("temp must be a contiguous device tensor")
     with _OnDeviceOf(inp):
         _check(_lib.ks_scan_with_temp(DTYPES[dtype], OPS[op], int(bool(inclusive)), ALGOS[algo], inp.data_ptr(),
-                                      out.data_ptr(), n, temp.data_ptr(), _nbytes(temp), _stream_ptr(stream)),
+                                      out.data_ptr(), n, temp.data_ptr(), _nbytes(temp),
+                                      _stream_ptr(stream, inp.device.index)),
                "ks_scan_with_temp")
     return out
 
@@ -254,7 +266,7 @@ def ks_copy(inp: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
     """Vectorised device copy used as the bandwidth ceiling in measurements."""
     if _nbytes(inp) != _nbytes(out):
         raise ValueError("inp and out differ in size")
-    _check(_lib.ks_copy(inp.data_ptr(), out.data_ptr(), _nbytes(inp), _stream_ptr(stream)), "ks_copy")
+    _check(_lib.ks_copy(inp.data_ptr(), out.data_ptr(), _nbytes(inp), _stream_ptr(stream, inp.device.index)), "ks_copy")
     return out
 
 

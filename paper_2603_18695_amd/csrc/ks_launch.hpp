@@ -3,6 +3,7 @@
 // the reduce-then-scan recursion.  Instantiated once per pair in ks_pairs_*.hip.
 #pragma once
 
+#include <cmath>
 #include <map>
 #include <type_traits>
 
@@ -124,8 +125,8 @@ inline int reported_occupancy(const ScanCall &c, std::map<int, int> &cache, Kern
 }
 
 // ---- mapreduce: the launch -----------------------------------------------------------
-// Every pair whose elements fill a 16-byte granule evenly (1, 2, 4, 8, 16 bytes) can be reduced;
-// pairs that are also scanned reach this through Pair, the byte types through ReducePair.
+// Every pair can be reduced; those that are also scanned reach this through Pair, the byte types
+// through ReducePair.
 template <class T, class Op>
 struct ReduceLaunch {
     using C = typename ChainOf<Op>::type;
@@ -134,16 +135,19 @@ struct ReduceLaunch {
     // Shape, measured on MI355X (GB/s of the bytes read, rows x workgroups per compute unit).  Commutative
     // operators (strided runs): float32 sum 2^28 4 x 2 7186, 2 x 4 6970, 4 x 4 6876, 8 x 2 6871, 4 x 8 6459;
     // arg-max struct 2^26 4 x 2 7120, 4 x 4 6771, 4 x 8 6344: two workgroups per compute unit keep enough
-    // loads in flight, more only add partials to fold at the end.  Ordered operators (contiguous
-    // ranges, one ordered wave reduction per row, bound by instruction issue): 2x2 matrices 8 x 8
-    // 5058, 4 x 8 4930, 8 x 2 4633; affine 8 x 8 5305, 2 x 8 5521, 4 x 2 4860.
-    static constexpr int kReduceRows = Op::commutative ? 4 : 8;
+    // loads in flight, more only add partials to fold at the end.  Ordered reductions (contiguous
+    // ranges, blocked arrangement through LDS, one ordered wave reduction per run), us per call at 1 GiB
+    // with 1 / 2 / 3 / 4 / 8 workgroups per compute unit: affine 185 / 164 / 174 / 180 / 182, 2x2 uint32
+    // matrices 183 / 164 / 175 / 178 / 184, quaternions 202 / 165 / 175 / 179 / 186, 2x2 uint64 matrices
+    // 248 / 174 / 184 / 199 / 198, range struct 153 / 159 / 164 / 169 / 178.
+    static constexpr bool kOrdered = ordered_reduction<T, Op>();
+    static constexpr int kReduceRows = !kOrdered ? 4 : blocked_fits<T, 8>() ? 8 : 9;
     // Bytes decoded to float32 (UnitFloat8): five instructions per byte read make that kernel bound by
     // arithmetic, and a third workgroup per compute unit hides more of it: n = 10^9, us per call with
-    // 1 / 2 / 3 / 4 / 6 workgroups 294 / 181 / 168 / 177 / 161 (10^8: 33 / 24.7 / 24.6 / 27 / 31); the plain
-    // byte sums stay at two: 240 / 145 / 146 / 168 / 152.
+    // 1 / 2 / 3 / 4 / 6 workgroups 285 / 176 / 151 / 151 / 160 (10^8: 32 / 23.7 / 24.2 / 27 / 31); the plain
+    // byte sums stay at two: 220 / 138 / 146 / 147 / 151.
     static constexpr bool kDecodesBytes = sizeof(T) == 1 && std::is_same<typename Op::acc, float>::value;
-    static constexpr int kReduceWgsPerCu = !Op::commutative ? 8 : kDecodesBytes ? 3 : 2;
+    static constexpr int kReduceWgsPerCu = kDecodesBytes ? 3 : 2;
     static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * 16 / sizeof(T);   // elements per run
     static size_t reduce_scratch_bytes(size_t grid) {
         return kControlBytes + align_up((grid > 0 ? grid : 1) * WordsOf<C>::W * sizeof(uint64_t), 256);
@@ -170,6 +174,15 @@ struct ReduceLaunch {
         }
         const size_t total_runs = ceil_div(n, kReduceRun);
         size_t grid = (size_t)per_cu * (size_t)c.dev->cus;
+        if (want <= 0) {
+            // Below about 100 MB fewer workgroups are faster: each one costs about 12 ns at the end (its
+            // partial, and its turn at the one counter), and one workgroup streams about 29 GB/s, so
+            // g workgroups take a * g + B / (g * w) and the best g is sqrt(B / (a * w)) = sqrt(B / 350 bytes).
+            // Measured, float32 sum, us per call at grids of 64 / 128 / 256 / 512: 4 MB 4.4 / 4.7 / 6.0 / -,
+            // 10 MB 5.7 / 5.4 / 6.3 / 9.4, 40 MB 23.6 / 13.8 / 10.4 / 11.8, 100 MB 59 / 33 / 20.9 / 19.3.
+            const size_t by_bytes = (size_t)std::sqrt((double)(n * sizeof(T)) / 350.0);
+            if (grid > by_bytes) grid = by_bytes;
+        }
         if (grid > ceil_div(total_runs, (size_t)kWaves)) grid = ceil_div(total_runs, (size_t)kWaves);
         if (grid < 1) grid = 1;   // n == 0: one workgroup writes the identity
         if (reduce_scratch_bytes(grid) > c.temp_bytes) return KS_ERR_WORKSPACE;
@@ -516,13 +529,7 @@ struct Pair {
     }
 
     // ---- mapreduce ---------------------------------------------------------------
-    static int run_mapreduce(const ScanCall &c) {
-        if constexpr (!granule_sized<T>()) {
-            return KS_ERR_UNSUPPORTED;   // the reduction kernel is written for the striped arrangement
-        } else {
-            return ReduceLaunch<T, Op>::run(c);
-        }
-    }
+    static int run_mapreduce(const ScanCall &c) { return ReduceLaunch<T, Op>::run(c); }
 
     static int run(const ScanCall &c) {
         if (c.in_stride != 1 || c.out_stride != 1)

@@ -8,9 +8,12 @@
 //     loads and register arrangement as the scan).  For commutative operators a wave strides
 //     over the runs as the paper's threads stride over the elements, every lane folds its own
 //     items and one DPP reduction comes at the very end.  For the others a wave folds a
-//     CONTIGUOUS range of runs in order (one ordered DPP reduction per row), and since the
-//     partials are combined in workgroup order the result is the left fold: operators that do
-//     not commute are served too, which the paper's strided accumulation cannot do.
+//     CONTIGUOUS range of runs in order: each run goes through the wave's LDS region into the
+//     blocked arrangement (a lane holds ROWS consecutive granules), every lane folds its own
+//     elements in sequence and ONE ordered DPP reduction combines the lanes; since the partials
+//     are combined in workgroup order the result is the left fold: operators that do not commute
+//     are served too, which the paper's strided accumulation cannot do.  Element sizes that do
+//     not divide a granule (12, 32 bytes) take this path whatever the operator.
 //   - No designated workgroup that spins on flags: the workgroup that arrives LAST (a counter
 //     in the scratch) folds the partials, so nobody waits for a workgroup that has not run.
 //   - Partials travel as tagged 64-bit words (ks_kernels.hpp, descriptors): value and flag in
@@ -38,6 +41,53 @@ struct ReduceArgs {
 
 constexpr int kFinishWindows = 4;   // windows of 64 partials a finishing wave has in flight at once
 
+// ordered_reduction<IO, Op>(): contiguous ranges and the blocked arrangement instead of strided runs
+template <class IO, class Op>
+constexpr bool ordered_reduction() { return !Op::commutative || 16 % sizeof(IO) != 0; }
+
+// One run folded by its wave, any order allowed: the lane's own items, nothing across lanes.
+template <class IO, class Op, int ROWS>
+__device__ __forceinline__ typename Op::acc fold_run_lane_private(const RawItems<ROWS> &raw, int lane_bytes,
+                                                                  uint32_t valid_bytes, bool partial, uint32_t head_skip) {
+    using A = typename Op::acc;
+    using S = TileShape<IO, ROWS>;
+    Op op;
+    ThreadItems<A, ROWS, S::G> it;
+    unpack_items<IO, ROWS, Op, false>(raw, lane_bytes, valid_bytes, partial, it);
+    if constexpr (sizeof(IO) < 4) {
+        if (head_skip != 0) {   // the bytes in front of the caller's first element
+#pragma unroll
+            for (int k = 0; k < S::G; ++k)
+                if (lane_bytes + k * (int)sizeof(IO) < (int)head_skip) it.x[0][k] = Op::identity();
+        }
+    }
+    A mine = it.x[0][0];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+#pragma unroll
+        for (int k = 0; k < S::G; ++k)
+            if (j != 0 || k != 0) mine = op(mine, it.x[j][k]);
+    }
+    return mine;
+}
+
+// One run folded in order: through `region` (the wave's own LDS) into the blocked arrangement,
+// the lane's consecutive elements in sequence, then the lanes in order.  The same value in every lane.
+template <class IO, class Op, int ROWS>
+__device__ __forceinline__ typename Op::acc fold_run_in_order(u32x4 *region, RawItems<ROWS> raw, uint32_t valid_bytes,
+                                                              bool partial) {
+    using A = typename Op::acc;
+    constexpr int E = BlockedShape<IO, ROWS>::E;
+    Op op;
+    striped_to_blocked<ROWS>(region, raw);
+    LaneItems<A, E> it;
+    unpack_blocked<IO, ROWS, Op>(raw, 0, valid_bytes, partial, it);
+    A mine = it.y[0];
+#pragma unroll
+    for (int k = 1; k < E; ++k) mine = op(mine, it.y[k]);
+    return read_lane(wave_inclusive_scan(mine, op), kWave - 1);
+}
+
 template <class IO, class Op, int ROWS>
 __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typename ResultOf<Op, IO>::type *out,
                                                            ReduceArgs a) {
@@ -45,24 +95,24 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typenam
     using R = typename ResultOf<Op, IO>::type;
     using C = typename ChainOf<Op>::type;
     using COp = typename ChainOf<Op>::op;
-    using S = TileShape<IO, ROWS>;
-    constexpr size_t RUN = S::WAVE_ELEMS;
+    constexpr bool ORDERED = ordered_reduction<IO, Op>();
+    constexpr size_t RUN = (size_t)kWave * ROWS * 16 / sizeof(IO);   // elements of one run
     __shared__ typename WordsOf<C>::type s_tot[kWaves];
     __shared__ uint32_t s_last;
-    Op op;
+    __shared__ u32x4 s_stage[ORDERED ? kWaves * Stage<ROWS>::SLOTS : 1];
     COp cop;
     const int lane = threadIdx.x & (kWave - 1);
     // uniform for the compiler too: the runs' buffer descriptors then stay in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane_bytes = lane * 16;
     const size_t gw = (size_t)blockIdx.x * kWaves + wave;
-    // commutative: runs gw, gw + W, gw + 2W, ... (W = waves of the grid); ordered: a contiguous range
-    const size_t step = Op::commutative ? (size_t)gridDim.x * kWaves : 1;
-    size_t run = Op::commutative ? gw : gw * a.runs_per_wave;
-    size_t end = Op::commutative ? a.total_runs : run + a.runs_per_wave;
+    // any order: runs gw, gw + W, gw + 2W, ... (W = waves of the grid); ordered: a contiguous range
+    const size_t step = ORDERED ? 1 : (size_t)gridDim.x * kWaves;
+    size_t run = ORDERED ? gw * a.runs_per_wave : gw;
+    size_t end = ORDERED ? run + a.runs_per_wave : a.total_runs;
     if (end > a.total_runs) end = a.total_runs;
 
-    // Commutative: acc is the lane's own running value.  Otherwise: the wave's, the same in every lane.
+    // Any order: acc is the lane's own running value.  Ordered: the wave's, the same in every lane.
     C acc = COp::identity();
     RawItems<ROWS> raw;
     TileWindow w;
@@ -77,42 +127,20 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typenam
             wn = tile_window<IO>(in, a.n, (run + step) * RUN, RUN);
             load_raw<ROWS, false>(wn, lane_bytes, nxt);
         }
-        ThreadItems<A, ROWS, S::G> it;
-        unpack_items<IO, ROWS, Op, false>(raw, lane_bytes, w.valid_bytes, (run + 1) * RUN > a.n, it);
-        if constexpr (sizeof(IO) < 4) {
-            if (run == 0 && a.head_skip != 0) {   // the bytes in front of the caller's first element
-#pragma unroll
-                for (int k = 0; k < S::G; ++k)
-                    if (lane_bytes + k * (int)sizeof(IO) < (int)a.head_skip) it.x[0][k] = Op::identity();
-            }
-        }
-        if constexpr (Op::commutative) {
-            A mine = it.x[0][0];
-#pragma unroll
-            for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-                for (int k = 0; k < S::G; ++k)
-                    if (j != 0 || k != 0) mine = op(mine, it.x[j][k]);
-            }
-            acc = cop(acc, convert<C>(mine));
+        const bool partial = (run + 1) * RUN > a.n;
+        if constexpr (ORDERED) {
+            acc = cop(acc, convert<C>(fold_run_in_order<IO, Op, ROWS>(s_stage + wave * Stage<ROWS>::SLOTS, raw,
+                                                                      w.valid_bytes, partial)));
         } else {
-            A run_total = Op::identity();
-#pragma unroll
-            for (int j = 0; j < ROWS; ++j) {
-                A g = it.x[j][0];
-#pragma unroll
-                for (int k = 1; k < S::G; ++k) g = op(g, it.x[j][k]);
-                const A row_total = read_lane(wave_inclusive_scan(g, op), kWave - 1);   // lanes in order
-                run_total = (j == 0) ? row_total : op(run_total, row_total);
-            }
-            acc = cop(acc, convert<C>(run_total));
+            acc = cop(acc, convert<C>(fold_run_lane_private<IO, Op, ROWS>(raw, lane_bytes, w.valid_bytes, partial,
+                                                                          run == 0 ? a.head_skip : 0u)));
         }
         if (run + step < end) {
             raw = nxt;
             w = wn;
         }
     }
-    if constexpr (Op::commutative) acc = read_lane(wave_inclusive_scan(acc, cop), kWave - 1);
+    if constexpr (!ORDERED) acc = read_lane(wave_inclusive_scan(acc, cop), kWave - 1);
     if (lane == 0) s_tot[wave] = to_words(acc);
     __syncthreads();
     if (threadIdx.x == 0) {

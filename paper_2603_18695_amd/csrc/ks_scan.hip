@@ -292,9 +292,7 @@ int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n,
 
 size_t ks_mapreduce_result_bytes(ks_dtype dtype, ks_map map, ks_op op) {
     const PairEntry *e = reduce_entry((int)dtype, (int)map, (int)op);
-    if (!e) return 0;
-    if (e->elem_bytes != 1 && e->elem_bytes != 4 && e->elem_bytes != 8 && e->elem_bytes != 16) return 0;
-    return e->result_bytes;
+    return e ? e->result_bytes : 0;
 }
 
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {

@@ -81,6 +81,39 @@ def test_mapreduce_and_static_argument_checks_need_no_gpu(ks):
     assert lib.ks_scan_static(7, 4, 1, 1 << 40, 1 << 41, 1 << 27, None) == ks.KS_ERR_WORKSPACE   # beyond the static scratch
 
 
+def test_bytes_are_reduced_and_not_scanned(ks):
+    # the 8-bit types of the paper's mapreduce benchmark (Sec. VII-B): three sums over uint8, no scan
+    U8, SUM = ks.DTYPES["u8"], ks.OPS["sum"]
+    assert ks.ks_elem_bytes("u8") == 1
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="unit_float8") == 4      # a float
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="widen64") == 8          # a uint64
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="identity") == 1         # modulo 2^8
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="max") == 0
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="square") == 0
+    assert ks.ks_mapreduce_result_bytes(dtype="f32", op="sum", map="unit_float8") == 0     # the map takes bytes only
+    assert ks.ks_mapreduce_result_bytes(dtype="f32", op="sum") == 4
+    assert ks.ks_mapreduce_result_bytes(dtype="argmax_i32_cnt64", op="argmax_count") == 16
+    assert ks.ks_mapreduce_result_bytes(dtype="i32", op="sum", map="nonzero") == 4
+    assert ks.ks_mapreduce_result_bytes(dtype="mat2_u64", op="mat2_mul") == 32
+    assert ks.ks_mapreduce_result_bytes(dtype="range_i32_cnt32", op="range_count") == 12
+    lib = ks.raw_library()
+    assert lib.ks_mapreduce_result_bytes(99, 0, 0) == 0 and lib.ks_mapreduce_result_bytes(U8, 99, SUM) == 0
+    assert not ks.ks_pair_supported("u8", "sum") and not ks.ks_map_supported("u8", "unit_float8", "sum")
+    assert ks.ks_scan_temp_bytes(dtype="u8", op="sum", n=1000) == 0
+    lib.ks_scan.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.ks_scan(U8, SUM, 1, 0x10000000, 0x20000000, 16, None) == ks.KS_ERR_UNSUPPORTED
+    lib.ks_scan_strided.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                                         ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.ks_scan_strided(U8, SUM, 1, 0x10000000, 2, 0x20000000, 2, 16, None) == ks.KS_ERR_UNSUPPORTED
+    lib.ks_mapreduce.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.ks_mapreduce(U8, ks.MAPS["square"], SUM, 0x10000000, 5, 0x20000000, None) == ks.KS_ERR_UNSUPPORTED
+    assert lib.ks_mapreduce(U8, ks.MAPS["widen64"], ks.OPS["max"], 0x10000000, 5, 0x20000000, None) == ks.KS_ERR_UNSUPPORTED
+    # the input may start at any byte; the result must be aligned to its own type
+    assert lib.ks_mapreduce(U8, ks.MAPS["widen64"], SUM, 0x10000003, 5, 0x20000004, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_mapreduce(U8, ks.MAPS["unit_float8"], SUM, 0x10000003, 5, 0x20000002, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_mapreduce(U8, ks.MAPS["unit_float8"], SUM, None, 5, 0x20000000, None) == ks.KS_ERR_INVALID_ARG
+
+
 def test_map_triples(ks):
     for triple in [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
                    ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]:

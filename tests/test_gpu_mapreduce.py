@@ -45,18 +45,14 @@ def check(dtype, op, got, ref, what):
 
 
 def run_elems(ks, dtype):
-    return 64 * 8 * (16 // ks.ks_elem_bytes(dtype))       # elements one wave folds per step (4 or 8 rows per lane)
+    eb = ks.ks_elem_bytes(dtype)
+    rows = 9 if (8 * 16) % eb else 8                       # a lane's rows * 16 bytes hold whole elements
+    return 64 * rows * 16 // eb                            # elements one wave folds per step (at most)
 
 
 @pytest.mark.parametrize("dtype,op", sorted(KINDS))
 def test_every_pair_edge_sizes(ks, dtype, op):
     oop, odt, _, _ = KINDS[(dtype, op)]
-    if ks.ks_elem_bytes(dtype) not in (4, 8, 16):
-        # the reduction kernel is written for the striped arrangement: other element sizes are refused
-        with pytest.raises(ks.KsError) as e:
-            reduce_on_gpu(ks, dtype, op, random_input(dtype, op, 100, seed=1))
-        assert e.value.status == ks.KS_ERR_UNSUPPORTED
-        return
     run = run_elems(ks, dtype)
     sizes = [0, 1, 2, 63, 64, 65, run - 1, run, run + 1, 4 * run - 1, 4 * run, 4 * run + 1, 37 * run + 5,
              2048 * 4 * run - 1, 2048 * 4 * run + 1, 3 * 2048 * 4 * run + 12345]
