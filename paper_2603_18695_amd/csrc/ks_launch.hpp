@@ -136,10 +136,14 @@ struct ReduceLaunch {
     // operators (strided runs): float32 sum 2^28 4 x 2 7186, 2 x 4 6970, 4 x 4 6876, 8 x 2 6871, 4 x 8 6459;
     // arg-max struct 2^26 4 x 2 7120, 4 x 4 6771, 4 x 8 6344: two workgroups per compute unit keep enough
     // loads in flight, more only add partials to fold at the end.  Ordered reductions (contiguous
-    // ranges, blocked arrangement through LDS, one ordered wave reduction per run), us per call at 1 GiB
-    // with 1 / 2 / 3 / 4 / 8 workgroups per compute unit: affine 185 / 164 / 174 / 180 / 182, 2x2 uint32
-    // matrices 183 / 164 / 175 / 178 / 184, quaternions 202 / 165 / 175 / 179 / 186, 2x2 uint64 matrices
-    // 248 / 174 / 184 / 199 / 198, range struct 153 / 159 / 164 / 169 / 178.
+    // ranges, blocked arrangement through LDS, one ordered wave reduction per run; 8 rows, 9 for the
+    // 12-byte struct), us per call with 1 / 2 / 3 workgroups per compute unit:
+    //   affine (8 bytes)        128 MiB 24.3 / 24.9 / 29.4   512 MiB 79.8 / 84.1 / 88.9   1 GiB 180 / 160 / 174   2 GiB 349 / 332 / 337
+    //   range struct (12 bytes) 128 MiB 22.2 / 24.0 / 26.2   512 MiB 78.1 / 80.5 / 83.2   1 GiB 151 / 158 / 166   2 GiB 308 / 310 / 325
+    //   2x2 uint32 matrices     128 MiB 26.1 / 25.6 / 30.1   512 MiB 85.3 / 83.3 / 91.0   1 GiB 179 / 160 / 175   2 GiB 332 / 334 / 338
+    //   quaternions             128 MiB 28.7 / 26.5 / 30.8   512 MiB 93.9 / 84.8 / 92.7   1 GiB 195 / 160 / 176   2 GiB 366 / 336 / 337
+    //   2x2 uint64 matrices     128 MiB 37.9 / 31.9 / 35.4   512 MiB 126 / 89.7 / 97.5    1 GiB 242 / 173 / 180   2 GiB 457 / 340 / 335
+    // so: two, but one for elements below 16 bytes up to 768 MiB (for the 12-byte struct at any size).
     static constexpr bool kOrdered = ordered_reduction<T, Op>();
     static constexpr int kReduceRows = !kOrdered ? 4 : blocked_fits<T, 8>() ? 8 : 9;
     // Bytes decoded to float32 (UnitFloat8): five instructions per byte read make that kernel bound by
@@ -148,6 +152,7 @@ struct ReduceLaunch {
     // byte sums stay at two: 220 / 138 / 146 / 147 / 151.
     static constexpr bool kDecodesBytes = sizeof(T) == 1 && std::is_same<typename Op::acc, float>::value;
     static constexpr int kReduceWgsPerCu = kDecodesBytes ? 3 : 2;
+    static constexpr bool kOneWhenSmall = kOrdered && sizeof(T) < 16;
     static constexpr size_t kReduceRun = (size_t)kWave * kReduceRows * 16 / sizeof(T);   // elements per run
     static size_t reduce_scratch_bytes(size_t grid) {
         return kControlBytes + align_up((grid > 0 ? grid : 1) * WordsOf<C>::W * sizeof(uint64_t), 256);
@@ -159,6 +164,7 @@ struct ReduceLaunch {
         const int os = reported_occupancy(c, reported_per_cu, kernel, kBlock, per_cu);
         if (os != KS_OK) return os;
         if (per_cu > kReduceWgsPerCu) per_cu = kReduceWgsPerCu;
+        if (kOneWhenSmall && (c.n * sizeof(T) < ((size_t)768 << 20) || sizeof(T) % 8 != 0)) per_cu = 1;
         const long long want = options().wgs_per_cu;
         if (want > 0) per_cu = (int)(want < 64 ? want : 64);   // any grid is safe here: nobody waits for a workgroup
         // Elements narrower than a dword: the kernel's 16-byte reads start on a dword boundary, so the
@@ -203,7 +209,11 @@ struct ReduceLaunch {
         a.spin_limit = (uint32_t)(spin < 0 ? 0 : (spin > 0xffffffffll ? 0xffffffffll : spin));
         a.abort_flag = c.abort_flag;
         a.call_seq = c.call_seq;
-        const size_t per_wave = ceil_div(total_runs, grid * kWaves);
+        // Ordered reductions: an odd number of runs per wave.  All waves walk their ranges in step, and
+        // with ranges a power of two apart (1 GiB over 1024 waves: 1 MiB) their reads fall on the
+        // same memory channels at the same time (affine, 1 GiB: 178 us against 163 us with ranges 512 KiB apart).
+        size_t per_wave = ceil_div(total_runs, grid * kWaves);
+        if (per_wave > 2) per_wave |= 1;
         if (per_wave > 0xffffffffull) return KS_ERR_INVALID_ARG;
         a.runs_per_wave = (uint32_t)per_wave;
         LastLaunch &l = last_launch();
