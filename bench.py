@@ -350,6 +350,18 @@ def main() -> int:
         "parity": parity,
         "other_configs": others,
     }
+    if args.mapreduce and args.map == "unit_float8":
+        # five vector instructions per byte read: this reduction is bound by arithmetic before memory.
+        # Peak: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (no packed
+        # float32); instructions per byte: SQ_INSTS_VALU x 64 lanes / n of this kernel, from the committed
+        # rocprofv3 summary (counters cannot be read from inside a run).
+        valu_per_byte, alu_peak = 5.27, 256 * 4 * 16 * 2.4e9 / 1e12
+        achieved = valu_per_byte * n / (event_ms * 1e-3) / 1e12
+        result["roofline"] = {"bound": "alu", "achieved": achieved, "peak": alu_peak, "unit": "T lane-instructions/s",
+                              "frac": achieved / alu_peak, "traffic": None, "kernel_ms": event_ms,
+                              "instructions_per_byte": valu_per_byte,
+                              "instructions_source": "profiles/mapreduce_paper_sizes_f32_u8_kernel_trace.md",
+                              "hbm_frac": gbs_event / HBM_PEAK_GBS}
     print(json.dumps(result), flush=True)
     return 0
 

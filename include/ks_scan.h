@@ -16,8 +16,9 @@
  *   - Element sizes (paper Sec. IV-A: any struct of plain fields): 4, 8 and 16
  *     bytes run in every kernel shape; other sizes that divide 128 or 144 bytes
  *     (here 12 and 32) run in the one shape where a lane holds 8 or 9
- *     consecutive 16-byte granules, in both strategies and in ks_scan_strided;
- *     ks_mapreduce and the shape options "waves" / "form" do not apply to them.
+ *     consecutive 16-byte granules, in both strategies, in ks_scan_strided and in
+ *     ks_mapreduce; the shape options "waves" / "form" do not apply to them.
+ *     One-byte elements (KS_U8) are reduced only (ks_mapreduce).
  *   - in == out (exactly in place) is allowed; any other overlap is rejected.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise (except ks_scan_check)
@@ -166,9 +167,9 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
  *         where the map changes it: float for KS_MAP_UNIT_FLOAT8, uint64_t for
  *         KS_MAP_WIDEN64 (ks_mapreduce_result_bytes gives its size)
  *   map   KS_MAP_IDENTITY or one of the maps; accepted (dtype, map, op) triples are
- *         those for which ks_mapreduce_result_bytes is not 0: the triples of
- *         ks_map_supported, all of them for element sizes 4, 8 and 16 bytes, and
- *         the three sums over bytes (paper Sec. VII-B, Tables I and III):
+ *         those for which ks_mapreduce_result_bytes is not 0: every pair of
+ *         ks_pair_supported, the triples of ks_map_supported, and the three sums
+ *         over bytes (paper Sec. VII-B, Tables I and III):
  *         (KS_U8, KS_MAP_UNIT_FLOAT8, KS_SUM), (KS_U8, KS_MAP_WIDEN64, KS_SUM) and
  *         (KS_U8, KS_MAP_IDENTITY, KS_SUM), the last one modulo 2^8 as the element
  *         type's own addition is.  Others return KS_ERR_UNSUPPORTED.
