@@ -41,6 +41,24 @@ def test_python_binding_has_the_same_names(ks):
         assert hasattr(ks, name), name
 
 
+def test_binding_enums_match_the_header(ks):
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    consts = {name: int(value) for name, value in re.findall(r"\b(KS_[A-Z0-9_]+)\s*=\s*(-?\d+)", text)}
+    for table, prefix in ((ks.DTYPES, "KS_"), (ks.OPS, "KS_"), (ks.MAPS, "KS_MAP_"), (ks.ALGOS, "KS_ALGO_")):
+        for name, value in table.items():
+            assert consts[prefix + name.upper()] == value, (prefix, name)
+    assert len(ks.DTYPES) == consts["KS_DTYPE_COUNT"] and len(ks.OPS) == consts["KS_OP_COUNT"]
+    assert len(ks.MAPS) == consts["KS_MAP_COUNT"]
+    for name, value in consts.items():
+        if name.startswith("KS_ERR_") or name == "KS_OK":
+            assert getattr(ks, name) == value, name
+    # every element type has a size, and the binding's scratch limit is the header's
+    for name in ks.DTYPES:
+        assert ks.ks_elem_bytes(name) in (1, 4, 8, 12, 16, 32), name
+    m = re.search(r"#define\s+KS_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert ks.STATIC_SCRATCH_BYTES == int(m.group(1)) << int(m.group(2))
+
+
 def test_enums_and_sizes(ks):
     assert ks.ks_elem_bytes("f32") == 4 and ks.ks_elem_bytes("u64") == 8
     assert ks.ks_elem_bytes("affine_f32") == 8 and ks.ks_elem_bytes("argmax_i32_cnt64") == 16
