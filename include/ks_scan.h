@@ -268,9 +268,15 @@ size_t ks_elem_bytes(ks_dtype dtype);
  *                  8 x 8 up to 16 MiB of input), else 4, 8 or 16
  *   "rows"         16-byte vectors per thread in the look-back kernel: 0 = the type's
  *                  default, else 4, 8, 9, 12 or 16.  A (waves, rows, prefetch, form)
- *                  combination that is not compiled for an element type (it would not
- *                  fit the register file or LDS) makes the scan call return
- *                  KS_ERR_UNSUPPORTED
+ *                  combination that is not compiled for a pair makes the scan call
+ *                  return KS_ERR_UNSUPPORTED: one that would not fit the register
+ *                  file or LDS for the element type; and, for every pair but the
+ *                  eight that the shape search runs on (sums of float, int32_t,
+ *                  uint64_t and double, uint64_t maximum, the affine type, the
+ *                  arg-max struct, 2x2 uint32_t matrices: all shapes that fit), one
+ *                  outside what the defaults can select (16 waves in form 1 at any
+ *                  rows, the pair's own default shape, 4 x 8, 8 x 8 without
+ *                  prefetch, 4 x 4 for 16-byte elements)
  *   "prefetch"     1 = load the next tile before waiting in the look-back, 0 = not,
  *                  -1 = the type's default
  *   "form"         0 = one common loop for all waves (the 4- and 8-wave shapes), 1 = the

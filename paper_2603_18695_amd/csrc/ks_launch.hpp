@@ -109,6 +109,33 @@ struct PairDefaults {
     }
 };
 
+// Which pairs are compiled in EVERY shape that fits: the subjects of the shape search, one or two per
+// element class (their results set the class's defaults).  Every other pair is compiled in the
+// shapes its defaults can select: the 16-wave shapes in separate loops (all rows: inputs of a few
+// rounds choose among them), its own default shape, and the small shapes 4 x 8, 8 x 8 and 4 x 4.
+// A shape option that asks for anything else is refused for them with KS_ERR_UNSUPPORTED.  The full
+// matrix is some sixty kernels per pair, the reduced one some twenty.
+template <class T, class Op>
+struct FullMatrix : std::false_type {};
+template <> struct FullMatrix<float, SumOp<float>> : std::true_type {};
+template <> struct FullMatrix<int32_t, SumOp<int32_t>> : std::true_type {};
+template <> struct FullMatrix<uint64_t, SumOp<uint64_t>> : std::true_type {};
+template <> struct FullMatrix<double, SumOp<double>> : std::true_type {};
+template <> struct FullMatrix<uint64_t, MaxOp<uint64_t>> : std::true_type {};
+template <> struct FullMatrix<AffineF32, AffineComposeOp> : std::true_type {};
+template <> struct FullMatrix<ArgmaxI32Cnt64, ArgmaxCountOp> : std::true_type {};
+template <> struct FullMatrix<Mat2U32, Mat2MulOp> : std::true_type {};
+
+template <class T, class Op, int WAVES, int ROWS, bool PREFETCH, int FORM>
+constexpr bool variant_offered() {
+    if (!variant_fits<T, typename Op::acc, WAVES, ROWS, PREFETCH, FORM>()) return false;
+    if (FullMatrix<T, Op>::value) return true;
+    constexpr Shape d = PairDefaults<T, Op>::shape();
+    if (WAVES == 16) return FORM == kFormSeparate || (FORM == d.form && ROWS == d.rows);
+    if (WAVES == 4) return (ROWS == 8 && PREFETCH) || (ROWS == 4 && PREFETCH && sizeof(T) >= 16);
+    return WAVES == 8 && ROWS == 8 && !PREFETCH;
+}
+
 // Workgroups per compute unit the runtime reports for a kernel variant, per device.  It can be
 // higher than what the hardware grants; with tickets that only means some workgroups start late.
 template <class Kernel>
@@ -381,8 +408,8 @@ struct Pair {
 
     template <int WAVES, int ROWS, bool INCLUSIVE, bool PREFETCH, int FORM>
     static int launch_lookback(const ScanCall &c) {
-        if constexpr (!variant_fits<T, A, WAVES, ROWS, PREFETCH, FORM>()) {
-            return KS_ERR_UNSUPPORTED;   // this shape would spill registers for this element type
+        if constexpr (!variant_offered<T, Op, WAVES, ROWS, PREFETCH, FORM>()) {
+            return KS_ERR_UNSUPPORTED;   // would spill registers for this element type, or is not compiled for this pair
         } else {
             auto kernel = scan_lookback_kernel<T, Op, WAVES, ROWS, INCLUSIVE, PREFETCH, FORM>;
             constexpr int kThreads = WAVES * kWave;
