@@ -521,6 +521,54 @@ def test_two_streams_at_once(ks):
         assert torch.equal(o2, want2), it
 
 
+def test_two_host_threads_on_their_own_streams(ks):
+    # The library's state (options, per-stream scratch, epochs, abort words) is shared by all host
+    # threads; two threads that scan and reduce on streams of their own, at the same time (the binding
+    # releases the interpreter lock during a call), must each get the results of their own inputs.
+    import threading
+    jobs = []
+    for k, (dtype, op, n, seed) in enumerate((("i32", "sum", 3_000_017, 31), ("u64", "sum", 1_700_003, 32))):
+        x = random_input(dtype, op, n, seed=seed)
+        scan_ref = to_device(reference(dtype, op, x, True))
+        total = reference(dtype, op, x, True)[-1]
+        jobs.append({"dtype": dtype, "op": op, "d_in": to_device(x), "want": scan_ref, "total": int(total),
+                     "stream": torch.cuda.Stream(), "errors": []})
+    torch.cuda.synchronize()
+
+    def work(job):
+        try:
+            d_in, s = job["d_in"], job["stream"]
+            out = torch.empty_like(d_in)
+            one = torch.empty_like(d_in[:1])
+            temp = torch.empty(ks.ks_scan_temp_bytes(dtype=job["dtype"], op=job["op"], n=d_in.numel()), dtype=torch.uint8,
+                               device="cuda")
+            for it in range(60):
+                out.zero_()
+                one.zero_()
+                if it % 3 == 2:
+                    ks.ks_scan_with_temp(d_in, out, temp, dtype=job["dtype"], op=job["op"], stream=s)
+                else:
+                    ks.ks_scan(d_in, out, dtype=job["dtype"], op=job["op"], stream=s)
+                ks.ks_mapreduce(d_in, one, dtype=job["dtype"], op=job["op"], stream=s)
+                ks.ks_scan_check(s)
+                if not torch.equal(out, job["want"]):
+                    job["errors"].append(f"scan differs in iteration {it}")
+                got = int(to_host(one, np.int32 if job["dtype"] == "i32" else np.uint64)[0])
+                if got != job["total"]:
+                    job["errors"].append(f"reduction {got} != {job['total']} in iteration {it}")
+        except Exception as e:      # a thread's exception would otherwise be lost
+            job["errors"].append(repr(e))
+
+    say("[case] two host threads, each with its own stream: 60 scans and reductions each")
+    threads = [threading.Thread(target=work, args=(job,)) for job in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for job in jobs:
+        assert not job["errors"], job["errors"][:3]
+
+
 def test_hip_graph_replays_match_eager_results(ks):
     # ks_scan_with_temp allocates nothing and clears its descriptors with a kernel, so a caller may
     # record it into a HIP graph (after one eager call, which runs the one-off residency check of
