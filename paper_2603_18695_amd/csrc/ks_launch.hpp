@@ -522,25 +522,38 @@ struct Pair {
 
     // ---- strided views -------------------------------------------------------
     // The look-back scan with element-wise accesses and one-element granules, WAVES waves x
-    // kStridedRows rows x 64 elements per tile; one tile or many.  One workgroup per compute unit,
+    // strided_rows rows x 64 elements per tile; one tile or many.  One workgroup per compute unit,
     // tiles by index.
-    static constexpr int kStridedRows = sizeof(A) >= 32 ? 4 : sizeof(A) >= 16 ? 8 : 16;
-    static size_t strided_tile(int waves) { return (size_t)waves * kWave * kStridedRows; }
+    // Rows: 16, 8 or 4 by the accumulator's size.  The 16-wave workgroup has 128 registers per lane,
+    // and the items and their lane bases (2 x rows x the accumulator's words) stay live across the
+    // look-back: half the rows for accumulators of 8 bytes and more, 12 for the float32 sum, whose
+    // look-back runs in double.
+    template <int WAVES>
+    static constexpr int strided_rows() {
+        constexpr int base = sizeof(A) >= 32 ? 4 : sizeof(A) >= 16 ? 8 : 16;
+        if (WAVES < 16) return base;
+        if (sizeof(A) >= 8) return base / 2;
+        return sizeof(C) > sizeof(A) ? 12 : base;
+    }
+    template <int WAVES>
+    static constexpr size_t strided_tile() { return (size_t)WAVES * kWave * strided_rows<WAVES>(); }
     // temp_bytes(KS_ALGO_LOOKBACK, n) sizes the descriptors for the smallest contiguous tile
-    static_assert((size_t)4 * kWave * kStridedRows * sizeof(T) >= (size_t)kMinTileGranules * 16,
+    static_assert(strided_tile<4>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
+                      strided_tile<8>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
+                      strided_tile<16>() * sizeof(T) >= (size_t)kMinTileGranules * 16,
                   "strided tile below the smallest tile");
     template <int WAVES, bool INCLUSIVE>
     static int launch_lookback_strided(const ScanCall &c) {
-        auto kernel = scan_lookback_strided_kernel<T, Op, WAVES, kStridedRows, INCLUSIVE>;
+        auto kernel = scan_lookback_strided_kernel<T, Op, WAVES, strided_rows<WAVES>(), INCLUSIVE>;
         constexpr int kThreads = WAVES * kWave;
-        const size_t tiles = ceil_div(c.n, strided_tile(WAVES));
+        const size_t tiles = ceil_div(c.n, strided_tile<WAVES>());
         if (tiles >= 0xfffffff0ull) return KS_ERR_INVALID_ARG;
         if (lookback_scratch_bytes(tiles) > c.temp_bytes) return KS_ERR_WORKSPACE;
         uint32_t tickets = 0;
         const size_t grid = persistent_grid(c, 1, tiles, tickets);
         LastLaunch &l = last_launch();
         l.waves = WAVES;
-        l.rows = kStridedRows;
+        l.rows = strided_rows<WAVES>();
         l.form = kFormCommon;
         const LookbackArgs a = lookback_args(c, tiles, tickets);
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream, static_cast<const T *>(c.in),
@@ -550,7 +563,7 @@ struct Pair {
     }
     // Workgroup size by the distance between neighbouring elements: the closer they are, the more
     // of each cache line a wave uses and the more waves a compute unit can feed.  Measured, n = 2^24,
-    // us per call with 4 / 8 / 16 waves: float32 stride 2 (8 bytes apart) 99 / 73 / 68, stride 4 160 / 151 /
+    // us per call with 4 / 8 / 16 waves: float32 stride 2 (8 bytes apart) 99 / 73 / 64, stride 4 160 / 151 /
     // 163, stride 8 287 / 290 / 332, stride 32 1109 / 1121 / 1169; float64 stride 2 (16 bytes) 161 / 152 / 204,
     // stride 4 294 / 295 / 404, stride 8 593 / 637 / 763.
     static int run_strided(const ScanCall &c) {
@@ -561,7 +574,11 @@ struct Pair {
         switch (waves) {
             case 4: return c.inclusive ? launch_lookback_strided<4, true>(c) : launch_lookback_strided<4, false>(c);
             case 8: return c.inclusive ? launch_lookback_strided<8, true>(c) : launch_lookback_strided<8, false>(c);
-            default: return c.inclusive ? launch_lookback_strided<16, true>(c) : launch_lookback_strided<16, false>(c);
+            default:
+                // elements of 8 bytes and more are never 8 bytes apart, so only the "waves" option leads
+                // here for them; with more than 8 bytes to accumulate the wave scans do not fit 128 registers: not compiled
+                if constexpr (sizeof(T) > 8 || sizeof(A) > 8) return KS_ERR_UNSUPPORTED;
+                else return c.inclusive ? launch_lookback_strided<16, true>(c) : launch_lookback_strided<16, false>(c);
         }
     }
 
