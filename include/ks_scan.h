@@ -182,6 +182,17 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
 int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n, void *out,
                  void *stream);
 
+/*
+ * Give back the library-owned scratch that ks_scan, ks_scan_map, ks_scan_strided and
+ * ks_mapreduce cache for `stream` on the current device (the pre-allocation of the
+ * paper's Sec. VII-C, held until the process ends otherwise): for callers that are
+ * done with a stream, or create and destroy many.  Waits for the stream first.  A
+ * buffer that a stream capture has recorded is kept, since the graph may still be
+ * replayed.  The next call on the stream allocates again.  Returns KS_OK also when
+ * there was nothing to free.
+ */
+int ks_release_scratch(void *stream);
+
 /* 1 if ks_scan_map accepts this (dtype, map, op), else 0. */
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op);
 

@@ -34,7 +34,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5}
 
-EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -60,6 +60,8 @@ _lib.ks_scan_with_temp.argtypes = [_i, _i, _i, _i, _vp, _vp, _sz, _vp, _sz, _vp]
 _lib.ks_scan_with_temp.restype = _i
 _lib.ks_scan_check.argtypes = [_vp]
 _lib.ks_scan_check.restype = _i
+_lib.ks_release_scratch.argtypes = [_vp]
+_lib.ks_release_scratch.restype = _i
 _lib.ks_pair_supported.argtypes = [_i, _i]
 _lib.ks_pair_supported.restype = _i
 _lib.ks_elem_bytes.argtypes = [_i]
@@ -260,6 +262,11 @@ def ks_set_option(name: str, value: int) -> None:
 
 def ks_get_option(name: str) -> int:
     return int(_lib.ks_get_option(name.encode()))
+
+
+def ks_release_scratch(stream=None) -> None:
+    """Synchronise the stream and free the scratch the library caches for it (kept if a graph recorded it)."""
+    _check(_lib.ks_release_scratch(_stream_ptr(stream)), "ks_release_scratch")
 
 
 def ks_copy(inp: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:

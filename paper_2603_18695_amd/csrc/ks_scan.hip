@@ -295,6 +295,24 @@ size_t ks_mapreduce_result_bytes(ks_dtype dtype, ks_map map, ks_op op) {
     return e ? e->result_bytes : 0;
 }
 
+int ks_release_scratch(void *stream) {
+    hipError_t he = hipStreamSynchronize((hipStream_t)stream);   // nothing in flight may still use the buffer
+    if (he != hipSuccess) return set_hip_error(he);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const DeviceInfo *dev = nullptr;
+    int st;
+    if ((st = device_info(&dev)) != KS_OK) return st;
+    auto it = g_streams.find(std::make_pair(dev->device, (hipStream_t)stream));
+    if (it == g_streams.end()) return KS_OK;
+    StreamState &ws = it->second;
+    if (!ws.ptr || ws.captured) return KS_OK;   // nothing cached, or a graph may still replay into it
+    he = hipFree(ws.ptr);
+    ws.ptr = nullptr;
+    ws.bytes = 0;
+    ws.epoch = 0;
+    return he == hipSuccess ? KS_OK : set_hip_error(he);
+}
+
 int ks_map_supported(ks_dtype dtype, ks_map map, ks_op op) {
     if (map == KS_MAP_IDENTITY) return ks_pair_supported(dtype, op);
     return pair_entry_mapped((int)dtype, (int)map, (int)op) ? 1 : 0;

@@ -569,6 +569,49 @@ def test_two_host_threads_on_their_own_streams(ks):
         assert not job["errors"], job["errors"][:3]
 
 
+def test_release_scratch(ks):
+    # the library-owned scratch of a stream can be given back; the next call allocates again; a
+    # buffer that a graph has recorded is kept
+    s = torch.cuda.Stream()
+    ks.ks_release_scratch(s)                       # nothing cached yet: a no-op
+    dtype, op, n = "argmax_i32_cnt64", "argmax_count", 1 << 26
+    x = ks_inputs.whole("argmax", 1 << 16)
+    d_in = to_device(x).repeat(n >> 16, 1)
+    d_out = torch.empty_like(d_in)
+    small = random_input("i32", "sum", 100_003, seed=9)
+    d_small, ref_small = to_device(small), to_device(reference("i32", "sum", small, True))
+    o_small = torch.empty_like(d_small)
+    expect = ks.ks_scan_temp_bytes(dtype=dtype, op=op, n=n)
+    assert expect >= 4 << 20
+    torch.cuda.synchronize()
+    say(f"[case] release scratch: {expect} bytes held by a stream, then given back")
+    free_before = torch.cuda.mem_get_info()[0]
+    ks.ks_scan(d_in, d_out, dtype=dtype, op=op, stream=s)
+    ks.ks_scan_check(s)
+    free_held = torch.cuda.mem_get_info()[0]
+    ks.ks_release_scratch(s)
+    free_released = torch.cuda.mem_get_info()[0]
+    assert free_before - free_held >= expect // 2, (free_before, free_held, expect)
+    assert free_released - free_held >= expect // 2, (free_released, free_held, expect)
+    for _ in range(2):                             # allocates again (the smallest buffer), then reuses it
+        o_small.zero_()
+        ks.ks_scan(d_small, o_small, dtype="i32", op="sum", stream=s)
+        ks.ks_scan_check(s)
+        assert torch.equal(o_small, ref_small)
+    # recorded into a graph: the release leaves the buffer alone and the replays stay right
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        ks.ks_scan(d_small, o_small, dtype="i32", op="sum")
+    ks.ks_release_scratch(s)
+    for _ in range(3):
+        o_small.zero_()
+        with torch.cuda.stream(s):
+            graph.replay()
+        ks.ks_scan_check(s)
+        assert torch.equal(o_small, ref_small)
+    del graph
+
+
 def test_hip_graph_replays_match_eager_results(ks):
     # ks_scan_with_temp allocates nothing and clears its descriptors with a kernel, so a caller may
     # record it into a HIP graph (after one eager call, which runs the one-off residency check of
