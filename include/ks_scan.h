@@ -183,6 +183,29 @@ int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n,
                  void *stream);
 
 /*
+ * Types and operators of the caller's own (paper Sec. IV-A, V-B: any struct of plain
+ * fields, any associative operator).  The kernels are C++ templates in the headers
+ * next to the library's sources (csrc/ks_launch.hpp); a translation unit of the
+ * caller's, compiled by hipcc for gfx950 and linked against the library, defines
+ *     struct MyOp {                         // T: a trivially copyable struct, sizeof(T) a multiple of 4
+ *         static constexpr bool commutative = ...;
+ *         using acc = T;                    // the type held in registers
+ *         __device__ static T identity();
+ *         __device__ T operator()(T earlier, T later) const;
+ *     };
+ *     extern "C" const void *my_pair() { return ks::Pair<T, MyOp>::entry(); }
+ * and passes that pointer here.  Element sizes: 4, 8 and 16 bytes, and any other size
+ * that divides 128 or 144 bytes (12, 24, 32, 36, 48, ...).  Scratch, streams, graphs,
+ * errors and the in == out rule as for ks_scan and ks_mapreduce; a pointer that did
+ * not come from these headers in this version returns KS_ERR_INVALID_ARG.
+ * paper_2603_18695_amd/examples/user_pair.hip is a complete example.
+ */
+int ks_scan_pair(const void *pair, int inclusive, const void *in, void *out, size_t n, void *stream);
+int ks_mapreduce_pair(const void *pair, const void *in, size_t n, void *out, void *stream);
+/* sizeof the pair's element type; 0 if `pair` is not a pair of this version of the library. */
+size_t ks_pair_elem_bytes(const void *pair);
+
+/*
  * Give back the library-owned scratch that ks_scan, ks_scan_map, ks_scan_strided and
  * ks_mapreduce cache for `stream` on the current device (the pre-allocation of the
  * paper's Sec. VII-C, held until the process ends otherwise): for callers that are

@@ -34,7 +34,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5}
 
-EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_pair", "ks_mapreduce_pair", "ks_pair_elem_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -62,6 +62,12 @@ _lib.ks_scan_check.argtypes = [_vp]
 _lib.ks_scan_check.restype = _i
 _lib.ks_release_scratch.argtypes = [_vp]
 _lib.ks_release_scratch.restype = _i
+_lib.ks_scan_pair.argtypes = [_vp, _i, _vp, _vp, _sz, _vp]
+_lib.ks_scan_pair.restype = _i
+_lib.ks_mapreduce_pair.argtypes = [_vp, _vp, _sz, _vp, _vp]
+_lib.ks_mapreduce_pair.restype = _i
+_lib.ks_pair_elem_bytes.argtypes = [_vp]
+_lib.ks_pair_elem_bytes.restype = _sz
 _lib.ks_pair_supported.argtypes = [_i, _i]
 _lib.ks_pair_supported.restype = _i
 _lib.ks_elem_bytes.argtypes = [_i]
@@ -262,6 +268,43 @@ def ks_set_option(name: str, value: int) -> None:
 
 def ks_get_option(name: str) -> int:
     return int(_lib.ks_get_option(name.encode()))
+
+
+def ks_pair_elem_bytes(pair: int) -> int:
+    """sizeof the element type of a pair compiled outside the library; 0 if `pair` is not one."""
+    return int(_lib.ks_pair_elem_bytes(pair))
+
+
+def _pair_elements(t: torch.Tensor, pair: int) -> int:
+    eb = ks_pair_elem_bytes(pair)
+    if eb == 0:
+        raise ValueError("not a pair of this version of the library")
+    if not t.is_cuda or not t.is_contiguous() or _nbytes(t) % eb:
+        raise ValueError("tensor must be a contiguous device tensor of whole elements")
+    return _nbytes(t) // eb
+
+
+def ks_scan_pair(pair: int, inp: torch.Tensor, out: torch.Tensor, *, inclusive: bool = True, stream=None) -> torch.Tensor:
+    """out = scan(inp) for a type and operator compiled outside the library: `pair` is the address that
+    ks::Pair<T, Op>::entry() returned there (see include/ks_scan.h and examples/user_pair.hip)."""
+    n = _pair_elements(inp, pair)
+    if _pair_elements(out, pair) != n:
+        raise ValueError("inp and out differ in size")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_scan_pair(pair, int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
+                                 _stream_ptr(stream, inp.device.index)), "ks_scan_pair")
+    return out
+
+
+def ks_mapreduce_pair(pair: int, inp: torch.Tensor, out: torch.Tensor, *, stream=None) -> torch.Tensor:
+    """out[0] = the left fold of inp for a pair compiled outside the library; `out` holds one element."""
+    n = _pair_elements(inp, pair)
+    if _pair_elements(out, pair) != 1:
+        raise ValueError("out must hold exactly one element")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_mapreduce_pair(pair, inp.data_ptr() if n else None, n, out.data_ptr(),
+                                      _stream_ptr(stream, inp.device.index)), "ks_mapreduce_pair")
+    return out
 
 
 def ks_release_scratch(stream=None) -> None:

@@ -9,6 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libks_scan.so")
+# a pair defined outside the library, as a caller would (examples/user_pair.hip); the GPU tests load it
+USER_SRC = os.path.join(HERE, "examples", "user_pair.hip")
+USER_LIB = os.path.join(HERE, "examples", "libks_user_pair.so")
 SOURCES = ["ks_scan.hip", "ks_pairs_i32.hip", "ks_pairs_i64.hip", "ks_pairs_float.hip", "ks_pairs_struct.hip",
            "ks_pairs_mapped.hip", "ks_pairs_bytes.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
@@ -44,8 +47,13 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    cmd = [_hipcc(), *FLAGS, "-shared", "-I", CSRC, USER_SRC, "-L", HERE, "-lks_scan", "-Wl,-rpath,$ORIGIN/..",
+           "-o", USER_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the user-pair example failed:\n" + r.stderr)
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {USER_LIB}")
     return LIB
 
 

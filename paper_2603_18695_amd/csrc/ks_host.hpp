@@ -57,8 +57,13 @@ struct ScanCall {
     size_t in_stride = 1, out_stride = 1;
 };
 
-// One entry per instantiated (dtype, op) pair.
+// One entry per instantiated (dtype, op) pair.  Pair<T, Op>::entry() may also be instantiated outside
+// the library, in a translation unit of the caller's that includes ks_launch.hpp, for a type and an
+// operator of the caller's (ks_scan_pair / ks_mapreduce_pair take the pointer); `abi` tells the
+// library that both sides were compiled against the same layout of this struct and of ScanCall.
+constexpr uint32_t kPairAbi = 0x4b530002u;
 struct PairEntry {
+    uint32_t abi;
     size_t elem_bytes;
     size_t elem_align;
     size_t (*temp_bytes)(ks_algo algo, size_t n);

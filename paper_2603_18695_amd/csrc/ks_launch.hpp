@@ -594,7 +594,7 @@ struct Pair {
     }
 
     static const PairEntry *entry() {
-        static const PairEntry e = {sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
+        static const PairEntry e = {kPairAbi, sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
                                     &Pair::run_mapreduce, sizeof(T), alignof(T)};
         return &e;
     }
@@ -604,7 +604,7 @@ struct Pair {
 template <class T, class Op>
 struct ReducePair {
     static const PairEntry *entry() {
-        static const PairEntry e = {sizeof(T), alignof(T), nullptr, nullptr, nullptr, &ReduceLaunch<T, Op>::run,
+        static const PairEntry e = {kPairAbi, sizeof(T), alignof(T), nullptr, nullptr, nullptr, &ReduceLaunch<T, Op>::run,
                                     sizeof(typename ResultOf<Op, T>::type), alignof(typename ResultOf<Op, T>::type)};
         return &e;
     }

@@ -113,11 +113,18 @@ StreamState &stream_state(const DeviceInfo *dev, hipStream_t stream) {
     return st;
 }
 
+// pointers, size and overlap of a scan's arguments for the pair `e`
+int validate_arrays(const PairEntry *e, const void *in, void *out, size_t n);
+
 int validate(ks_dtype dtype, ks_op op, const void *in, void *out, size_t n, const PairEntry **entry) {
     if ((int)dtype < 0 || dtype >= KS_DTYPE_COUNT || (int)op < 0 || op >= KS_OP_COUNT) return KS_ERR_INVALID_ARG;
     const PairEntry *e = pair_entry(dtype, op);
     if (!e || !e->run) return KS_ERR_UNSUPPORTED;
     *entry = e;
+    return validate_arrays(e, in, out, n);
+}
+
+int validate_arrays(const PairEntry *e, const void *in, void *out, size_t n) {
     if (n == 0) return KS_OK;
     if (!in || !out) return KS_ERR_INVALID_ARG;
     if (n > ((size_t)1 << 40)) return KS_ERR_INVALID_ARG;
@@ -293,6 +300,37 @@ int ks_mapreduce(ks_dtype dtype, ks_map map, ks_op op, const void *in, size_t n,
 size_t ks_mapreduce_result_bytes(ks_dtype dtype, ks_map map, ks_op op) {
     const PairEntry *e = reduce_entry((int)dtype, (int)map, (int)op);
     return e ? e->result_bytes : 0;
+}
+
+// A pair compiled by the caller: the pointer must be what Pair<T, Op>::entry() returned to code
+// built against this version of the library's headers.
+static const PairEntry *caller_pair(const void *pair) {
+    const PairEntry *e = static_cast<const PairEntry *>(pair);
+    return e && e->abi == kPairAbi ? e : nullptr;
+}
+
+int ks_scan_pair(const void *pair, int inclusive, const void *in, void *out, size_t n, void *stream) {
+    const PairEntry *e = caller_pair(pair);
+    if (!e) return KS_ERR_INVALID_ARG;
+    if (!e->run) return KS_ERR_UNSUPPORTED;
+    const int st = validate_arrays(e, in, out, n);
+    if (st != KS_OK || n == 0) return st;
+    return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_mapreduce_pair(const void *pair, const void *in, size_t n, void *out, void *stream) {
+    const PairEntry *e = caller_pair(pair);
+    if (!e) return KS_ERR_INVALID_ARG;
+    if (!e->mapreduce) return KS_ERR_UNSUPPORTED;
+    if (!out || (n > 0 && !in)) return KS_ERR_INVALID_ARG;
+    if (n > ((size_t)1 << 40)) return KS_ERR_INVALID_ARG;
+    if (((uintptr_t)in % e->elem_align) || ((uintptr_t)out % e->result_align)) return KS_ERR_MISALIGNED;
+    return scan_with_library_workspace(e, 1, in, out, n, stream, 1, 1, true);
+}
+
+size_t ks_pair_elem_bytes(const void *pair) {
+    const PairEntry *e = caller_pair(pair);
+    return e ? e->elem_bytes : 0;
 }
 
 int ks_release_scratch(void *stream) {

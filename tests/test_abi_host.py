@@ -132,6 +132,31 @@ def test_bytes_are_reduced_and_not_scanned(ks):
     assert lib.ks_mapreduce(U8, ks.MAPS["unit_float8"], SUM, None, 5, 0x20000000, None) == ks.KS_ERR_INVALID_ARG
 
 
+def test_pairs_compiled_outside_the_library(ks):
+    # the example of a caller's own types and operators is built with the library; its pairs are
+    # recognised by their tag, anything else is refused before any GPU work
+    import os
+    user = ctypes.CDLL(os.path.join(os.path.dirname(ks.LIB_PATH), "examples", "libks_user_pair.so"))
+    pairs = {}
+    for name, size in (("affine_u32", 8), ("stats24", 24)):
+        fn = getattr(user, f"ks_user_{name}_pair")
+        fn.restype = ctypes.c_void_p
+        pairs[name] = fn()
+        assert ks.ks_pair_elem_bytes(pairs[name]) == size
+    lib = ks.raw_library()
+    junk = ctypes.create_string_buffer(256)
+    assert ks.ks_pair_elem_bytes(ctypes.addressof(junk)) == 0 and ks.ks_pair_elem_bytes(None) == 0
+    assert lib.ks_scan_pair(ctypes.addressof(junk), 1, 0x10000000, 0x20000000, 16, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_mapreduce_pair(None, 0x10000000, 16, 0x20000000, None) == ks.KS_ERR_INVALID_ARG
+    good = pairs["stats24"]
+    assert lib.ks_scan_pair(good, 1, None, None, 0, None) == ks.KS_OK                           # n == 0
+    assert lib.ks_scan_pair(good, 1, None, 0x20000000, 16, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_scan_pair(good, 1, 0x10000004, 0x20000000, 16, None) == ks.KS_ERR_MISALIGNED  # 8-byte fields
+    assert lib.ks_scan_pair(good, 1, 0x10000000, 0x10000018, 16, None) == ks.KS_ERR_OVERLAP
+    assert lib.ks_mapreduce_pair(good, 0x10000000, 16, None, None) == ks.KS_ERR_INVALID_ARG
+    assert lib.ks_mapreduce_pair(good, 0x10000000, 16, 0x20000004, None) == ks.KS_ERR_MISALIGNED
+
+
 def test_map_triples(ks):
     for triple in [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
                    ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]:
