@@ -13,7 +13,7 @@
 //     elements in sequence and ONE ordered DPP reduction combines the lanes; since the partials
 //     are combined in workgroup order the result is the left fold: operators that do not commute
 //     are served too, which the paper's strided accumulation cannot do.  Element sizes that do
-//     not divide a granule (12, 32 bytes) take this path whatever the operator.
+//     not divide a granule (12, 24, 32 bytes) take this path whatever the operator.
 //   - No designated workgroup that spins on flags: the workgroup that arrives LAST (a counter
 //     in the scratch) folds the partials, so nobody waits for a workgroup that has not run.
 //   - Partials travel as tagged 64-bit words (ks_kernels.hpp, descriptors): value and flag in
