@@ -39,7 +39,8 @@ extern "C" {
 typedef enum {
     KS_OK = 0,
     KS_ERR_INVALID_ARG = -1, /* null pointer with n > 0, bad enum value                      */
-    KS_ERR_UNSUPPORTED = -2, /* (dtype, op) pair not instantiated                            */
+    KS_ERR_UNSUPPORTED = -2, /* (dtype, op) pair, (dtype, map, op) triple or forced kernel shape
+                                that is not compiled                                         */
     KS_ERR_MISALIGNED = -3,  /* pointer not aligned to the element type                      */
     KS_ERR_OVERLAP = -4,     /* in and out overlap without being identical                   */
     KS_ERR_WORKSPACE = -5,   /* temp too small / misaligned, or internal allocation failed   */
@@ -67,7 +68,8 @@ typedef enum {
 
 /* Operators; L is the accumulated (earlier) operand, R the later one. */
 typedef enum {
-    KS_SUM = 0,            /* L + R (integers wrap); identity 0.  All six scalar types           */
+    KS_SUM = 0,            /* L + R (integers wrap); identity 0.  All six scalar types; KS_U8 in
+                              ks_mapreduce                                                       */
     KS_MIN = 1,            /* min(L, R); identity = largest value (+inf).  Scalar types          */
     KS_MAX = 2,            /* max(L, R); identity = smallest value (-inf). Scalar types.  With NaN
                               among float inputs the results of min / max from that element on
