@@ -173,7 +173,7 @@ def scan(op: str, dt: str | None, x: np.ndarray, inclusive: bool = True) -> np.n
     return ScanStream(op, dt, inclusive).feed(x)
 
 
-def apply_map(name: str, x: np.ndarray) -> np.ndarray:
+def apply_map(name: str, x: np.ndarray, kind: str | None = None) -> np.ndarray:
     """The element-wise map f of the map-fused scan ``scan(f, op, src)`` (paper Sec. IV-A).
 
     identity: x;  square: x * x (integers wrap in their own width; float32 inputs are squared in
@@ -186,8 +186,17 @@ def apply_map(name: str, x: np.ndarray) -> np.ndarray:
     the float32 nearest to that rational (float64 division, then one rounding to float32; the
     quotient of two small integers is far from any float32 tie, which the pins check code by code);
     widen64: the code as a uint64, so that a sum of bytes cannot wrap.
+    widen_f32 takes uint16 bit patterns and `kind` ("bf16" or "f16") and gives the float32 of the same value.
     """
     x = np.asarray(x)
+    if name == "widen_f32":
+        # 16-bit floats stored as uint16 bit patterns, promoted to float32 (every such value is a
+        # float32 exactly): "bf16" = the upper half of a float32's bits, "f16" = IEEE binary16
+        if x.dtype != np.uint16 or kind not in ("bf16", "f16"):
+            raise TypeError("map 'widen_f32' takes uint16 bit patterns of kind 'bf16' or 'f16'")
+        if kind == "bf16":
+            return (x.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        return x.view(np.float16).astype(np.float32)
     if name in ("unit_float8", "widen64"):
         if x.dtype != np.uint8:
             raise TypeError(f"map {name!r} takes uint8 codes")
@@ -265,8 +274,20 @@ def mapreduce(map_name: str, op: str, dt: str | None, x: np.ndarray, chunk: int 
         if map_name == "identity":
             return np.uint8(int(mapreduce("widen64", "sum", "u8", x, chunk)) & 0xFF)
         dt = {"unit_float8": "f32", "widen64": "u64"}[map_name]
+    kind = None
+    if dt in ("bf16", "f16"):
+        # 16-bit floats: reduced after promotion to float32 (sum, min, max), nothing else
+        if map_name != "widen_f32" or op not in ("sum", "min", "max"):
+            raise KeyError((map_name, op, dt))
+        kind, dt = dt, "f32"
     if n == 0:
         return identity_of(op, dt)
+    if kind is not None:
+        stream = ScanStream(op, dt, True)
+        last = None
+        for at in range(0, n, chunk):
+            last = stream.feed(np.ascontiguousarray(apply_map(map_name, x[at:at + chunk], kind)))[-1]
+        return last
     probe = apply_map(map_name, x[:1])
     if probe.dtype == np.float64 and dt == "f32":
         dt = "f64"   # squares of float32 values, held exactly in float64

@@ -261,3 +261,52 @@ def test_byte_sums_wide_and_in_the_element_type():
     assert int(oracle.mapreduce("identity", "sum", "u8", x[:0])) == 0 and int(oracle.mapreduce("widen64", "sum", "u8", x[:0])) == 0
     with pytest.raises(KeyError):
         oracle.mapreduce("identity", "max", "u8", x)
+
+
+# ---- 16-bit floats, reduced after promotion to float32 ----
+
+def _value_from_fields(bits: int, exp_bits: int, man_bits: int) -> float:
+    """sign, exponent and mantissa fields -> value, written out from the IEEE definition (finite codes only)."""
+    sign = -1.0 if bits >> (exp_bits + man_bits) else 1.0
+    e = (bits >> man_bits) & ((1 << exp_bits) - 1)
+    m = bits & ((1 << man_bits) - 1)
+    bias = (1 << (exp_bits - 1)) - 1
+    if e == 0:
+        return sign * m * 2.0 ** (1 - bias - man_bits)
+    return sign * (1.0 + m * 2.0 ** -man_bits) * 2.0 ** (e - bias)
+
+
+@pytest.mark.parametrize("kind,exp_bits,man_bits", [("bf16", 8, 7), ("f16", 5, 10)])
+def test_sixteen_bit_floats_promote_to_the_same_value(kind, exp_bits, man_bits):
+    codes = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    values = oracle.apply_map("widen_f32", codes, kind)
+    assert values.dtype == np.float32
+    top = (1 << exp_bits) - 1
+    finite = ((codes.astype(np.uint32) >> man_bits) & top) != top
+    want = np.array([_value_from_fields(int(c), exp_bits, man_bits) for c in codes[finite]])
+    assert np.array_equal(values[finite].astype(np.float64), want)          # every finite code, exactly
+    assert np.all(~np.isfinite(values[~finite]))                            # the rest are infinities and NaNs
+    assert float(values[0]) == 0.0 and np.signbit(values[0x8000])
+    with pytest.raises(TypeError):
+        oracle.apply_map("widen_f32", codes, None)
+    with pytest.raises(TypeError):
+        oracle.apply_map("widen_f32", codes.astype(np.int32), kind)
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+def test_sixteen_bit_float_reductions(kind):
+    x = ks_inputs.random_half_bits(kind, 200_003, seed=23)
+    values = oracle.apply_map("widen_f32", x, kind).astype(np.float64)
+    exact = math.fsum(values)
+    got = float(oracle.mapreduce("widen_f32", "sum", kind, x))
+    assert abs(got - exact) <= len(x) * 2.0 ** -53 * max(1.0, np.abs(np.cumsum(values)).max())
+    assert float(oracle.mapreduce("widen_f32", "max", kind, x)) == values.max()
+    assert float(oracle.mapreduce("widen_f32", "min", kind, x)) == values.min()
+    assert float(oracle.mapreduce("widen_f32", "sum", kind, x, chunk=4321)) == got
+    one = {"bf16": 0x3F80, "f16": 0x3C00}[kind]
+    n = 70_001
+    assert float(oracle.mapreduce("widen_f32", "sum", kind, np.full(n, one, np.uint16))) == float(n)   # n ones
+    assert float(oracle.mapreduce("widen_f32", "sum", kind, x[:0])) == 0.0
+    assert float(oracle.mapreduce("widen_f32", "max", kind, x[:0])) == -np.inf
+    with pytest.raises(KeyError):
+        oracle.mapreduce("identity", "sum", kind, x)
