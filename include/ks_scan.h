@@ -18,7 +18,8 @@
  *     (here 12 and 32) run in the one shape where a lane holds 8 or 9
  *     consecutive 16-byte granules, in both strategies, in ks_scan_strided and in
  *     ks_mapreduce; the shape options "waves" / "form" do not apply to them.
- *     One-byte elements (KS_U8) are reduced only (ks_mapreduce).
+ *     One- and two-byte elements (KS_U8, KS_BF16, KS_F16) are reduced only
+ *     (ks_mapreduce); they may start at any element, whatever its address.
  *   - in == out (exactly in place) is allowed; any other overlap is rejected.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise (except ks_scan_check)
@@ -63,7 +64,9 @@ typedef enum {
     KS_MAT2_U64 = 10,        /* struct { uint64_t m00, m01, m10, m11; } row-major   32 B */
     KS_RANGE_I32_CNT32 = 11, /* struct { int32_t lo, hi; uint32_t cnt; }            12 B */
     KS_U8 = 12,              /* uint8_t; ks_mapreduce only (the scans refuse it)     1 B */
-    KS_DTYPE_COUNT = 13
+    KS_BF16 = 13,            /* bfloat16 as uint16_t bits; ks_mapreduce only         2 B */
+    KS_F16 = 14,             /* IEEE binary16 as uint16_t bits; ks_mapreduce only    2 B */
+    KS_DTYPE_COUNT = 15
 } ks_dtype;
 
 /* Operators; L is the accumulated (earlier) operand, R the later one. */
@@ -100,8 +103,9 @@ typedef enum {
  * Element-wise maps for the map-fused scan and mapreduce (paper Sec. IV-A: the
  * high-level interface scan(f, op, src), mapreduce(f, op, src)).  The map is
  * applied as elements are loaded.  The first four are T -> T: the output has the
- * input's element type.  The last two take KS_U8 and change the type (f: T -> S of
- * Sec. II-C); only ks_mapreduce accepts them, and its result is an S.
+ * input's element type.  The others take KS_U8, KS_BF16 or KS_F16 and change the
+ * type (f: T -> S of Sec. II-C); only ks_mapreduce accepts them, and its result is
+ * an S.
  */
 typedef enum {
     KS_MAP_IDENTITY = 0,
@@ -112,7 +116,8 @@ typedef enum {
                                -1 to +1 (the 8-bit type of the paper's mapreduce benchmark,
                                Sec. VII-B), the float nearest to (2c - 255) / 255           */
     KS_MAP_WIDEN64 = 5,     /* uint8_t -> uint64_t, so that a sum of bytes cannot wrap          */
-    KS_MAP_COUNT = 6
+    KS_MAP_WIDEN_F32 = 6,   /* KS_BF16 / KS_F16 -> the float of the same value (exact)          */
+    KS_MAP_COUNT = 7
 } ks_map;
 
 /*
@@ -166,15 +171,18 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
  *   in    device pointer, n contiguous elements of dtype (may be NULL if n == 0)
  *   out   device pointer to ONE element of the result type, aligned to it, written
  *         by the call; it may lie inside `in`.  The result type is dtype, except
- *         where the map changes it: float for KS_MAP_UNIT_FLOAT8, uint64_t for
- *         KS_MAP_WIDEN64 (ks_mapreduce_result_bytes gives its size)
+ *         where the map changes it: float for KS_MAP_UNIT_FLOAT8 and
+ *         KS_MAP_WIDEN_F32, uint64_t for KS_MAP_WIDEN64 (ks_mapreduce_result_bytes
+ *         gives its size)
  *   map   KS_MAP_IDENTITY or one of the maps; accepted (dtype, map, op) triples are
  *         those for which ks_mapreduce_result_bytes is not 0: every pair of
  *         ks_pair_supported, the triples of ks_map_supported, and the three sums
  *         over bytes (paper Sec. VII-B, Tables I and III):
  *         (KS_U8, KS_MAP_UNIT_FLOAT8, KS_SUM), (KS_U8, KS_MAP_WIDEN64, KS_SUM) and
  *         (KS_U8, KS_MAP_IDENTITY, KS_SUM), the last one modulo 2^8 as the element
- *         type's own addition is.  Others return KS_ERR_UNSUPPORTED.
+ *         type's own addition is; and sum, minimum and maximum of 16-bit floats
+ *         promoted to float, (KS_BF16 or KS_F16, KS_MAP_WIDEN_F32, KS_SUM / KS_MIN /
+ *         KS_MAX), result a float.  Others return KS_ERR_UNSUPPORTED.
  * Float32 sums are accumulated in double and rounded once at the end.  Scratch,
  * stream behaviour (asynchronous; recordable into a graph under ks_scan's
  * conditions) and errors as for ks_scan; a finishing wave that does not see all

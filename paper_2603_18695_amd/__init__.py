@@ -28,11 +28,11 @@ KS_ERR_INVALID_ARG, KS_ERR_UNSUPPORTED, KS_ERR_MISALIGNED, KS_ERR_OVERLAP = -1, 
 KS_ERR_WORKSPACE, KS_ERR_HIP, KS_ERR_TIMEOUT = -5, -6, -7
 
 DTYPES = {"i32": 0, "u32": 1, "i64": 2, "u64": 3, "f32": 4, "f64": 5, "affine_f32": 6,
-          "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9, "mat2_u64": 10, "range_i32_cnt32": 11, "u8": 12}
+          "argmax_i32_cnt64": 7, "mat2_u32": 8, "quat_f32": 9, "mat2_u64": 10, "range_i32_cnt32": 11, "u8": 12, "bf16": 13, "f16": 14}
 OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "mat2_mul": 5, "quat_mul": 6,
        "range_count": 7}
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
-MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5}
+MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5, "widen_f32": 6}
 
 EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_pair", "ks_mapreduce_pair", "ks_pair_elem_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",

@@ -282,7 +282,7 @@ int ks_scan_strided(ks_dtype dtype, ks_op op, int inclusive, const void *in, siz
 static const PairEntry *reduce_entry(int dtype, int map, int op) {
     if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT || map < 0 || map >= KS_MAP_COUNT)
         return nullptr;
-    if (dtype == KS_U8) return pair_entry_bytes(dtype, map, op);
+    if (dtype == KS_U8 || dtype == KS_BF16 || dtype == KS_F16) return pair_entry_bytes(dtype, map, op);
     return map == KS_MAP_IDENTITY ? pair_entry(dtype, op) : pair_entry_mapped(dtype, map, op);
 }
 
@@ -394,6 +394,7 @@ size_t ks_elem_bytes(ks_dtype dtype) {
         case KS_MAT2_U64: return 32;
         case KS_RANGE_I32_CNT32: return 12;
         case KS_U8: return 1;
+        case KS_BF16: case KS_F16: return 2;
         default: return 0;
     }
 }

@@ -277,8 +277,25 @@ struct NonzeroMap {  // 1 where x != 0, else 0: a sum scan of it numbers the kep
     __device__ __forceinline__ T operator()(const T &x) const { return x != T(0) ? T(1) : T(0); }
 };
 
+// 16-bit floats as they lie in memory (reductions only: promoted to float32 as they are loaded).
+struct BF16Bits {   // bfloat16: the upper half of a float32
+    uint16_t bits;
+};
+struct F16Bits {    // IEEE binary16
+    uint16_t bits;
+};
+
 // Maps that change the type, f: T -> S (paper Sec. II-C): `result` is S, the type of what a
 // mapreduce with this map writes.
+struct WidenF32Map {   // the float32 of the same value: exact for both formats
+    using result = float;
+    __device__ __forceinline__ float operator()(BF16Bits x) const {
+        return __builtin_bit_cast(float, (uint32_t)x.bits << 16);
+    }
+    __device__ __forceinline__ float operator()(F16Bits x) const {
+        return (float)__builtin_bit_cast(_Float16, x.bits);
+    }
+};
 struct Widen64Map {   // a byte as an integer that sums of any length cannot wrap
     using result = uint64_t;
     __device__ __forceinline__ uint32_t operator()(uint8_t c) const { return c; }

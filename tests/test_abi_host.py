@@ -54,7 +54,7 @@ def test_binding_enums_match_the_header(ks):
             assert getattr(ks, name) == value, name
     # every element type has a size, and the binding's scratch limit is the header's
     for name in ks.DTYPES:
-        assert ks.ks_elem_bytes(name) in (1, 4, 8, 12, 16, 32), name
+        assert ks.ks_elem_bytes(name) in (1, 2, 4, 8, 12, 16, 32), name
     m = re.search(r"#define\s+KS_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
     assert ks.STATIC_SCRATCH_BYTES == int(m.group(1)) << int(m.group(2))
 
@@ -114,6 +114,14 @@ def test_bytes_are_reduced_and_not_scanned(ks):
     assert ks.ks_mapreduce_result_bytes(dtype="i32", op="sum", map="nonzero") == 4
     assert ks.ks_mapreduce_result_bytes(dtype="mat2_u64", op="mat2_mul") == 32
     assert ks.ks_mapreduce_result_bytes(dtype="range_i32_cnt32", op="range_count") == 12
+    # 16-bit floats: sum, minimum and maximum after promotion to float, nothing else
+    for dt in ("bf16", "f16"):
+        assert ks.ks_elem_bytes(dt) == 2 and not ks.ks_pair_supported(dt, "sum")
+        for op in ("sum", "min", "max"):
+            assert ks.ks_mapreduce_result_bytes(dtype=dt, op=op, map="widen_f32") == 4
+        assert ks.ks_mapreduce_result_bytes(dtype=dt, op="sum") == 0
+        assert ks.ks_mapreduce_result_bytes(dtype=dt, op="sum", map="unit_float8") == 0
+    assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="widen_f32") == 0
     lib = ks.raw_library()
     assert lib.ks_mapreduce_result_bytes(99, 0, 0) == 0 and lib.ks_mapreduce_result_bytes(U8, 99, SUM) == 0
     assert not ks.ks_pair_supported("u8", "sum") and not ks.ks_map_supported("u8", "unit_float8", "sum")

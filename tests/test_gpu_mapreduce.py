@@ -228,6 +228,39 @@ def test_byte_sums_at_the_paper_sizes(ks):
         del d, x
 
 
+# ---- 16-bit floats, reduced after promotion to float32 ----
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+def test_sixteen_bit_floats(ks, kind):
+    run = 64 * 4 * 8                        # elements one wave folds per step
+    sizes = [0, 1, 2, 3, 7, 8, 9, 63, 64, 65, run - 1, run, run + 1, 4 * run + 3, 37 * run + 5, 512 * 4 * run + 1,
+             3 * 512 * 4 * run + 12345, (1 << 27) + 3]
+    x_all = ks_inputs.random_half_bits(kind, sizes[-1] + 8, seed=51)
+    d_all = torch.from_numpy(x_all.view(np.int16)).cuda()
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    for n in sizes:
+        for off in ((0, 1, 2, 3) if n < 100_000 else (0, 1)):     # the input need not start on a dword
+            x = x_all[off:off + n]
+            for op in ("sum", "max", "min"):
+                say(f"[case] mapreduce ({kind},widen_f32,{op}) n={n} +{off}")
+                out.fill_(123.0)
+                ks.ks_mapreduce(d_all[off:off + n], out, dtype=kind, op=op, map="widen_f32")
+                ks.ks_scan_check()
+                got, ref = float(out.cpu()[0]), float(oracle.mapreduce("widen_f32", op, kind, x))
+                if op == "sum":
+                    assert abs(got - ref) <= float_bound(np.array([ref]))[0], (kind, op, n, off, got, ref)
+                else:
+                    assert got == ref, (kind, op, n, off, got, ref)
+    # n ones: exact as long as the count is a float32
+    one = {"bf16": 0x3F80, "f16": 0x3C00}[kind]
+    ones = torch.full((1 << 24,), one, dtype=torch.int16, device="cuda")
+    ks.ks_mapreduce(ones, out, dtype=kind, op="sum", map="widen_f32")
+    ks.ks_scan_check()
+    assert float(out.cpu()[0]) == float(1 << 24)
+    with pytest.raises(ks.KsError) as e:
+        ks.ks_mapreduce(ones, torch.empty(2, dtype=torch.uint8, device="cuda"), dtype=kind, op="sum")
+    assert e.value.status == ks.KS_ERR_UNSUPPORTED      # no reduction in the 16-bit type itself
+
+
 def test_recorded_into_a_graph(ks):
     n = 3_000_001
     xs = [np.random.default_rng(90 + r).integers(-50, 50, size=n).astype(np.int32) for r in range(3)]
