@@ -18,8 +18,16 @@
  *     (here 12 and 32) run in the one shape where a lane holds 8 or 9
  *     consecutive 16-byte granules, in both strategies, in ks_scan_strided and in
  *     ks_mapreduce; the shape options "waves" / "form" do not apply to them.
- *     One- and two-byte elements (KS_U8, KS_BF16, KS_F16) are reduced only
- *     (ks_mapreduce); they may start at any element, whatever its address.
+ *     One-byte elements (KS_U8) are reduced only (ks_mapreduce).
+ *   - 16-bit floats (KS_BF16, KS_F16; KS_SUM, KS_MIN, KS_MAX): every element is
+ *     promoted to float as it is loaded and the arithmetic is float's (sums: as
+ *     for KS_F32); a scan rounds every output to the 16-bit type, to nearest, ties
+ *     to even (sums beyond the type's range become infinities), so running minima
+ *     and maxima are exact and a sum output lies within half a unit in the last
+ *     place of the float result.  For the scans both arrays must start on a 4-byte
+ *     boundary (n may be odd: what lies behind the output is not touched);
+ *     ks_scan_strided does not take them.  ks_mapreduce takes them at any 2-byte
+ *     address, with KS_MAP_WIDEN_F32, and writes a float.
  *   - in == out (exactly in place) is allowed; any other overlap is rejected.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise (except ks_scan_check)
@@ -64,8 +72,8 @@ typedef enum {
     KS_MAT2_U64 = 10,        /* struct { uint64_t m00, m01, m10, m11; } row-major   32 B */
     KS_RANGE_I32_CNT32 = 11, /* struct { int32_t lo, hi; uint32_t cnt; }            12 B */
     KS_U8 = 12,              /* uint8_t; ks_mapreduce only (the scans refuse it)     1 B */
-    KS_BF16 = 13,            /* bfloat16 as uint16_t bits; ks_mapreduce only         2 B */
-    KS_F16 = 14,             /* IEEE binary16 as uint16_t bits; ks_mapreduce only    2 B */
+    KS_BF16 = 13,            /* bfloat16 as uint16_t bits (see "16-bit floats" below)  2 B */
+    KS_F16 = 14,             /* IEEE binary16 as uint16_t bits                        2 B */
     KS_DTYPE_COUNT = 15
 } ks_dtype;
 

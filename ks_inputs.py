@@ -145,12 +145,13 @@ def random_codes(n: int, seed: int, skew: float = 0.0) -> np.ndarray:
     return out
 
 
-def random_half_bits(kind: str, n: int, seed: int) -> np.ndarray:
-    """n finite 16-bit floats as uint16 bit patterns, values in (-1, 1) with a tenth of them up to
-    +-64: kind "bf16" (the upper 16 bits of a float32, truncated) or "f16" (IEEE binary16, rounded)."""
+def random_half_bits(kind: str, n: int, seed: int, spikes: bool = True) -> np.ndarray:
+    """n finite 16-bit floats as uint16 bit patterns, values in (-1, 1), with `spikes` a tenth of them
+    up to +-64: kind "bf16" (the upper 16 bits of a float32, truncated) or "f16" (IEEE binary16, rounded)."""
     rng = np.random.default_rng([seed, 99])
     v = rng.uniform(-1.0, 1.0, size=n).astype(np.float32)
-    v *= np.where(rng.random(n) < 0.1, np.float32(64.0), np.float32(1.0))
+    if spikes:
+        v *= np.where(rng.random(n) < 0.1, np.float32(64.0), np.float32(1.0))
     if kind == "bf16":
         return (v.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
     if kind == "f16":

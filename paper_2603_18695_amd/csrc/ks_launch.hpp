@@ -75,6 +75,9 @@ struct PairDefaults {
     static constexpr bool kSum = std::is_same<typename MapOf<Op>::unmapped, SumOp<T>>::value;
     static constexpr Shape shape() {
         if (!granule_sized<T>()) return Shape{16, blocked_fits<T, 9>() ? 9 : 8, true, kFormBlocked};
+        // 2-byte elements accumulated in 4 bytes: a granule unpacks into eight registers, and 8 rows of
+        // them with the parked next tile are what 128 registers hold
+        if (sizeof(T) == 2) return Shape{16, 8, true, kFormSeparate};
         if (sizeof(A) == 4) return Shape{16, 9, true, kFormSeparate};
         // 8-byte scalars, sums: 8 rows in striped separate loops measure 1 % above 9 rows blocked
         // (uint64 sum 6.32 / 6.26, float64 sum 6.33 / 6.26 TB/s).  Minimum and maximum of 8-byte values
@@ -538,9 +541,10 @@ struct Pair {
     template <int WAVES>
     static constexpr size_t strided_tile() { return (size_t)WAVES * kWave * strided_rows<WAVES>(); }
     // temp_bytes(KS_ALGO_LOOKBACK, n) sizes the descriptors for the smallest contiguous tile
-    static_assert(strided_tile<4>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
-                      strided_tile<8>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
-                      strided_tile<16>() * sizeof(T) >= (size_t)kMinTileGranules * 16,
+    static_assert(sizeof(T) < 4 ||   // 2-byte elements are not scanned through strided views (run_strided)
+                      (strided_tile<4>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
+                       strided_tile<8>() * sizeof(T) >= (size_t)kMinTileGranules * 16 &&
+                       strided_tile<16>() * sizeof(T) >= (size_t)kMinTileGranules * 16),
                   "strided tile below the smallest tile");
     template <int WAVES, bool INCLUSIVE>
     static int launch_lookback_strided(const ScanCall &c) {
@@ -567,6 +571,10 @@ struct Pair {
     // 163, stride 8 287 / 290 / 332, stride 32 1109 / 1121 / 1169; float64 stride 2 (16 bytes) 161 / 152 / 204,
     // stride 4 294 / 295 / 404, stride 8 593 / 637 / 763.
     static int run_strided(const ScanCall &c) {
+        if constexpr (sizeof(T) < 4) return KS_ERR_UNSUPPORTED;   // one-element accesses below a dword: not built
+        else return run_strided_views(c);
+    }
+    static int run_strided_views(const ScanCall &c) {
         const size_t apart = (c.in_stride > c.out_stride ? c.in_stride : c.out_stride) * sizeof(T);
         int waves = apart <= 8 ? 16 : apart <= 16 ? 8 : 4;
         const long long want = options().waves;
@@ -594,8 +602,10 @@ struct Pair {
     }
 
     static const PairEntry *entry() {
-        static const PairEntry e = {kPairAbi, sizeof(T), alignof(T), &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
-                                    &Pair::run_mapreduce, sizeof(T), alignof(T)};
+        // scans of 2-byte elements work on whole dwords: both arrays start on one
+        constexpr size_t align = sizeof(T) < 4 ? 4 : alignof(T);
+        static const PairEntry e = {kPairAbi, sizeof(T), align, &Pair::temp_bytes, &Pair::pick_algo, &Pair::run,
+                                    &Pair::run_mapreduce, sizeof(T), align};
         return &e;
     }
 };

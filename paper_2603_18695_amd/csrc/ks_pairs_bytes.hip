@@ -12,6 +12,21 @@ static const PairEntry *half_entry(int op) {
     return nullptr;
 }
 
+// Scans of 16-bit floats: every element promoted to float32 as it is loaded, accumulated in float32
+// (sums: double above one wave's run), every output rounded to the 16-bit type, ties to even.
+template <class T>
+static const PairEntry *half_scan_entry(int op) {
+    if (op == KS_SUM) return Pair<T, MappedOp<SumOp<float>, WidenF32Map>>::entry();
+    if (op == KS_MIN) return Pair<T, MappedOp<MinOp<float>, WidenF32Map>>::entry();
+    if (op == KS_MAX) return Pair<T, MappedOp<MaxOp<float>, WidenF32Map>>::entry();
+    return nullptr;
+}
+const PairEntry *pair_entry_half(int dtype, int op) {
+    if (dtype == KS_BF16) return half_scan_entry<BF16Bits>(op);
+    if (dtype == KS_F16) return half_scan_entry<F16Bits>(op);
+    return nullptr;
+}
+
 const PairEntry *pair_entry_bytes(int dtype, int map, int op) {
     if (dtype == KS_BF16 && map == KS_MAP_WIDEN_F32) return half_entry<BF16Bits>(op);
     if (dtype == KS_F16 && map == KS_MAP_WIDEN_F32) return half_entry<F16Bits>(op);

@@ -31,12 +31,14 @@ const PairEntry *pair_entry_float(int, int);
 const PairEntry *pair_entry_struct(int, int);
 const PairEntry *pair_entry_mapped(int, int, int);
 const PairEntry *pair_entry_bytes(int, int, int);
+const PairEntry *pair_entry_half(int, int);
 
 const PairEntry *pair_entry(int dtype, int op) {
     if (dtype < 0 || dtype >= KS_DTYPE_COUNT || op < 0 || op >= KS_OP_COUNT) return nullptr;
     if (const PairEntry *e = pair_entry_i32(dtype, op)) return e;
     if (const PairEntry *e = pair_entry_i64(dtype, op)) return e;
     if (const PairEntry *e = pair_entry_float(dtype, op)) return e;
+    if (const PairEntry *e = pair_entry_half(dtype, op)) return e;
     return pair_entry_struct(dtype, op);
 }
 

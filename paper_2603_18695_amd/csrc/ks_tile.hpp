@@ -26,7 +26,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // Element sizes that fit a 16-byte granule a whole number of times run in every arrangement;
 // the others only in the blocked one (BlockedShape, below).
 template <class IO>
-constexpr bool granule_sized() { return sizeof(IO) == 4 || sizeof(IO) == 8 || sizeof(IO) == 16; }
+constexpr bool granule_sized() { return sizeof(IO) == 2 || sizeof(IO) == 4 || sizeof(IO) == 8 || sizeof(IO) == 16; }
 
 template <class IO, int ROWS_>
 struct TileShape {
@@ -72,9 +72,11 @@ __device__ __forceinline__ TileWindow tile_window(const IO *base, size_t n, size
     const size_t left = n > tile_first ? n - tile_first : 0;
     const uint32_t valid = (uint32_t)((left < tile_elems ? left : tile_elems) * sizeof(IO));
     TileWindow w;
-    // Elements narrower than a dword (read only, by the reduction): the range check works on
-    // dwords, so the extent is rounded up to the dword that holds the last element; `base` is
-    // dword-aligned there, the surplus bytes lie in the same dword, and valid_bytes stays exact.
+    // Elements narrower than a dword: the range check works on dwords, so the extent is rounded up
+    // to the dword that holds the last element; `base` is dword-aligned there, the surplus bytes
+    // lie in the same dword, and valid_bytes stays exact.  Loads mask what they read past
+    // valid_bytes; stores write the granule that holds such a dword element by element
+    // (apply_prefix_and_store).
     const uint32_t extent = sizeof(IO) < 4 ? (valid + 3u) & ~3u : valid;
     // raw buffer (stride 0), 32-bit data format, no swizzle: the gfx90a / gfx94x / gfx950 encoding
     w.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<IO *>(base + tile_first), 0, (int)extent, 0x00020000);
@@ -264,11 +266,27 @@ __device__ __forceinline__ void apply_prefix_and_store(const TileWindow &w, int 
                                                        const A &prefix, Op op) {
     constexpr int G = TileShape<IO, ROWS>::G;
     const int at = pinned<PIN>(lane_bytes);
+    // 2-byte elements: an array of odd length ends in the middle of a dword, and the other half of
+    // that dword is not the caller's to write.  Only then (one tile per call at most) the granule
+    // that holds it goes out element by element; a 16-byte store would write the whole dword.
+    const bool ragged_dword = sizeof(IO) < 4 && (w.valid_bytes & 3u) != 0;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         Granule<IO, G> g;
 #pragma unroll
         for (int k = 0; k < G; ++k) g.e[k] = convert<IO>(op(prefix, it.x[j][k]));
+        if constexpr (sizeof(IO) == 2) {
+            const uint32_t first = (uint32_t)(at + j * (kWave * 16));
+            if (ragged_dword && first < w.valid_bytes && first + 16u > (w.valid_bytes & ~3u)) {
+#pragma unroll
+                for (int k = 0; k < G; ++k) {
+                    if (first + (uint32_t)k * 2u < w.valid_bytes)
+                        __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, g.e[k]), w.rsrc,
+                                                              (int)first + k * 2, 0, kNonTemporal);
+                }
+                continue;
+            }
+        }
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, g), w.rsrc, at + j * (kWave * 16), 0,
                                                kNonTemporal);
     }

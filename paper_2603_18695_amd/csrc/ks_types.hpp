@@ -380,6 +380,19 @@ template <>
 struct Convert<float, double> {
     __device__ __forceinline__ static float apply(const double &x) { return (float)x; }
 };
+// float32 -> 16-bit floats: round to nearest, ties to even (what a scan of 16-bit floats stores)
+template <>
+struct Convert<BF16Bits, float> {
+    __device__ __forceinline__ static BF16Bits apply(const float &x) {
+        return BF16Bits{__builtin_bit_cast(uint16_t, (__bf16)x)};   // gfx950 converts in hardware, two per instruction
+    }
+};
+template <>
+struct Convert<F16Bits, float> {
+    __device__ __forceinline__ static F16Bits apply(const float &x) {
+        return F16Bits{__builtin_bit_cast(uint16_t, (_Float16)x)};
+    }
+};
 template <>
 struct Convert<uint32_t, uint8_t> {
     __device__ __forceinline__ static uint32_t apply(const uint8_t &x) { return x; }

@@ -116,12 +116,20 @@ def test_bytes_are_reduced_and_not_scanned(ks):
     assert ks.ks_mapreduce_result_bytes(dtype="range_i32_cnt32", op="range_count") == 12
     # 16-bit floats: sum, minimum and maximum after promotion to float, nothing else
     for dt in ("bf16", "f16"):
-        assert ks.ks_elem_bytes(dt) == 2 and not ks.ks_pair_supported(dt, "sum")
+        assert ks.ks_elem_bytes(dt) == 2
+        assert all(ks.ks_pair_supported(dt, op) for op in ("sum", "min", "max"))      # scanned as well
+        assert not ks.ks_pair_supported(dt, "affine_compose")
         for op in ("sum", "min", "max"):
             assert ks.ks_mapreduce_result_bytes(dtype=dt, op=op, map="widen_f32") == 4
         assert ks.ks_mapreduce_result_bytes(dtype=dt, op="sum") == 0
         assert ks.ks_mapreduce_result_bytes(dtype=dt, op="sum", map="unit_float8") == 0
     assert ks.ks_mapreduce_result_bytes(dtype="u8", op="sum", map="widen_f32") == 0
+    lib16 = ks.raw_library()
+    lib16.ks_scan.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    BF = ks.DTYPES["bf16"]
+    assert lib16.ks_scan(BF, ks.OPS["sum"], 1, 0x10000002, 0x20000000, 16, None) == ks.KS_ERR_MISALIGNED   # scans: dwords
+    assert lib16.ks_scan(BF, ks.OPS["sum"], 1, 0x10000000, 0x20000002, 16, None) == ks.KS_ERR_MISALIGNED
+    assert ks.ks_scan_temp_bytes(dtype="bf16", op="sum", n=10 ** 6) >= 256
     lib = ks.raw_library()
     assert lib.ks_mapreduce_result_bytes(99, 0, 0) == 0 and lib.ks_mapreduce_result_bytes(U8, 99, SUM) == 0
     assert not ks.ks_pair_supported("u8", "sum") and not ks.ks_map_supported("u8", "unit_float8", "sum")
