@@ -53,7 +53,9 @@ def measured_traffic(workload: str, n: int):
 
 # the oracle's names for the workloads' (operator, element type): only the oracle leg uses them
 ORACLE_KIND = {"int32_sum": ("sum", "i32"), "f32_sum": ("sum", "f32"), "u64_exsum": ("sum", "u64"),
-               "affine": ("affine", "f32"), "argmax": ("argmax", None), "f64_sum": ("sum", "f64"), "u8_codes": ("sum", "u64")}
+               "affine": ("affine", "f32"), "argmax": ("argmax", None), "f64_sum": ("sum", "f64"), "u8_codes": ("sum", "u64"),
+               "bf16_sum": ("sum", "f32"), "f16_sum": ("sum", "f32")}
+HALF_KINDS = {"bf16_sum": ("bf16", 7, -126), "f16_sum": ("f16", 10, -14)}    # oracle's name, mantissa bits, lowest exponent
 FLOAT_WORKLOADS = {"f32_sum", "affine", "f64_sum"}
 PREHEAT_S = 0.1
 
@@ -70,6 +72,19 @@ def worst_ratio_or_raise(workload: str, got, ref, what: str) -> float:
     if got.tobytes() != ref.tobytes():
         raise AssertionError(f"{what}: integer results differ from the oracle")
     return 0.0
+
+
+def half_ratio_or_raise(workload: str, got_bits, ref, what: str) -> float:
+    """16-bit float outputs of a sum scan against the oracle's float64 values: within half a unit in the
+    last place of the 16-bit type plus the float bar of the float32 accumulation (the GPU tests' bar)."""
+    import oracle
+    kind, mantissa, low = HALF_KINDS[workload]
+    got = oracle.apply_map("widen_f32", got_bits, kind).astype(np.float64)
+    half_ulp = 0.5 * 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** low))) - mantissa)
+    ratio = float(np.max(np.abs(got - ref) / (half_ulp + np.maximum(1e-4 * np.abs(ref), 1e-3)))) if len(ref) else 0.0
+    if not ratio <= 1.0:
+        raise AssertionError(f"{what}: 16-bit outputs off, worst ratio {ratio:.3g}")
+    return ratio
 
 
 def log(*a):
@@ -122,6 +137,8 @@ def main() -> int:
     if not args.mapreduce and (args.map != "identity" or w.dtype == "u8"):
         log("bench.py: --map and the byte workload go with --mapreduce (the scans take neither)")
         return 2
+    if args.mapreduce and w.dtype in ("bf16", "f16") and args.map == "identity":
+        args.map = "widen_f32"      # the one map under which 16-bit floats are reduced
     if args.mapreduce and not ks.ks_mapreduce_result_bytes(dtype=w.dtype, op=w.op, map=args.map):
         log(f"bench.py: ks_mapreduce does not take ({w.dtype}, {args.map}, {w.op})")
         return 2
@@ -237,7 +254,7 @@ def main() -> int:
             d_out = s_out[::args.stride].contiguous()
         oop, odt = ORACLE_KIND[args.workload]
         if args.mapreduce:    # the fold runs over the mapped elements, in the type the map gives them
-            odt = {"unit_float8": "f32", "widen64": "u64"}.get(args.map, "u64" if w.dtype == "u8" else odt)
+            odt = {"unit_float8": "f32", "widen64": "u64", "widen_f32": "f32"}.get(args.map, "u64" if w.dtype == "u8" else odt)
             if args.map == "square" and odt == "f32":
                 odt = "f64"
         budget_elems = n if w.dtype == "u8" else min(n, 1 << 28)
@@ -247,11 +264,17 @@ def main() -> int:
             if done >= budget_elems:
                 break
             t = time.perf_counter()
-            if args.mapreduce and (args.map != "identity" or w.dtype == "u8"):
+            bits = c
+            if args.workload in HALF_KINDS:      # the 16-bit floats are promoted (exactly) before the fold
+                c = oracle.apply_map("widen_f32", c, HALF_KINDS[args.workload][0])
+            elif args.mapreduce and (args.map != "identity" or w.dtype == "u8"):
                 c = oracle.apply_map("widen64" if (w.dtype, args.map) == ("u8", "identity") else args.map, c)
             ref = stream.feed(c)
             cpu_s += time.perf_counter() - t
-            if not args.mapreduce:
+            if not args.mapreduce and args.workload in HALF_KINDS:
+                got = to_host(d_out[at:at + len(c)], bits.dtype)
+                worst = max(worst, half_ratio_or_raise(args.workload, got, ref, f"bench parity at {at}"))
+            elif not args.mapreduce:
                 got = to_host(d_out[at:at + len(c)], c.dtype)
                 worst = max(worst, worst_ratio_or_raise(args.workload, got, ref, f"bench parity at {at}"))
             at += len(c)
@@ -263,6 +286,8 @@ def main() -> int:
             if w.dtype == "u8":
                 got = d_one.cpu().numpy().view(np.float32 if args.map == "unit_float8" else last.dtype)
                 kind = "f32_sum" if args.map == "unit_float8" else "int32_sum"    # float bar, or bit for bit
+            elif args.workload in HALF_KINDS:
+                got, kind = d_one.cpu().numpy().view(np.float32), "f32_sum"
             else:
                 got = to_host(d_one.view(d_in.dtype).reshape((1,) + tuple(d_in.shape[1:])), host_chunks[0].dtype)
                 kind = args.workload
@@ -332,7 +357,7 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": {"f32_sum": "f32", "int32_sum": "i32", "u64_exsum": "u64", "affine": "f64", "argmax": "i32/i64",
-                  "f64_sum": "f64", "u8_codes": {"unit_float8": "f32", "widen64": "u64"}.get(args.map, "u8")}[args.workload],
+                  "f64_sum": "f64", "bf16_sum": "f32", "f16_sum": "f32", "u8_codes": {"unit_float8": "f32", "widen64": "u64"}.get(args.map, "u8")}[args.workload],
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {'inclusive' if w.inclusive else 'exclusive'} {w.op} scan, {w.dtype}, "
                                f"n={n}, seed {w.seed}", "algo": args.algo, "elem_bytes": eb, "stride": args.stride,

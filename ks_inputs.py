@@ -54,6 +54,9 @@ WORKLOADS = {
     "f64_sum": Workload("f64_sum", "f64", "sum", True, 1 << 27, 5, 8),
     # uint8 codes, uniform over 0 .. 255: the 8-bit types of the paper's mapreduce benchmark (reductions only)
     "u8_codes": Workload("u8_codes", "u8", "sum", True, 10 ** 9, 6, 1),
+    # 16-bit floats as bit patterns, values uniform in (-1, 1): running sums with float32 arithmetic
+    "bf16_sum": Workload("bf16_sum", "bf16", "sum", True, 1 << 29, 7, 2),
+    "f16_sum": Workload("f16_sum", "f16", "sum", True, 1 << 29, 8, 2),
 }
 
 ARGMAX_SWEEP = [1 << k for k in range(10, 31, 2)]   # 2^10 .. 2^30 in powers of 4
@@ -70,6 +73,10 @@ def _draw(name: str, rng: np.random.Generator, start: int, m: int) -> np.ndarray
         return rng.integers(0, 1 << 32, size=m, dtype=np.uint64)
     if name == "u8_codes":
         return rng.integers(0, 256, size=m, dtype=np.uint8)
+    if name == "bf16_sum":      # float32 values cut to their upper 16 bits
+        return (rng.uniform(-1.0, 1.0, size=m).astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    if name == "f16_sum":
+        return rng.uniform(-1.0, 1.0, size=m).astype(np.float16).view(np.uint16)
     if name == "affine":
         out = np.empty((m, 2), dtype=np.float32)
         out[:, 0] = rng.uniform(0.99, 1.01, size=m).astype(np.float32)

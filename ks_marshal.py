@@ -12,7 +12,7 @@ import torch
 
 from ks_inputs import ARGMAX_DTYPE
 
-_SIGNED_VIEW = {np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}
+_SIGNED_VIEW = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}
 
 
 def to_device(x: np.ndarray, device="cuda") -> torch.Tensor:
