@@ -271,6 +271,10 @@ struct Pair {
     static constexpr bool kRtsBlocked = !granule_sized<T>();
     static constexpr int kRtsRows = kRtsBlocked ? PairDefaults<T, Op>::shape().rows : 4;
     static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
+    // Map-fused pairs of 4- and 8-byte elements ride on the shapes tuned for their plain pair, two of
+    // them; the 16-bit floats, whose map is their promotion, are pairs of their own and choose among all
+    // the shapes their defaults can select.
+    static constexpr bool kTwoShapesOnly = MapOf<Op>::mapped && sizeof(T) >= 4;
 
     // elements in `granules` 16-byte granules (callers pass whole tiles, which hold whole elements)
     static size_t granule_elems(size_t granules) { return granules * 16 / sizeof(T); }
@@ -323,7 +327,7 @@ struct Pair {
 
     static Shape lookback_shape(size_t n, int cus) {
         Shape s = PairDefaults<T, Op>::shape_for(n);
-        if (MapOf<Op>::mapped) return s;
+        if (kTwoShapesOnly) return s;
         s = few_rounds_shape(n, cus, s);
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
@@ -472,7 +476,7 @@ struct Pair {
     }
 
     static int run_lookback(const ScanCall &c) {
-        if constexpr (MapOf<Op>::mapped) {
+        if constexpr (kTwoShapesOnly) {
             // mapped pairs are compiled in their element class's two default shapes only
             constexpr Shape d = PairDefaults<T, Op>::shape();
             constexpr Shape sm = PairDefaults<T, Op>::small_shape();
