@@ -149,8 +149,9 @@ int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, 
  *     out[i] = f(in[0]) op f(in[1]) op ... op f(in[i])     (inclusive)
  * with f one of ks_map; arguments, workspace, stream behaviour and errors as for
  * ks_scan.  KS_MAP_IDENTITY is ks_scan.  Instantiated (dtype, map, op) triples:
- * see ks_map_supported; others return KS_ERR_UNSUPPORTED.  Mapped scans run in
- * the element class's default kernel shape (the tuning options do not apply).
+ * see ks_map_supported; others return KS_ERR_UNSUPPORTED.  Mapped scans choose
+ * their kernel shapes as the plain pair does (of the shape options, those within
+ * what the defaults can select apply).
  */
 int ks_scan_map(ks_dtype dtype, ks_map map, ks_op op, int inclusive, const void *in, void *out,
                 size_t n, void *stream);

@@ -73,6 +73,7 @@ template <class T, class Op>
 struct PairDefaults {
     using A = typename Op::acc;
     static constexpr bool kSum = std::is_same<typename MapOf<Op>::unmapped, SumOp<T>>::value;
+    static constexpr bool kSumLike = std::is_same<typename MapOf<Op>::unmapped, SumOp<A>>::value;   // a sum of the accumulator type
     static constexpr Shape shape() {
         if (!granule_sized<T>()) return Shape{16, blocked_fits<T, 9>() ? 9 : 8, true, kFormBlocked};
         // 2-byte elements accumulated in 4 bytes: a granule unpacks into eight registers, and 8 rows of
@@ -271,10 +272,6 @@ struct Pair {
     static constexpr bool kRtsBlocked = !granule_sized<T>();
     static constexpr int kRtsRows = kRtsBlocked ? PairDefaults<T, Op>::shape().rows : 4;
     static constexpr int kMinTileGranules = 4 * kWave * 4;   // smallest compiled look-back tile: 4 waves x 4 rows
-    // Map-fused pairs of 4- and 8-byte elements ride on the shapes tuned for their plain pair, two of
-    // them; the 16-bit floats, whose map is their promotion, are pairs of their own and choose among all
-    // the shapes their defaults can select.
-    static constexpr bool kTwoShapesOnly = MapOf<Op>::mapped && sizeof(T) >= 4;
 
     // elements in `granules` 16-byte granules (callers pass whole tiles, which hold whole elements)
     static size_t granule_elems(size_t granules) { return granules * 16 / sizeof(T); }
@@ -312,8 +309,8 @@ struct Pair {
             consider(Shape{16, 9, true, kFormSeparate});
         if (variant_fits<T, A, 16, 12, true, kFormSeparate>())
             consider(Shape{16, 12, true, kFormSeparate});
-        else if (variant_fits<T, A, 16, 12, false, kFormSeparate>())
-            consider(Shape{16, 12, false, kFormSeparate});
+        else if (variant_fits<T, A, 16, 12, false, kFormSeparate>() && (sizeof(T) > 2 || PairDefaults<T, Op>::kSumLike))
+            consider(Shape{16, 12, false, kFormSeparate});   // (16-bit minimum / maximum: five registers over at 12 rows)
         if (variant_fits<T, A, 16, 16, false, kFormSeparate>() && rounds(16) == 1)
             consider(Shape{16, 16, false, kFormSeparate});
         // less than one round: smaller tiles keep more compute units busy
@@ -327,7 +324,6 @@ struct Pair {
 
     static Shape lookback_shape(size_t n, int cus) {
         Shape s = PairDefaults<T, Op>::shape_for(n);
-        if (kTwoShapesOnly) return s;
         s = few_rounds_shape(n, cus, s);
         const Options &o = options();
         if (o.waves == 4 || o.waves == 8 || o.waves == 16) s.waves = (int)o.waves;
@@ -476,23 +472,12 @@ struct Pair {
     }
 
     static int run_lookback(const ScanCall &c) {
-        if constexpr (kTwoShapesOnly) {
-            // mapped pairs are compiled in their element class's two default shapes only
-            constexpr Shape d = PairDefaults<T, Op>::shape();
-            constexpr Shape sm = PairDefaults<T, Op>::small_shape();
-            if constexpr (sizeof(T) < 16) {
-                if (c.n * sizeof(T) <= PairDefaults<T, Op>::kSmallInputBytes)
-                    return lookback_flags_dispatch<sm.waves, sm.rows, sm.form>(c, sm.prefetch);
-            }
-            return lookback_flags_dispatch<d.waves, d.rows, d.form>(c, d.prefetch);
-        } else {
-            const Shape s = lookback_shape(c.n, c.dev->cus);
-            switch (s.waves) {
-                case 4: return lookback_rows_dispatch<4>(c, s);
-                case 8: return lookback_rows_dispatch<8>(c, s);
-                case 16: return lookback_rows_dispatch<16>(c, s);
-                default: return KS_ERR_INVALID_ARG;
-            }
+        const Shape s = lookback_shape(c.n, c.dev->cus);
+        switch (s.waves) {
+            case 4: return lookback_rows_dispatch<4>(c, s);
+            case 8: return lookback_rows_dispatch<8>(c, s);
+            case 16: return lookback_rows_dispatch<16>(c, s);
+            default: return KS_ERR_INVALID_ARG;
         }
     }
 

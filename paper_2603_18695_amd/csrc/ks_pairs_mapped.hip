@@ -1,5 +1,5 @@
 // (dtype, map, op) instantiations of the map-fused scan, scan(f, op, src) of the
-// paper's Sec. IV-A.  Each one is compiled in its element class's default shape.
+// paper's Sec. IV-A.  Each one is compiled in the shapes its element class's defaults can select.
 #include "ks_launch.hpp"
 
 namespace ks {
