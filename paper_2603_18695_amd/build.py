@@ -12,6 +12,9 @@ LIB = os.path.join(HERE, "libks_scan.so")
 # a pair defined outside the library, as a caller would (examples/user_pair.hip); the GPU tests load it
 USER_SRC = os.path.join(HERE, "examples", "user_pair.hip")
 USER_LIB = os.path.join(HERE, "examples", "libks_user_pair.so")
+# the C ABI from a program without Python (examples/scan_from_c.cpp); a GPU test runs it
+C_EXAMPLE_SRC = os.path.join(HERE, "examples", "scan_from_c.cpp")
+C_EXAMPLE = os.path.join(HERE, "examples", "scan_from_c")
 SOURCES = ["ks_scan.hip", "ks_pairs_i32.hip", "ks_pairs_i64.hip", "ks_pairs_float.hip", "ks_pairs_struct.hip",
            "ks_pairs_mapped.hip", "ks_pairs_bytes.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
@@ -52,8 +55,13 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("building the user-pair example failed:\n" + r.stderr)
+    cmd = [_hipcc(), "-O2", "--offload-arch=gfx950", "-I", os.path.join(os.path.dirname(HERE), "include"), C_EXAMPLE_SRC,
+           "-L", HERE, "-lks_scan", "-Wl,-rpath,$ORIGIN/..", "-o", C_EXAMPLE]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the C example failed:\n" + r.stderr)
     if verbose:
-        print(f"built {LIB} and {USER_LIB}")
+        print(f"built {LIB}, {USER_LIB} and {C_EXAMPLE}")
     return LIB
 
 

@@ -164,3 +164,13 @@ def test_what_is_not_a_pair_is_refused(ks, pairs):
     assert lib.ks_scan_pair(good, 1, None, None, 0, None) == ks.KS_OK
     assert lib.ks_scan_pair(good, 1, 0x10000004, 0x20000000, 16, None) == ks.KS_ERR_MISALIGNED     # int64 fields
     assert lib.ks_scan_pair(good, 1, 0x10000000, 0x10000018, 16, None) == ks.KS_ERR_OVERLAP
+
+
+def test_the_c_abi_from_a_program_without_python(ks):
+    # examples/scan_from_c.cpp: hipMalloc, ks_scan, ks_mapreduce, ks_scan_check, ks_release_scratch, its own check
+    import subprocess
+    exe = os.path.join(os.path.dirname(ks.LIB_PATH), "examples", "scan_from_c")
+    say("[case] examples/scan_from_c 5000003")
+    r = subprocess.run([exe, "5000003"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "match the host" in r.stdout, r.stdout
