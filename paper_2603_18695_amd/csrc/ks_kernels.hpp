@@ -245,12 +245,13 @@ __device__ __forceinline__ int lane_tile_bytes(int dwave) {
 // for anyway, and nobody ever waits for a ticket alone (except for the very first ones, at the
 // start of the kernel).
 //
-// Control block: the first 256 bytes of the scratch.  word 0: tickets drawn; word 1:
-// workgroups that have left.  Both are zero before a launch; the last workgroup to
-// leave puts them back to zero, so a library-owned scratch needs no clearing
-// between calls.
+// Control block: the first 4 KiB of the scratch, in 128-byte lines.  Line 0, word 0:
+// tickets drawn; word 1: workgroups that have left; word 2 and lines 1 .. 16: the
+// reduction's counters (ks_reduce.hpp).  All are zero before a launch; the last
+// workgroup to leave puts them back to zero, so a library-owned scratch needs no
+// clearing between calls.
 // ---------------------------------------------------------------------------
-constexpr size_t kControlBytes = 256;
+constexpr size_t kControlBytes = 4096;
 constexpr uint32_t kNoTile = 0xffffffffu;
 
 // Issue a draw (one lane).

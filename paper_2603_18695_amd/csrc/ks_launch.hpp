@@ -3,7 +3,6 @@
 // the reduce-then-scan recursion.  Instantiated once per pair in ks_pairs_*.hip.
 #pragma once
 
-#include <cmath>
 #include <map>
 #include <type_traits>
 
@@ -211,15 +210,10 @@ struct ReduceLaunch {
         }
         const size_t total_runs = ceil_div(n, kReduceRun);
         size_t grid = (size_t)per_cu * (size_t)c.dev->cus;
-        if (want <= 0) {
-            // Below about 100 MB fewer workgroups are faster: each one costs about 12 ns at the end (its
-            // partial, and its turn at the one counter), and one workgroup streams about 29 GB/s, so
-            // g workgroups take a * g + B / (g * w) and the best g is sqrt(B / (a * w)) = sqrt(B / 350 bytes).
-            // Measured, float32 sum, us per call at grids of 64 / 128 / 256 / 512: 4 MB 4.4 / 4.7 / 6.0 / -,
-            // 10 MB 5.7 / 5.4 / 6.3 / 9.4, 40 MB 23.6 / 13.8 / 10.4 / 11.8, 100 MB 59 / 33 / 20.9 / 19.3.
-            const size_t by_bytes = (size_t)std::sqrt((double)(n * sizeof(T)) / 350.0);
-            if (grid > by_bytes) grid = by_bytes;
-        }
+        // The full grid at every size: with the arrivals counted in two levels (ks_reduce.hpp) a workgroup
+        // costs next to nothing at the end.  float32 sum, us per call from C, 1 / 2 workgroups per compute
+        // unit: 4 MB 4.1 / 4.1, 10 MB 5.2 / 4.8, 20 MB 6.9 / 5.9, 40 MB 10.6 / 8.5, 100 MB 21.3 / 16.6, 400 MB 75 / 58.
+        // (Counted on one word, 512 workgroups cost 5 us at the end, and grids had to shrink with the input.)
         if (grid > ceil_div(total_runs, (size_t)kWaves)) grid = ceil_div(total_runs, (size_t)kWaves);
         if (grid < 1) grid = 1;   // n == 0: one workgroup writes the identity
         if (reduce_scratch_bytes(grid) > c.temp_bytes) return KS_ERR_WORKSPACE;

@@ -14,8 +14,10 @@
 //     are combined in workgroup order the result is the left fold: operators that do not commute
 //     are served too, which the paper's strided accumulation cannot do.  Element sizes that do
 //     not divide a granule (12, 24, 32 bytes) take this path whatever the operator.
-//   - No designated workgroup that spins on flags: the workgroup that arrives LAST (a counter
-//     in the scratch) folds the partials, so nobody waits for a workgroup that has not run.
+//   - No designated workgroup that spins on flags: the workgroup that arrives LAST folds the
+//     partials, so nobody waits for a workgroup that has not run.  Who is last is counted in two
+//     levels, 16 groups of workgroups and the groups: atomics on one address are served one
+//     after the other, about 10 ns each, and 512 workgroups counting on one word cost 5 us.
 //   - Partials travel as tagged 64-bit words (ks_kernels.hpp, descriptors): value and flag in
 //     one relaxed atomic instead of a release store and acquire loads; the finishing wave
 //     polls the tags (bounded) rather than relying on the order of the counter and the data.
@@ -29,7 +31,7 @@ namespace ks {
 struct ReduceArgs {
     size_t n;
     size_t total_runs;
-    uint32_t *control;     // control block of the scratch; word 1 counts the workgroups that have published
+    uint32_t *control;     // control block of the scratch: the counters of arrive_last
     uint64_t *partials;    // gridDim.x entries of tagged words
     uint32_t epoch, spin_limit;
     uint32_t *abort_flag;
@@ -40,6 +42,28 @@ struct ReduceArgs {
 };
 
 constexpr int kFinishWindows = 4;   // windows of 64 partials a finishing wave has in flight at once
+
+// Who arrives last?  Workgroup b counts on the word of group b % kCountGroups (a 128-byte line
+// each: lines 1 .. 16 of the control block); the one that completes its group counts the group
+// on word 2 of line 0, and the one that completes the groups is the last workgroup of the grid.
+// Called by one thread per workgroup, after its partial has been published.
+constexpr uint32_t kCountGroups = 16;
+constexpr uint32_t kLineWords = 32;
+static_assert((1 + kCountGroups) * kLineWords * sizeof(uint32_t) <= kControlBytes, "the counters' lines must fit the control block");
+__device__ __forceinline__ bool arrive_last(uint32_t *control) {
+    const uint32_t g = blockIdx.x % kCountGroups;
+    const uint32_t members = (gridDim.x - g + kCountGroups - 1) / kCountGroups;   // workgroups of this group
+    if (__hip_atomic_fetch_add(&control[kLineWords * (1 + g)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u != members)
+        return false;
+    const uint32_t groups = gridDim.x < kCountGroups ? gridDim.x : kCountGroups;
+    return __hip_atomic_fetch_add(&control[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == groups;
+}
+// The last workgroup leaves the counters at zero for the next call.
+__device__ __forceinline__ void reset_arrivals(uint32_t *control) {
+    __hip_atomic_store(&control[2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t g = 0; g < kCountGroups; ++g)
+        __hip_atomic_store(&control[kLineWords * (1 + g)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // ordered_reduction<IO, Op>(): contiguous ranges and the blocked arrangement instead of strided runs
 template <class IO, class Op>
@@ -148,8 +172,7 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typenam
 #pragma unroll
         for (int k = 1; k < kWaves; ++k) partial = cop(partial, from_words<C>(s_tot[k]));
         desc_publish<C>(a.partials, blockIdx.x, a.epoch, kPartial, partial);
-        const uint32_t before = __hip_atomic_fetch_add(&a.control[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = before + 1u == gridDim.x ? 1u : 0u;
+        s_last = arrive_last(a.control) ? 1u : 0u;
     }
     __syncthreads();
     if (s_last == 0u) return;
@@ -203,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void mapreduce_kernel(const IO *in, typenam
             if constexpr (ResultOf<Op, IO>::from_map) out[0] = convert<R>(total);   // f: T -> S, the result is an S
             else out[0] = convert<IO>(convert<A>(total));
         }
-        __hip_atomic_store(&a.control[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        reset_arrivals(a.control);   // ready for the next call
     }
 }
 
