@@ -3,8 +3,9 @@
 // gfx950 against the headers in ../csrc and linked with libks_scan.so; the entry points below hand the
 // pairs to ks_scan_pair / ks_mapreduce_pair (include/ks_scan.h).
 //
-//   hipcc -O3 -std=c++17 --offload-arch=gfx950 -fPIC -shared -I../csrc user_pair.hip \
-//         -L.. -lks_scan -o libks_user_pair.so
+//   hipcc -O3 -std=c++17 --offload-arch=gfx950 -fno-gpu-rdc -Xclang -target-feature -Xclang -packed-fp32-ops \
+//         -fPIC -shared -I../csrc user_pair.hip -L.. -lks_scan -Wl,-rpath,'$ORIGIN/..' -o libks_user_pair.so
+// (the flags the library itself is built with: build.py)
 #include "ks_launch.hpp"
 
 namespace {
