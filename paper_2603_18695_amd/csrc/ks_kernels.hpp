@@ -246,13 +246,37 @@ __device__ __forceinline__ int lane_tile_bytes(int dwave) {
 // start of the kernel).
 //
 // Control block: the first 4 KiB of the scratch, in 128-byte lines.  Line 0, word 0:
-// tickets drawn; word 1: workgroups that have left; word 2 and lines 1 .. 16: the
-// reduction's counters (ks_reduce.hpp).  All are zero before a launch; the last
-// workgroup to leave puts them back to zero, so a library-owned scratch needs no
-// clearing between calls.
+// tickets drawn; word 2 and lines 1 .. 16: the counters that tell which workgroup is
+// the last one (of a launch by ticket; of a reduction, ks_reduce.hpp).  All are zero
+// before a launch; the last workgroup puts them back to zero, so a library-owned
+// scratch needs no clearing between calls.
 // ---------------------------------------------------------------------------
 constexpr size_t kControlBytes = 4096;
 constexpr uint32_t kNoTile = 0xffffffffu;
+
+// Who arrives last?  Workgroup b counts on the word of group b % kCountGroups (a 128-byte line
+// each: lines 1 .. 16 of the control block); the one that completes its group counts the group
+// on word 2 of line 0, and the one that completes the groups is the last workgroup of the grid.
+// Atomics on ONE word are served one after the other, about 10 ns each: 512 workgroups counting on a
+// single word cost 5 us.  Called by one thread per workgroup, when the workgroup is done.
+constexpr uint32_t kCountGroups = 16;
+constexpr uint32_t kLineWords = 32;
+static_assert((1 + kCountGroups) * kLineWords * sizeof(uint32_t) <= kControlBytes, "the counters' lines must fit the control block");
+__device__ __forceinline__ bool arrive_last(uint32_t *control) {
+    const uint32_t g = blockIdx.x % kCountGroups;
+    const uint32_t members = (gridDim.x - g + kCountGroups - 1) / kCountGroups;   // workgroups of this group
+    if (__hip_atomic_fetch_add(&control[kLineWords * (1 + g)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u != members)
+        return false;
+    const uint32_t groups = gridDim.x < kCountGroups ? gridDim.x : kCountGroups;
+    return __hip_atomic_fetch_add(&control[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == groups;
+}
+// The last workgroup leaves the counters at zero for the next call.
+__device__ __forceinline__ void reset_arrivals(uint32_t *control) {
+    __hip_atomic_store(&control[2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t g = 0; g < kCountGroups; ++g)
+        __hip_atomic_store(&control[kLineWords * (1 + g)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 
 // Issue a draw (one lane).
 __device__ __forceinline__ uint32_t draw_ticket(uint32_t *control) {
@@ -261,10 +285,9 @@ __device__ __forceinline__ uint32_t draw_ticket(uint32_t *control) {
 
 // Called by one lane of every workgroup of a launch by ticket, after its last draw has come back.
 __device__ __forceinline__ void leave_grid(uint32_t *control) {
-    const uint32_t before = __hip_atomic_fetch_add(&control[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (before + 1u == gridDim.x) {
+    if (arrive_last(control)) {
         __hip_atomic_store(&control[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&control[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        reset_arrivals(control);
     }
 }
 

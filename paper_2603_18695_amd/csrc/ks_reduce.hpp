@@ -43,28 +43,6 @@ struct ReduceArgs {
 
 constexpr int kFinishWindows = 4;   // windows of 64 partials a finishing wave has in flight at once
 
-// Who arrives last?  Workgroup b counts on the word of group b % kCountGroups (a 128-byte line
-// each: lines 1 .. 16 of the control block); the one that completes its group counts the group
-// on word 2 of line 0, and the one that completes the groups is the last workgroup of the grid.
-// Called by one thread per workgroup, after its partial has been published.
-constexpr uint32_t kCountGroups = 16;
-constexpr uint32_t kLineWords = 32;
-static_assert((1 + kCountGroups) * kLineWords * sizeof(uint32_t) <= kControlBytes, "the counters' lines must fit the control block");
-__device__ __forceinline__ bool arrive_last(uint32_t *control) {
-    const uint32_t g = blockIdx.x % kCountGroups;
-    const uint32_t members = (gridDim.x - g + kCountGroups - 1) / kCountGroups;   // workgroups of this group
-    if (__hip_atomic_fetch_add(&control[kLineWords * (1 + g)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u != members)
-        return false;
-    const uint32_t groups = gridDim.x < kCountGroups ? gridDim.x : kCountGroups;
-    return __hip_atomic_fetch_add(&control[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == groups;
-}
-// The last workgroup leaves the counters at zero for the next call.
-__device__ __forceinline__ void reset_arrivals(uint32_t *control) {
-    __hip_atomic_store(&control[2], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (uint32_t g = 0; g < kCountGroups; ++g)
-        __hip_atomic_store(&control[kLineWords * (1 + g)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // ordered_reduction<IO, Op>(): contiguous ranges and the blocked arrangement instead of strided runs
 template <class IO, class Op>
 constexpr bool ordered_reduction() { return !Op::commutative || 16 % sizeof(IO) != 0; }
