@@ -145,6 +145,24 @@ int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, 
             void *stream);
 
 /*
+ * Seeded scan: one piece of a longer sequence (paper Sec. II-C with everything
+ * before in[0] already folded into one value):
+ *     out[i] = seed op in[0] op ... op in[i]     (inclusive)
+ *     out[i] = seed op in[0] op ... op in[i-1]   (exclusive; out[0] = seed)
+ * `seed` is a device pointer to ONE element of dtype, read when the call runs on
+ * the stream (it may be the last output of the call before, or lie inside `out`).
+ * This is what scanning an array chunk by chunk, or shard by shard on several
+ * devices, needs: the seed of a piece is the total of the pieces before it.  The
+ * seed is the LEFT operand, so operators that do not commute are served; no map is
+ * applied to it, and float sums carry it in double like every other prefix.
+ * Always the single-pass algorithm with the library-owned scratch; one small
+ * extra kernel stores the seed.  Other arguments, streams, graphs and errors as for
+ * ks_scan; seed == NULL with n > 0 is KS_ERR_INVALID_ARG.
+ */
+int ks_scan_seeded(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n,
+                   const void *seed, void *stream);
+
+/*
  * Map-fused scan (paper Sec. IV-A, scan(f, op, src)):
  *     out[i] = f(in[0]) op f(in[1]) op ... op f(in[i])     (inclusive)
  * with f one of ks_map; arguments, workspace, stream behaviour and errors as for

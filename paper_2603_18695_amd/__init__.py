@@ -34,7 +34,7 @@ OPS = {"sum": 0, "min": 1, "max": 2, "affine_compose": 3, "argmax_count": 4, "ma
 ALGOS = {"auto": 0, "lookback": 1, "reduce_then_scan": 2}
 MAPS = {"identity": 0, "square": 1, "abs": 2, "nonzero": 3, "unit_float8": 4, "widen64": 5, "widen_f32": 6}
 
-EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_pair", "ks_mapreduce_pair", "ks_pair_elem_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
+EXPORTS = ["ks_scan", "ks_scan_seeded", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_bytes", "ks_release_scratch", "ks_scan_pair", "ks_mapreduce_pair", "ks_pair_elem_bytes", "ks_scan_map", "ks_scan_strided", "ks_map_supported", "ks_scan_temp_bytes", "ks_scan_with_temp",
            "ks_scan_check", "ks_pair_supported",
            "ks_elem_bytes", "ks_set_option", "ks_get_option", "ks_copy", "ks_status_string",
            "ks_last_hip_error", "ks_version"]
@@ -42,6 +42,8 @@ EXPORTS = ["ks_scan", "ks_scan_static", "ks_mapreduce", "ks_mapreduce_result_byt
 _vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _lib.ks_scan.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan.restype = _i
+_lib.ks_scan_seeded.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp, _vp]
+_lib.ks_scan_seeded.restype = _i
 _lib.ks_scan_static.argtypes = [_i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.ks_scan_static.restype = _i
 _lib.ks_mapreduce.argtypes = [_i, _i, _i, _vp, _sz, _vp, _vp]
@@ -182,6 +184,21 @@ def ks_mapreduce(inp: torch.Tensor, out: torch.Tensor, *, dtype: str, op: str, m
 def ks_mapreduce_result_bytes(*, dtype: str, op: str, map: str = "identity") -> int:
     """Size of what ks_mapreduce writes for this triple; 0 if it does not accept it."""
     return int(_lib.ks_mapreduce_result_bytes(DTYPES[dtype], MAPS[map], OPS[op]))
+
+
+def ks_scan_seeded(inp: torch.Tensor, out: torch.Tensor, seed: torch.Tensor, *, dtype: str, op: str,
+                   inclusive: bool = True, stream=None) -> torch.Tensor:
+    """out[i] = seed op inp[0] op ... op inp[i]: one piece of a longer sequence; `seed` is a device tensor
+    of one element (for instance a slice of the previous piece's output).  Asynchronous on the stream."""
+    n = _elements(inp, dtype)
+    if _elements(out, dtype) != n:
+        raise ValueError("inp and out differ in size")
+    if not seed.is_cuda or _nbytes(seed) != _ELEM_BYTES[dtype]:
+        raise ValueError("seed must be a device tensor of exactly one element")
+    with _OnDeviceOf(inp):
+        _check(_lib.ks_scan_seeded(DTYPES[dtype], OPS[op], int(bool(inclusive)), inp.data_ptr(), out.data_ptr(), n,
+                                   seed.data_ptr(), _stream_ptr(stream, inp.device.index)), "ks_scan_seeded")
+    return out
 
 
 STATIC_SCRATCH_BYTES = 8 << 20

@@ -55,6 +55,8 @@ struct ScanCall {
     // strided views (paper Sec. IV-C): element i at in[i * in_stride] / out[i * out_stride]; always
     // the look-back algorithm, temp as for it
     size_t in_stride = 1, out_stride = 1;
+    // seeded scan: device pointer to one element that precedes in[0] (look-back algorithm, contiguous arrays)
+    const void *seed = nullptr;
 };
 
 // One entry per instantiated (dtype, op) pair.  Pair<T, Op>::entry() may also be instantiated outside

@@ -300,7 +300,22 @@ struct LookbackArgs {
     uint32_t *abort_flag;    // abort word of the call's stream
     uint32_t call_seq;       // what a wave that gives up writes there; never zero
     uint32_t tickets;        // 0: tiles by index (grid <= tiles), 1: by ticket
+    uint32_t seeded;         // 1: everything before element 0 is the value in line kSeedLine of the control block
 };
+
+// A seeded scan (out[i] = seed op in[0] op ... op in[i]: one piece of a longer sequence, scanned
+// chunk by chunk or shard by shard) differs from a plain one at tile 0 only: what precedes that tile is
+// the seed instead of nothing.  The launch stores the seed in the operator's chain type in line
+// kSeedLine of the control block (seed_store_kernel) before the scan kernel starts.
+constexpr uint32_t kSeedLine = 20;
+template <class C, class COp>
+__device__ __forceinline__ C seed_or_identity(const LookbackArgs &a) {
+    if (!a.seeded) return COp::identity();
+    typename WordsOf<C>::type w;
+#pragma unroll
+    for (int i = 0; i < WordsOf<C>::W; ++i) w.w[i] = a.control[kLineWords * kSeedLine + i];
+    return from_words<C>(w);
+}
 
 // First tile of the calling workgroup (all threads call; kNoTile: nothing left, leave).
 __device__ __forceinline__ uint32_t first_tile(const LookbackArgs &a, uint32_t *s_first) {
@@ -432,8 +447,9 @@ template <class A, class Op>
 __device__ __forceinline__ void publish_aggregate(const LookbackArgs &a, uint32_t tile, const A &aggregate) {
     if ((threadIdx.x & (kWave - 1)) != 0) return;
     if (tile == 0) {
-        desc_publish<A>(a.desc, 0, a.epoch, kPrefix, aggregate);
-        desc_publish<A>(a.xdesc, 0, a.epoch, kPrefix, Op::identity());   // nothing before tile 0
+        const A before = seed_or_identity<A, Op>(a);   // nothing before tile 0, or the seed
+        desc_publish<A>(a.desc, 0, a.epoch, kPrefix, Op()(before, aggregate));
+        desc_publish<A>(a.xdesc, 0, a.epoch, kPrefix, before);
     } else {
         desc_publish<A>(a.desc, tile, a.epoch, kPartial, aggregate);
     }
@@ -451,6 +467,8 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
     if (tile != 0) {
         ok = lookback<A, Op>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
         if (ok && lane == 0) desc_publish<A>(a.desc, tile, a.epoch, kPrefix, op(excl, aggregate));
+    } else {
+        excl = seed_or_identity<A, Op>(a);
     }
     if (lane == 0) {
         x.prefix = to_words(excl);
@@ -683,8 +701,13 @@ __device__ __forceinline__ void common_wave_loop(
 
         // publish as early as possible: successors only need the aggregate
         if (lookback_wave && lane == 0) {
-            desc_publish<C>(a.desc, tile, a.epoch, tile == 0 ? kPrefix : kPartial, aggregate);
-            if (tile == 0) desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, COp::identity());   // nothing before tile 0
+            if (tile == 0) {
+                const C before = seed_or_identity<C, COp>(a);   // nothing before tile 0, or the seed
+                desc_publish<C>(a.desc, 0, a.epoch, kPrefix, cop(before, aggregate));
+                desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, before);
+            } else {
+                desc_publish<C>(a.desc, tile, a.epoch, kPartial, aggregate);
+            }
         }
         const uint32_t next = next_tile_of(a, x.q, tile);
         const bool more = next < a.ntiles;
@@ -701,6 +724,8 @@ __device__ __forceinline__ void common_wave_loop(
             if (tile != 0) {
                 ok = lookback<C, COp>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
                 if (ok && lane == 0) desc_publish<C>(a.desc, tile, a.epoch, kPrefix, cop(excl, aggregate));
+            } else {
+                excl = seed_or_identity<C, COp>(a);
             }
             if (lane == 0) {
                 x.prefix = to_words(excl);
@@ -934,6 +959,21 @@ __global__ __launch_bounds__(WAVES *kWave) void scan_lookback_strided_kernel(con
         if (tile >= a.ntiles) break;
     }
     if (a.tickets && threadIdx.x == kDrawingWave * kWave) leave_grid(a.control);
+}
+
+// The seed of a seeded scan, one element of the caller's in the element type, goes into the control
+// block in the chain type.  A map that changes the type promotes it (16-bit floats); any other map is
+// not applied: the seed is a value already accumulated, not an input element.
+template <class IO, class Op>
+__global__ void seed_store_kernel(const IO *seed, uint32_t *control) {
+    using A = typename Op::acc;
+    using C = typename ChainOf<Op>::type;
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    A v;
+    if constexpr (ResultOf<Op, IO>::from_map) v = convert<A>(typename MapOf<Op>::type()(seed[0]));
+    else v = convert<A>(seed[0]);
+    const typename WordsOf<C>::type w = to_words(convert<C>(v));
+    for (int i = 0; i < WordsOf<C>::W; ++i) control[kLineWords * kSeedLine + i] = w.w[i];
 }
 
 template <int UNUSED = 0>

@@ -400,6 +400,7 @@ struct Pair {
         a.abort_flag = c.abort_flag;
         a.call_seq = c.call_seq;
         a.tickets = tickets;
+        a.seeded = 0;
         return a;
     }
 
@@ -427,7 +428,12 @@ struct Pair {
             l.waves = WAVES;
             l.rows = ROWS;
             l.form = FORM;
-            const LookbackArgs a = lookback_args(c, tiles, tickets);
+            LookbackArgs a = lookback_args(c, tiles, tickets);
+            if (c.seed) {   // after the scratch has been cleared (if it had to be), before the scan starts
+                hipLaunchKernelGGL((seed_store_kernel<T, Op>), dim3(1), dim3(kWave), 0, c.stream,
+                                   static_cast<const T *>(c.seed), a.control);
+                a.seeded = 1;
+            }
             hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, c.stream,
                                static_cast<const T *>(c.in), static_cast<T *>(c.out), a);
             hipError_t e = hipGetLastError();

@@ -165,9 +165,10 @@ int ks_scan_with_temp(ks_dtype dtype, ks_op op, int inclusive, ks_algo algo, con
 // (device, stream).  Strided views always take the look-back algorithm.
 static int scan_with_library_workspace(const PairEntry *e, int inclusive, const void *in, void *out, size_t n,
                                        void *stream, size_t in_stride = 1, size_t out_stride = 1,
-                                       bool reduce = false) {
+                                       bool reduce = false, const void *seed = nullptr) {
     const bool strided = in_stride != 1 || out_stride != 1;
-    const ks_algo algo = strided || reduce ? KS_ALGO_LOOKBACK : e->pick_algo(n);   // both tag their scratch with an epoch
+    // strided views, reductions and seeded scans always take the single-pass route (all tag their scratch with an epoch)
+    const ks_algo algo = strided || reduce || seed ? KS_ALGO_LOOKBACK : e->pick_algo(n);
     // a reduction's scratch (control block and one partial per workgroup) always fits the smallest buffer
     const size_t need = reduce ? 1 : e->temp_bytes(algo, n);
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -223,7 +224,7 @@ static int scan_with_library_workspace(const PairEntry *e, int inclusive, const 
         epoch = ws.epoch;
     }
     ScanCall c{inclusive, algo, in, out, n, ws.ptr, ws.bytes, (hipStream_t)stream, epoch, clear, dev,
-               dev->abort_table + ws.abort_slot, ws.seq, in_stride, out_stride};
+               dev->abort_table + ws.abort_slot, ws.seq, in_stride, out_stride, seed};
     return reduce ? e->mapreduce(c) : e->run(c);
 }
 
@@ -232,6 +233,16 @@ int ks_scan(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, 
     int st = validate(dtype, op, in, out, n, &e);
     if (st != KS_OK || n == 0) return st;
     return scan_with_library_workspace(e, inclusive, in, out, n, stream);
+}
+
+int ks_scan_seeded(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, const void *seed,
+                   void *stream) {
+    const PairEntry *e = nullptr;
+    int st = validate(dtype, op, in, out, n, &e);
+    if (st != KS_OK || n == 0) return st;
+    if (!seed) return KS_ERR_INVALID_ARG;
+    if ((uintptr_t)seed % (e->elem_bytes < 4 ? e->elem_bytes : e->elem_align)) return KS_ERR_MISALIGNED;
+    return scan_with_library_workspace(e, inclusive, in, out, n, stream, 1, 1, false, seed);
 }
 
 int ks_scan_static(ks_dtype dtype, ks_op op, int inclusive, const void *in, void *out, size_t n, void *stream) {
