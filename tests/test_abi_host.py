@@ -173,6 +173,22 @@ def test_pairs_compiled_outside_the_library(ks):
     assert lib.ks_mapreduce_pair(good, 0x10000000, 16, 0x20000004, None) == ks.KS_ERR_MISALIGNED
 
 
+def test_seeded_scan_argument_checks_need_no_gpu(ks):
+    lib = ks.raw_library()
+    I32, SUM = ks.DTYPES["i32"], ks.OPS["sum"]
+    assert lib.ks_scan_seeded(I32, SUM, 1, None, None, 0, None, None) == ks.KS_OK                           # n == 0
+    assert lib.ks_scan_seeded(I32, SUM, 1, 0x10000000, 0x20000000, 16, None, None) == ks.KS_ERR_INVALID_ARG  # no seed
+    assert lib.ks_scan_seeded(I32, SUM, 1, 0x10000000, 0x20000000, 16, 0x30000002, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan_seeded(I32, SUM, 1, 0x10000002, 0x20000000, 16, 0x30000000, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan_seeded(I32, SUM, 1, 0x10000000, 0x10000008, 16, 0x30000000, None) == ks.KS_ERR_OVERLAP
+    assert lib.ks_scan_seeded(ks.DTYPES["u8"], SUM, 1, 0x10000000, 0x20000000, 16, 0x30000000, None) == ks.KS_ERR_UNSUPPORTED
+    assert lib.ks_scan_seeded(99, SUM, 1, 0x10000000, 0x20000000, 16, 0x30000000, None) == ks.KS_ERR_INVALID_ARG
+    # 16-bit floats: the arrays on dwords, the seed at any element
+    BF = ks.DTYPES["bf16"]
+    assert lib.ks_scan_seeded(BF, SUM, 1, 0x10000000, 0x20000000, 16, 0x30000001, None) == ks.KS_ERR_MISALIGNED
+    assert lib.ks_scan_seeded(BF, SUM, 1, 0x10000002, 0x20000000, 16, 0x30000002, None) == ks.KS_ERR_MISALIGNED
+
+
 def test_map_triples(ks):
     for triple in [("f32", "square", "sum"), ("f32", "abs", "sum"), ("f32", "abs", "max"), ("f64", "square", "sum"),
                    ("i32", "nonzero", "sum"), ("i32", "abs", "max"), ("i32", "square", "sum"), ("u64", "nonzero", "sum")]:
