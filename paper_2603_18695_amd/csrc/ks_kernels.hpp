@@ -304,9 +304,10 @@ struct LookbackArgs {
 };
 
 // A seeded scan (out[i] = seed op in[0] op ... op in[i]: one piece of a longer sequence, scanned
-// chunk by chunk or shard by shard) differs from a plain one at tile 0 only: what precedes that tile is
-// the seed instead of nothing.  The launch stores the seed in the operator's chain type in line
-// kSeedLine of the control block (seed_store_kernel) before the scan kernel starts.
+// chunk by chunk or shard by shard).  Descriptors and look-back are those of the plain scan; the
+// look-back wave puts the seed in front of the prefix it hands to its own workgroup's data waves.
+// The launch stores the seed in the operator's chain type in line kSeedLine of the control block
+// (seed_store_kernel) before the scan kernel starts.
 constexpr uint32_t kSeedLine = 20;
 template <class C, class COp>
 __device__ __forceinline__ C seed_or_identity(const LookbackArgs &a) {
@@ -447,9 +448,8 @@ template <class A, class Op>
 __device__ __forceinline__ void publish_aggregate(const LookbackArgs &a, uint32_t tile, const A &aggregate) {
     if ((threadIdx.x & (kWave - 1)) != 0) return;
     if (tile == 0) {
-        const A before = seed_or_identity<A, Op>(a);   // nothing before tile 0, or the seed
-        desc_publish<A>(a.desc, 0, a.epoch, kPrefix, Op()(before, aggregate));
-        desc_publish<A>(a.xdesc, 0, a.epoch, kPrefix, before);
+        desc_publish<A>(a.desc, 0, a.epoch, kPrefix, aggregate);
+        desc_publish<A>(a.xdesc, 0, a.epoch, kPrefix, Op::identity());   // nothing before tile 0
     } else {
         desc_publish<A>(a.desc, tile, a.epoch, kPartial, aggregate);
     }
@@ -467,10 +467,11 @@ __device__ __forceinline__ void resolve_prefix(const LookbackArgs &a, uint32_t t
     if (tile != 0) {
         ok = lookback<A, Op>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
         if (ok && lane == 0) desc_publish<A>(a.desc, tile, a.epoch, kPrefix, op(excl, aggregate));
-    } else {
-        excl = seed_or_identity<A, Op>(a);
     }
     if (lane == 0) {
+        // the descriptors are those of the plain scan; the seed goes in front of what this
+        // workgroup's own waves apply
+        if (a.seeded) excl = op(seed_or_identity<A, Op>(a), excl);
         x.prefix = to_words(excl);
         x.ok = ok ? 1u : 0u;
     }
@@ -701,13 +702,8 @@ __device__ __forceinline__ void common_wave_loop(
 
         // publish as early as possible: successors only need the aggregate
         if (lookback_wave && lane == 0) {
-            if (tile == 0) {
-                const C before = seed_or_identity<C, COp>(a);   // nothing before tile 0, or the seed
-                desc_publish<C>(a.desc, 0, a.epoch, kPrefix, cop(before, aggregate));
-                desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, before);
-            } else {
-                desc_publish<C>(a.desc, tile, a.epoch, kPartial, aggregate);
-            }
+            desc_publish<C>(a.desc, tile, a.epoch, tile == 0 ? kPrefix : kPartial, aggregate);
+            if (tile == 0) desc_publish<C>(a.xdesc, 0, a.epoch, kPrefix, COp::identity());   // nothing before tile 0
         }
         const uint32_t next = next_tile_of(a, x.q, tile);
         const bool more = next < a.ntiles;
@@ -724,10 +720,9 @@ __device__ __forceinline__ void common_wave_loop(
             if (tile != 0) {
                 ok = lookback<C, COp>(a.desc, a.xdesc, m, tile, a.epoch, a.spin_limit, a.abort_flag, a.call_seq, excl);
                 if (ok && lane == 0) desc_publish<C>(a.desc, tile, a.epoch, kPrefix, cop(excl, aggregate));
-            } else {
-                excl = seed_or_identity<C, COp>(a);
             }
             if (lane == 0) {
+                if (a.seeded) excl = cop(seed_or_identity<C, COp>(a), excl);   // see resolve_prefix
                 x.prefix = to_words(excl);
                 x.ok = ok ? 1u : 0u;
             }
